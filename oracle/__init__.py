@@ -1,0 +1,263 @@
+"""CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+numpy-facing wrapper over `nacho_oracle.c` (plain serial C, compiled with gcc).
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package; the HIP library and its Python binding never do, and this package
+imports nothing from them.
+
+Every function cites the passage of the paper it follows in the C source.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nacho_oracle.c")
+_LIB = os.path.join(_HERE, "libnacho_oracle.so")
+
+DENSE, COMPRESSED = 0, 1
+MAXL = 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Level(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("extent", C.c_int64),
+                ("pos", C.c_void_p), ("crd", C.c_void_p)]
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("nlevels", C.c_int32), ("lvl", _Level * MAXL)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ora_total_cost.restype = C.c_int64
+        _lib.ora_spadd_vec.restype = C.c_int64
+        _lib.ora_spadd_csr.restype = C.c_int64
+    return _lib
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a
+
+
+class Tensor:
+    """Sparse operand as a list of levels: ("dense", N) or ("compressed", N, pos, crd)."""
+
+    def __init__(self, levels):
+        self.levels = []
+        self._keep = []
+        t = _Tensor()
+        t.nlevels = len(levels)
+        for m, l in enumerate(levels):
+            if l[0] == "dense":
+                t.lvl[m].kind, t.lvl[m].extent = DENSE, int(l[1])
+                t.lvl[m].pos = None
+                t.lvl[m].crd = None
+            else:
+                pos, crd = _i32(l[2]), _i32(l[3])
+                self._keep += [pos, crd]
+                t.lvl[m].kind, t.lvl[m].extent = COMPRESSED, int(l[1])
+                t.lvl[m].pos = pos.ctypes.data
+                t.lvl[m].crd = crd.ctypes.data
+        self.c = t
+        self.nlevels = len(levels)
+
+
+def vector(idx, extent):
+    idx = _i32(idx)
+    return Tensor([("compressed", extent, np.array([0, idx.shape[0]], dtype=np.int32), idx)])
+
+
+def csr(pos, crd, n_rows, n_cols):
+    return Tensor([("dense", n_rows), ("compressed", n_cols, pos, crd)])
+
+
+def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols):
+    return Tensor([("compressed", n_rows, pos0, crd0), ("compressed", n_cols, pos1, crd1)])
+
+
+def _pack(ops):
+    arr = (_Tensor * len(ops))()
+    for t, o in enumerate(ops):
+        arr[t] = o.c
+    return arr
+
+
+def total_cost(ops, tail_extent=0) -> int:
+    return int(lib().ora_total_cost(_pack(ops), len(ops), C.c_int64(tail_extent)))
+
+
+def find_partition(ops, Q, tail_extent=0):
+    """Algorithm 1 for one query.  Returns (coord[dc], posn[k, d], cost)."""
+    k, d = len(ops), ops[0].nlevels
+    dc = d + (1 if tail_extent > 0 else 0)
+    coord = np.zeros(dc, dtype=np.int64)
+    posn = np.zeros((k, d), dtype=np.int64)
+    cost = C.c_int64(0)
+    rc = lib().ora_find_partition(_pack(ops), k, d, C.c_int64(tail_extent), C.c_int64(int(Q)),
+                                  coord.ctypes.data_as(C.c_void_p), posn.ctypes.data_as(C.c_void_p),
+                                  C.byref(cost))
+    if rc:
+        raise ValueError("ora_find_partition rejected its arguments")
+    return coord, posn, int(cost.value)
+
+
+def partition(ops, P, queries=None, tail_extent=0):
+    """All P+1 boundaries.  Returns dict(coord[P+1, dc], posn[P+1, k, d], cost[P+1])."""
+    k, d = len(ops), ops[0].nlevels
+    dc = d + (1 if tail_extent > 0 else 0)
+    coord = np.zeros((P + 1, dc), dtype=np.int64)
+    posn = np.zeros((P + 1, k, d), dtype=np.int64)
+    cost = np.zeros(P + 1, dtype=np.int64)
+    qp = None
+    if queries is not None:
+        queries = np.ascontiguousarray(queries, dtype=np.int64)
+        assert queries.shape[0] == P + 1
+        qp = queries.ctypes.data_as(C.c_void_p)
+    rc = lib().ora_partition(_pack(ops), k, d, C.c_int64(tail_extent), C.c_int64(P), qp,
+                             coord.ctypes.data_as(C.c_void_p), posn.ctypes.data_as(C.c_void_p),
+                             cost.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("ora_partition rejected its arguments")
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
+def spmv(pos, crd, val, x):
+    """Returns (y, s) as float64: y = A x, s_i = sum_j |A_ij x_j|."""
+    pos, crd = _i32(pos), _i32(crd)
+    n = pos.shape[0] - 1
+    y = np.empty(n, dtype=np.float64)
+    s = np.empty(n, dtype=np.float64)
+    if val.dtype == np.float64:
+        val, x = np.ascontiguousarray(val), np.ascontiguousarray(x, dtype=np.float64)
+        fn = lib().ora_spmv_f64
+    else:
+        val, x = np.ascontiguousarray(val, dtype=np.float32), np.ascontiguousarray(x, dtype=np.float32)
+        fn = lib().ora_spmv_f32
+    fn(C.c_int64(n), pos.ctypes.data_as(C.c_void_p), crd.ctypes.data_as(C.c_void_p),
+       val.ctypes.data_as(C.c_void_p), x.ctypes.data_as(C.c_void_p),
+       y.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p))
+    return y, s
+
+
+def spmm(pos, crd, val, B):
+    """Returns (C, S) as float64 [n_rows, n]."""
+    pos, crd = _i32(pos), _i32(crd)
+    n_rows = pos.shape[0] - 1
+    B = np.ascontiguousarray(B)
+    n = B.shape[1]
+    out = np.empty((n_rows, n), dtype=np.float64)
+    sab = np.empty((n_rows, n), dtype=np.float64)
+    if val.dtype == np.float64:
+        val, B = np.ascontiguousarray(val), B.astype(np.float64, copy=False)
+        fn = lib().ora_spmm_f64
+    else:
+        val, B = np.ascontiguousarray(val, dtype=np.float32), B.astype(np.float32, copy=False)
+        fn = lib().ora_spmm_f32
+    fn(C.c_int64(n_rows), pos.ctypes.data_as(C.c_void_p), crd.ctypes.data_as(C.c_void_p),
+       val.ctypes.data_as(C.c_void_p), B.ctypes.data_as(C.c_void_p), C.c_int64(n), C.c_int64(n),
+       out.ctypes.data_as(C.c_void_p), sab.ctypes.data_as(C.c_void_p))
+    return out, sab
+
+
+def _ptr_array(arrs):
+    a = (C.c_void_p * len(arrs))()
+    for t, x in enumerate(arrs):
+        a[t] = x.ctypes.data
+    return a
+
+
+def _vals(vals):
+    is64 = vals[0].dtype == np.float64
+    dt = np.float64 if is64 else np.float32
+    return [np.ascontiguousarray(v, dtype=dt) for v in vals], int(is64)
+
+
+def spadd_vec(idxs, vals):
+    """Union add of k sparse vectors.  Returns (idx int32, val f64, abs f64)."""
+    k = len(idxs)
+    idxs = [_i32(i) for i in idxs]
+    vals, is64 = _vals(vals)
+    nnz = np.array([i.shape[0] for i in idxs], dtype=np.int64)
+    cap = int(nnz.sum())
+    oi = np.empty(cap, dtype=np.int32)
+    ov = np.empty(cap, dtype=np.float64)
+    oa = np.empty(cap, dtype=np.float64)
+    n = lib().ora_spadd_vec(k, _ptr_array(idxs), _ptr_array(vals), nnz.ctypes.data_as(C.c_void_p),
+                            is64, oi.ctypes.data_as(C.c_void_p), ov.ctypes.data_as(C.c_void_p),
+                            oa.ctypes.data_as(C.c_void_p))
+    if n < 0:
+        raise ValueError("ora_spadd_vec rejected its arguments")
+    return oi[:n].copy(), ov[:n].copy(), oa[:n].copy()
+
+
+def spadd_dcsr(mats):
+    """Union add of k DCSR matrices given as dicts(pos0, crd0, pos1, crd1, val).
+    Returns dict(pos0, crd0, pos1, crd1 int32; val, abs float64)."""
+    k = len(mats)
+    p0 = [_i32(m["pos0"]) for m in mats]
+    c0 = [_i32(m["crd0"]) for m in mats]
+    p1 = [_i32(m["pos1"]) for m in mats]
+    c1 = [_i32(m["crd1"]) for m in mats]
+    vals, is64 = _vals([m["val"] for m in mats])
+    cap_r = sum(c.shape[0] for c in c0)
+    cap_n = sum(c.shape[0] for c in c1)
+    o_p0 = np.zeros(2, dtype=np.int32)
+    o_c0 = np.empty(cap_r, dtype=np.int32)
+    o_p1 = np.empty(cap_r + 1, dtype=np.int32)
+    o_c1 = np.empty(cap_n, dtype=np.int32)
+    o_v = np.empty(cap_n, dtype=np.float64)
+    o_a = np.empty(cap_n, dtype=np.float64)
+    counts = np.zeros(2, dtype=np.int64)
+    rc = lib().ora_spadd_dcsr(k, _ptr_array(p0), _ptr_array(c0), _ptr_array(p1), _ptr_array(c1),
+                              _ptr_array(vals), is64,
+                              o_p0.ctypes.data_as(C.c_void_p), o_c0.ctypes.data_as(C.c_void_p),
+                              o_p1.ctypes.data_as(C.c_void_p), o_c1.ctypes.data_as(C.c_void_p),
+                              o_v.ctypes.data_as(C.c_void_p), o_a.ctypes.data_as(C.c_void_p),
+                              counts.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("ora_spadd_dcsr rejected its arguments")
+    nr, nz = int(counts[0]), int(counts[1])
+    return {"pos0": o_p0, "crd0": o_c0[:nr].copy(), "pos1": o_p1[:nr + 1].copy(),
+            "crd1": o_c1[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}
+
+
+def spadd_csr(mats):
+    """Union add of k CSR matrices given as dicts(pos, crd, val).
+    Returns dict(pos, crd int32; val, abs float64)."""
+    k = len(mats)
+    pos = [_i32(m["pos"]) for m in mats]
+    crd = [_i32(m["crd"]) for m in mats]
+    vals, is64 = _vals([m["val"] for m in mats])
+    n_rows = pos[0].shape[0] - 1
+    cap = sum(c.shape[0] for c in crd)
+    o_pos = np.empty(n_rows + 1, dtype=np.int32)
+    o_crd = np.empty(cap, dtype=np.int32)
+    o_v = np.empty(cap, dtype=np.float64)
+    o_a = np.empty(cap, dtype=np.float64)
+    nz = lib().ora_spadd_csr(k, C.c_int64(n_rows), _ptr_array(pos), _ptr_array(crd), _ptr_array(vals),
+                             is64, o_pos.ctypes.data_as(C.c_void_p), o_crd.ctypes.data_as(C.c_void_p),
+                             o_v.ctypes.data_as(C.c_void_p), o_a.ctypes.data_as(C.c_void_p))
+    if nz < 0:
+        raise ValueError("ora_spadd_csr rejected its arguments")
+    return {"pos": o_pos, "crd": o_crd[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}

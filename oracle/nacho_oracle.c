@@ -1,0 +1,444 @@
+/*
+ * CPU oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, serial, obviously-correct implementation of what the hot path
+ * computes, written from the paper.  It shares no code with the HIP library
+ * and is never called by it; only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may load this file's shared object.
+ *
+ * Two kinds of result live here.
+ *
+ *  (1) Partition boundaries follow the paper's hierarchical search
+ *      (Section 3.2, Algorithm 1 "FindPartition") step by step, with the
+ *      concrete cost of Section 4.2.2 (the number of stored non-zeros of every
+ *      coiterated operand inside the queried sub-space, scaled by the extent
+ *      of a broadcast dimension) evaluated on level formats Dense and
+ *      Compressed (Section 4.2.1).  No blocking, no range tracking, no
+ *      k-ary probing: one binary search per level, one lower-bound search per
+ *      operand per probe.
+ *
+ *  (2) Values and output indices are the plain definitions:
+ *        SpMV   y_i  = sum_j A_ij x_j
+ *        SpMM   C_ik = sum_j A_ij B_jk
+ *        union add: the sorted union of the operands' stored coordinates, each
+ *        with the sum (in operand order) of the operands that store it; this
+ *        is the k-finger coiteration of Section 2.1 with "any operand matches"
+ *        in place of "all operands match" (Section 2.2 gives the two-level
+ *        loop nest for DCSR).
+ *
+ * Precision: products and sums are accumulated wider than the GPU's working
+ * type (long double for the fp64 kernels, double for the fp32 kernels) and the
+ * sum of absolute terms is returned beside every value so that a test can use
+ * the tolerance  |got - ref| <= tol * max(|ref|, sum|terms|).
+ *
+ * Readings of points the paper leaves open (each is listed in the design doc):
+ *   - search domain of a level is [0, N_m] (the 3-vector listing of Section
+ *     4.2.3 searches (0, N]); for an interior query the result is < N_m;
+ *   - the first boundary is the origin and the last is the end of the space,
+ *     by definition (the worked example of Section 2.1 draws [0,2) first);
+ *   - on a flat stretch of the cost function the HIGHEST coordinate is taken
+ *     (Algorithm 1 and the listing agree; it is then a stored coordinate);
+ *   - query p of P is floor(p * Q_total / P);
+ *   - lower-bound windows are half-open and return the window end when no
+ *     entry qualifies;
+ *   - a dense operand that is only located into (x of SpMV, B of SpMM) adds
+ *     no cost; SpMM uses loop order i -> j -> k with the dense k innermost.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+#define ORA_DENSE 0
+#define ORA_COMPRESSED 1
+#define ORA_MAXL 3
+#define ORA_MAXK 16
+
+typedef struct {
+    int32_t kind;         /* ORA_DENSE / ORA_COMPRESSED                      */
+    int64_t extent;       /* N_m                                             */
+    const int32_t *pos;   /* compressed: segment bounds, one per parent + 1  */
+    const int32_t *crd;   /* compressed: coordinates                         */
+} ora_level;
+
+typedef struct {
+    int32_t nlevels;
+    ora_level lvl[ORA_MAXL];
+} ora_tensor;
+
+/* ---- coordinate-tree navigation ---------------------------------------- */
+
+/* First position at level m+1 among the children of level-m position p
+ * (also valid for p == one-past-the-last position). */
+static int64_t child_begin(const ora_tensor *T, int m, int64_t p)
+{
+    const ora_level *c = &T->lvl[m + 1];
+    return c->kind == ORA_COMPRESSED ? (int64_t)c->pos[p] : p * c->extent;
+}
+
+/* Number of innermost (leaf) positions that precede every leaf below level-m
+ * position p, i.e. the leaf position where p's sub-tree starts. */
+static int64_t leaf_begin(const ora_tensor *T, int m, int64_t p)
+{
+    for (; m + 1 < T->nlevels; ++m) p = child_begin(T, m, p);
+    return p;
+}
+
+static void root_segment(const ora_tensor *T, int64_t *lo, int64_t *hi)
+{
+    const ora_level *l = &T->lvl[0];
+    if (l->kind == ORA_COMPRESSED) { *lo = l->pos[0]; *hi = l->pos[1]; }
+    else { *lo = 0; *hi = l->extent; }
+}
+
+/* Least position q in [lo, hi) whose coordinate is >= x; hi if none. */
+static int64_t lower_bound(const int32_t *crd, int64_t lo, int64_t hi, int64_t x)
+{
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)crd[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+/* Position, inside the level-m segment [lo, hi) of T, of the first entry whose
+ * coordinate is >= x (Dense: lo + x). */
+static int64_t locate(const ora_tensor *T, int m, int64_t lo, int64_t hi, int64_t x)
+{
+    const ora_level *l = &T->lvl[m];
+    if (l->kind == ORA_COMPRESSED) return lower_bound(l->crd, lo, hi, x);
+    (void)hi;
+    return lo + x;
+}
+
+/* C_m(x | prefix) restricted to one operand: the number of its stored
+ * non-zeros whose first m coordinates equal the prefix (that is the segment
+ * [lo,hi) of level m) and whose level-m coordinate is < x  (Section 3.1 with
+ * the cost of Section 4.2.2). */
+static int64_t level_cost(const ora_tensor *T, int m, int64_t lo, int64_t hi, int64_t x)
+{
+    int64_t p = locate(T, m, lo, hi, x);
+    return leaf_begin(T, m, p) - leaf_begin(T, m, lo);
+}
+
+int64_t ora_total_cost(const ora_tensor *ops, int k, int64_t tail_extent)
+{
+    int64_t w = tail_extent > 0 ? tail_extent : 1, q = 0;
+    for (int t = 0; t < k; ++t) {
+        int64_t lo, hi;
+        root_segment(&ops[t], &lo, &hi);
+        q += w * (leaf_begin(&ops[t], 0, hi) - leaf_begin(&ops[t], 0, lo));
+    }
+    return q;
+}
+
+/*
+ * Algorithm 1, FindPartition(L, C, Q, N).
+ *   ops[k]       coiterated operands, all with d levels over the same extents
+ *   tail_extent  > 0: one more, dense, innermost loop of that extent below the
+ *                d sparse levels, over which every operand is broadcast
+ *                (SpMM's k loop); every stored non-zero then costs tail_extent
+ *   Q            queried cost
+ * Outputs: coord[d (+1 with a tail)], posn[k*d] (per operand t and level m, the
+ * position of the first level-m entry that is not before the boundary),
+ * *cost = C(x) = Q - final residual.
+ */
+int ora_find_partition(const ora_tensor *ops, int k, int d, int64_t tail_extent,
+                       int64_t Q, int64_t *coord, int64_t *posn, int64_t *cost)
+{
+    if (k < 1 || k > ORA_MAXK || d < 1 || d > ORA_MAXL) return -1;
+    int64_t w = tail_extent > 0 ? tail_extent : 1;
+    int64_t lo[ORA_MAXK], hi[ORA_MAXK];
+    int present[ORA_MAXK];
+    int64_t R = Q;
+    for (int t = 0; t < k; ++t) {
+        if (ops[t].nlevels != d) return -1;
+        root_segment(&ops[t], &lo[t], &hi[t]);
+    }
+    for (int m = 0; m < d; ++m) {
+        int64_t N = ops[0].lvl[m].extent;
+        /* HighestCoordinateLeqQuery: the largest x in [0, N] with C_m(x|.) <= R */
+        int64_t low = 0, high = N;
+        while (low < high) {
+            int64_t x = low + (high - low + 1) / 2;
+            int64_t c = 0;
+            for (int t = 0; t < k; ++t) c += w * level_cost(&ops[t], m, lo[t], hi[t], x);
+            if (c <= R) low = x; else high = x - 1;
+        }
+        int64_t xm = low, c = 0;
+        for (int t = 0; t < k; ++t) c += w * level_cost(&ops[t], m, lo[t], hi[t], xm);
+        R -= c;                                   /* residual inside the sub-space */
+        coord[m] = xm;                            /* x <- x :: x_m                 */
+        for (int t = 0; t < k; ++t) {
+            const ora_tensor *T = &ops[t];
+            int64_t p = locate(T, m, lo[t], hi[t], xm);
+            posn[(size_t)t * d + m] = p;
+            if (T->lvl[m].kind == ORA_COMPRESSED)
+                present[t] = (p < hi[t] && (int64_t)T->lvl[m].crd[p] == xm);
+            else
+                present[t] = (xm < N);
+            if (m + 1 < d) {                      /* descend into x_m's children   */
+                lo[t] = child_begin(T, m, p);
+                hi[t] = present[t] ? child_begin(T, m, p + 1) : lo[t];
+            }
+        }
+    }
+    if (tail_extent > 0) {
+        /* innermost dense loop: C_k(x | prefix) = x per operand storing prefix */
+        int64_t np = 0;
+        for (int t = 0; t < k; ++t) np += present[t];
+        int64_t low = 0, high = tail_extent;
+        while (low < high) {
+            int64_t x = low + (high - low + 1) / 2;
+            if (np * x <= R) low = x; else high = x - 1;
+        }
+        R -= np * low;
+        coord[d] = low;
+    }
+    *cost = Q - R;
+    return 0;
+}
+
+/* floor(p * total / P) without overflow. */
+static int64_t equal_query(int64_t p, int64_t total, int64_t P)
+{
+    return (int64_t)(((__int128)p * (__int128)total) / (__int128)P);
+}
+
+/*
+ * All P+1 boundaries of a P-way partition (Section 3.2: processor p searches
+ * for p*Q/P and (p+1)*Q/P).  Boundary 0 is the origin and boundary P the end
+ * of the iteration space by definition; interior boundaries come from
+ * FindPartition, except that a query >= the total cost also yields the end.
+ *   queries   NULL for equally spaced queries, else P+1 values (first and last
+ *             are ignored)
+ *   coord     [(P+1) * dc]  with dc = d + (tail_extent > 0)
+ *   posn      [(P+1) * k * d]
+ *   cost      [P+1]
+ */
+int ora_partition(const ora_tensor *ops, int k, int d, int64_t tail_extent, int64_t P,
+                  const int64_t *queries, int64_t *coord, int64_t *posn, int64_t *cost)
+{
+    if (P < 1 || k < 1 || k > ORA_MAXK || d < 1 || d > ORA_MAXL) return -1;
+    int dc = d + (tail_extent > 0 ? 1 : 0);
+    int64_t total = ora_total_cost(ops, k, tail_extent);
+    for (int64_t p = 0; p <= P; ++p) {
+        int64_t *c = coord + (size_t)p * dc;
+        int64_t *q = posn + (size_t)p * k * d;
+        int64_t Q = queries ? queries[p] : equal_query(p, total, P);
+        if (p == 0 || p == P || Q >= total) {
+            int end = (p != 0);
+            for (int m = 0; m < dc; ++m) c[m] = 0;
+            if (end) c[0] = ops[0].lvl[0].extent;
+            for (int t = 0; t < k; ++t) {
+                int64_t lo, hi;
+                root_segment(&ops[t], &lo, &hi);
+                int64_t at = end ? hi : lo;
+                for (int m = 0; m < d; ++m) {
+                    q[(size_t)t * d + m] = at;
+                    if (m + 1 < d) at = child_begin(&ops[t], m, at);
+                }
+            }
+            cost[p] = end ? total : 0;
+        } else {
+            int rc = ora_find_partition(ops, k, d, tail_extent, Q, c, q, &cost[p]);
+            if (rc) return rc;
+        }
+    }
+    return 0;
+}
+
+/* ---- plain definitions of the balanced kernels -------------------------- */
+
+/* y_i = sum_j A_ij x_j, CSR, fp64 inputs, long double accumulation.
+ * s_i = sum_j |A_ij x_j| (for the tolerance rule). */
+void ora_spmv_f64(int64_t n_rows, const int32_t *pos, const int32_t *crd, const double *val,
+                  const double *x, double *y, double *s)
+{
+    for (int64_t i = 0; i < n_rows; ++i) {
+        long double acc = 0.0L, sabs = 0.0L;
+        for (int64_t q = pos[i]; q < pos[i + 1]; ++q) {
+            long double term = (long double)val[q] * (long double)x[crd[q]];
+            acc += term;
+            sabs += fabsl(term);
+        }
+        y[i] = (double)acc;
+        if (s) s[i] = (double)sabs;
+    }
+}
+
+/* Same for fp32 inputs, double accumulation, double outputs. */
+void ora_spmv_f32(int64_t n_rows, const int32_t *pos, const int32_t *crd, const float *val,
+                  const float *x, double *y, double *s)
+{
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double acc = 0.0, sabs = 0.0;
+        for (int64_t q = pos[i]; q < pos[i + 1]; ++q) {
+            double term = (double)val[q] * (double)x[crd[q]];
+            acc += term;
+            sabs += fabs(term);
+        }
+        y[i] = acc;
+        if (s) s[i] = sabs;
+    }
+}
+
+/* C_ik = sum_j A_ij B_jk; A CSR fp32, B dense row-major [*, n] with leading
+ * dimension ldb, C and S (sum of |terms|) dense double [n_rows, n]. */
+void ora_spmm_f32(int64_t n_rows, const int32_t *pos, const int32_t *crd, const float *val,
+                  const float *B, int64_t n, int64_t ldb, double *C, double *S)
+{
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double *c = C + (size_t)i * n;
+        double *s = S ? S + (size_t)i * n : NULL;
+        for (int64_t kk = 0; kk < n; ++kk) { c[kk] = 0.0; if (s) s[kk] = 0.0; }
+        for (int64_t q = pos[i]; q < pos[i + 1]; ++q) {
+            const float *b = B + (size_t)crd[q] * ldb;
+            double a = (double)val[q];
+            for (int64_t kk = 0; kk < n; ++kk) {
+                double term = a * (double)b[kk];
+                c[kk] += term;
+                if (s) s[kk] += fabs(term);
+            }
+        }
+    }
+}
+
+void ora_spmm_f64(int64_t n_rows, const int32_t *pos, const int32_t *crd, const double *val,
+                  const double *B, int64_t n, int64_t ldb, double *C, double *S)
+{
+    for (int64_t i = 0; i < n_rows; ++i) {
+        for (int64_t kk = 0; kk < n; ++kk) {
+            long double acc = 0.0L, sabs = 0.0L;
+            for (int64_t q = pos[i]; q < pos[i + 1]; ++q) {
+                long double term = (long double)val[q] * (long double)B[(size_t)crd[q] * ldb + kk];
+                acc += term;
+                sabs += fabsl(term);
+            }
+            C[(size_t)i * n + kk] = (double)acc;
+            if (S) S[(size_t)i * n + kk] = (double)sabs;
+        }
+    }
+}
+
+static double load_value(const void *val, int is_f64, int64_t q)
+{
+    return is_f64 ? ((const double *)val)[q] : (double)((const float *)val)[q];
+}
+
+/*
+ * k-finger union merge of the segments [p[t], e[t]) of k sorted coordinate
+ * lists (the coiteration loop of Section 2.1 with "any" for "all").  Appends to
+ * out_crd/out_val/out_abs at *n_out.  Values are added in operand order.
+ */
+static void union_merge(int k, const int32_t *const *crd, const void *const *val, int is_f64,
+                        int64_t *p, const int64_t *e,
+                        int32_t *out_crd, double *out_val, double *out_abs, int64_t *n_out)
+{
+    for (;;) {
+        int any = 0;
+        int64_t i = 0;
+        for (int t = 0; t < k; ++t)
+            if (p[t] < e[t]) {
+                int64_t it = crd[t][p[t]];
+                if (!any || it < i) i = it;
+                any = 1;
+            }
+        if (!any) break;
+        double sum = 0.0, sabs = 0.0;
+        for (int t = 0; t < k; ++t)
+            if (p[t] < e[t] && (int64_t)crd[t][p[t]] == i) {
+                double v = load_value(val[t], is_f64, p[t]);
+                sum += v;
+                sabs += fabs(v);
+                ++p[t];
+            }
+        out_crd[*n_out] = (int32_t)i;
+        out_val[*n_out] = sum;
+        if (out_abs) out_abs[*n_out] = sabs;
+        ++*n_out;
+    }
+}
+
+/* z = sum_t v_t for k sparse vectors (sorted unique indices).  Outputs must
+ * hold sum_t nnz_t entries; returns the number written. */
+int64_t ora_spadd_vec(int k, const int32_t *const *idx, const void *const *val, const int64_t *nnz,
+                      int is_f64, int32_t *out_idx, double *out_val, double *out_abs)
+{
+    int64_t p[ORA_MAXK], n_out = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) p[t] = 0;
+    union_merge(k, idx, val, is_f64, p, nnz, out_idx, out_val, out_abs, &n_out);
+    return n_out;
+}
+
+/*
+ * Z = sum_t A_t for k DCSR matrices (Section 2.2: rows coiterated as a union,
+ * then the columns of the operands that store the row).  out_crd0/out_pos1 must
+ * hold sum_t rows_t (+1) entries, out_crd1/out_val sum_t nnz_t.  counts[0] =
+ * stored rows, counts[1] = nnz of Z.  out_pos0 = {0, rows}.
+ */
+int ora_spadd_dcsr(int k, const int32_t *const *pos0, const int32_t *const *crd0,
+                   const int32_t *const *pos1, const int32_t *const *crd1,
+                   const void *const *val, int is_f64,
+                   int32_t *out_pos0, int32_t *out_crd0, int32_t *out_pos1, int32_t *out_crd1,
+                   double *out_val, double *out_abs, int64_t *counts)
+{
+    int64_t r[ORA_MAXK], re[ORA_MAXK], p[ORA_MAXK], e[ORA_MAXK];
+    int64_t nr = 0, nz = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) { r[t] = pos0[t][0]; re[t] = pos0[t][1]; }
+    out_pos1[0] = 0;
+    for (;;) {
+        int any = 0;
+        int64_t i = 0;
+        for (int t = 0; t < k; ++t)
+            if (r[t] < re[t]) {
+                int64_t it = crd0[t][r[t]];
+                if (!any || it < i) i = it;
+                any = 1;
+            }
+        if (!any) break;
+        for (int t = 0; t < k; ++t) {
+            if (r[t] < re[t] && (int64_t)crd0[t][r[t]] == i) {
+                p[t] = pos1[t][r[t]];
+                e[t] = pos1[t][r[t] + 1];
+                ++r[t];
+            } else {
+                p[t] = e[t] = 0;
+            }
+        }
+        int64_t before = nz;
+        union_merge(k, crd1, val, is_f64, p, e, out_crd1, out_val, out_abs, &nz);
+        if (nz > before) {                 /* a stored row holds at least one entry */
+            out_crd0[nr] = (int32_t)i;
+            out_pos1[nr + 1] = (int32_t)nz;
+            ++nr;
+        }
+    }
+    out_pos0[0] = 0;
+    out_pos0[1] = (int32_t)nr;
+    counts[0] = nr;
+    counts[1] = nz;
+    return 0;
+}
+
+/*
+ * Z = sum_t A_t for k CSR matrices with the same shape (dense rows, union of
+ * the columns per row).  out_pos has n_rows+1 entries.  Returns nnz of Z.
+ */
+int64_t ora_spadd_csr(int k, int64_t n_rows, const int32_t *const *pos, const int32_t *const *crd,
+                      const void *const *val, int is_f64,
+                      int32_t *out_pos, int32_t *out_crd, double *out_val, double *out_abs)
+{
+    int64_t p[ORA_MAXK], e[ORA_MAXK], nz = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    out_pos[0] = 0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        for (int t = 0; t < k; ++t) { p[t] = pos[t][i]; e[t] = pos[t][i + 1]; }
+        union_merge(k, crd, val, is_f64, p, e, out_crd, out_val, out_abs, &nz);
+        out_pos[i + 1] = (int32_t)nz;
+    }
+    return nz;
+}
