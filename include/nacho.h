@@ -1,0 +1,204 @@
+/*
+ * nacho.h -- C ABI of the MI355X (gfx950) library for provably load-balanced
+ * partitioning of sparse tensor algebra and the partitioned kernels it balances.
+ *
+ * The operations follow the paper "Partitioning Unstructured Sparse Tensor
+ * Algebra for Load-Balanced Parallel Execution":
+ *   - nacho_partition : Section 3.2, Algorithm 1 (hierarchical search) with the
+ *                       non-zero-count cost functions of Section 4.2.2, stored
+ *                       in position space (Section 4.2, 4.2.3);
+ *   - nacho_spmv/spmm : the compute kernel of Section 4.4 for y_i = A_ij x_j and
+ *                       C_ik = A_ij B_jk (cost scaled by the broadcast extent,
+ *                       Section 4.2.2, second listing);
+ *   - nacho_spadd_k   : partition -> assembly (count) -> prefix sum -> compute
+ *                       (Section 4.3, 4.4, pipeline of Figure 7(a)) for the
+ *                       k-operand union of sparse vectors, CSR or DCSR matrices
+ *                       (Section 2.1, 2.2).
+ *
+ * Conventions that hold for every entry point
+ *   * Descriptor structs (nacho_tensor, nacho_parts, nacho_sparse_out) live in
+ *     HOST memory and are read during the call only.
+ *   * Every array pointer inside them, and every `void*`/typed array argument
+ *     that is not explicitly marked "host", is a DEVICE pointer owned by the
+ *     caller.  The library allocates and frees nothing; scratch memory comes
+ *     from the `ws` argument, sized by nacho_workspace_bytes().
+ *   * A call only enqueues kernels on `hip_stream` (a hipStream_t passed as
+ *     void*; NULL is the default stream) and returns without synchronising.
+ *   * Indices and positions are int32; costs are int64.  Preconditions (not
+ *     checked): coordinates sorted and unique inside each segment, `pos`
+ *     non-decreasing with pos[0] = 0, sum of the operands' nnz < 2^31, all
+ *     operands of one call share the same level kinds and extents.
+ *   * `crd`, `val` and dense operand arrays must be 16-byte aligned.
+ *   * The return value is a status code.  Argument errors are detected on the
+ *     host before anything is launched (nothing is written then); a failed HIP
+ *     launch maps to NACHO_ERR_HIP.
+ *   * Calls that share a workspace or an output must not overlap in time.
+ */
+#ifndef NACHO_H
+#define NACHO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NACHO_OK = 0,
+    NACHO_ERR_INVALID_ARG = -1, /* null pointer, bad count, misaligned array, mismatched operands */
+    NACHO_ERR_UNSUPPORTED = -2, /* level formats / operand count outside what is implemented      */
+    NACHO_ERR_WORKSPACE = -3,   /* ws_bytes smaller than nacho_workspace_bytes() reports           */
+    NACHO_ERR_CAPACITY = -4,    /* sparse output larger than the caller's capacity                 */
+    NACHO_ERR_HIP = -5          /* a HIP call failed                                               */
+} nacho_status;
+
+typedef enum { NACHO_F32 = 0, NACHO_F64 = 1 } nacho_dtype;
+typedef enum { NACHO_DENSE = 0, NACHO_COMPRESSED = 1 } nacho_level_kind;
+typedef enum { NACHO_OP_PARTITION = 0, NACHO_OP_SPMV = 1, NACHO_OP_SPMM = 2, NACHO_OP_SPADD = 3 } nacho_op;
+
+#define NACHO_MAX_OPERANDS 8
+#define NACHO_MAX_LEVELS 2
+
+/* One level of a tensor's coordinate hierarchy (Section 4.2.1).
+ *   DENSE:      every coordinate in [0, extent) is present; pos, crd are NULL.
+ *   COMPRESSED: pos[parent] .. pos[parent+1] delimit the sorted coordinates
+ *               crd[] stored below `parent` (a top level has one parent, so
+ *               pos has 2 entries).  `count` is the number of entries of crd. */
+typedef struct {
+    int32_t kind;       /* nacho_level_kind                                    */
+    int64_t extent;     /* N_m, at most 2^31 - 1                               */
+    const int32_t *pos; /* device, [parents + 1]                               */
+    const int32_t *crd; /* device, [count]                                     */
+    int64_t count;      /* stored coordinates at this level (COMPRESSED only)  */
+} nacho_level;
+
+/* A sparse operand.  Supported shapes:
+ *   sparse vector  nlevels = 1  {COMPRESSED}
+ *   CSR            nlevels = 2  {DENSE, COMPRESSED}
+ *   DCSR           nlevels = 2  {COMPRESSED, COMPRESSED}
+ * `val` (device, one value per innermost coordinate) may be NULL for
+ * nacho_partition. */
+typedef struct {
+    int32_t nlevels;
+    nacho_level lvl[NACHO_MAX_LEVELS];
+    const void *val;
+} nacho_tensor;
+
+/* Stored result of the search (Section 4.2.3: the positions found by the
+ * search are kept for the assembly and compute stages).  P partitions have
+ * P + 1 boundaries; boundary 0 is the origin, boundary P the end of the
+ * iteration space, and partition p spans boundaries p .. p+1.
+ *   coord[b*d + m]          coordinate x_m of boundary b
+ *   posn[(b*k + t)*d + m]   for operand t: position of the first level-m entry
+ *                           that is not before the boundary (DENSE level: x_m)
+ *   cost[b]                 C(x) of boundary b = work strictly before it      */
+typedef struct {
+    int32_t k, d;
+    int64_t P;
+    int32_t *coord; /* device, [(P+1) * d]     */
+    int32_t *posn;  /* device, [(P+1) * k * d] */
+    int64_t *cost;  /* device, [P+1]           */
+} nacho_parts;
+
+/* Caller-allocated sparse result of nacho_spadd_k, in the operands' format.
+ *   vector: crd1[cap_nnz], val[cap_nnz]; pos1[2] = {0, nnz}
+ *   CSR:    pos1[n_rows+1], crd1[cap_nnz], val[cap_nnz]
+ *   DCSR:   pos0[2] = {0, rows}, crd0[cap_rows], pos1[cap_rows+1], crd1, val
+ * counts[0] = stored rows (DCSR; n_rows for CSR; 1 for a vector), counts[1] =
+ * nnz.  *status is set to NACHO_OK, or to NACHO_ERR_CAPACITY when cap_rows or
+ * cap_nnz is too small (then nothing is written beyond the capacities; counts
+ * still hold the required sizes).  The sums of the operands' counts are always
+ * sufficient capacities. */
+typedef struct {
+    int32_t *pos0;
+    int32_t *crd0;
+    int32_t *pos1;
+    int32_t *crd1;
+    void *val;
+    int64_t cap_rows, cap_nnz;
+    int64_t *counts; /* device, [2] */
+    int32_t *status; /* device, [1] */
+} nacho_sparse_out;
+
+/* Library version (major*10000 + minor*100 + patch) and a static string for a status. */
+int32_t nacho_version(void);
+const char *nacho_status_string(int32_t status);
+
+/* Number of partitions a fused call uses for total cost `total_cost` when the
+ * caller asks for `P` (0 = automatic).  Fused calls never use fewer partitions
+ * than fit one wavefront's staging buffer, so the result is >= P.
+ * `n_dense`: SpMM's dense extent (ignored otherwise); returns 0 on bad input. */
+int64_t nacho_num_partitions(int32_t op, int32_t dtype, int32_t k, int64_t total_cost,
+                             int64_t n_dense, int64_t P);
+
+/* Bytes of device workspace `op` needs for these operands (host descriptors;
+ * only counts/extents are read).  `P` as passed to the call (0 = automatic),
+ * `n_dense` = columns of B for SpMM (0 otherwise). */
+int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
+                              int64_t n_dense, int64_t P, size_t *bytes);
+
+/*
+ * Algorithm 1 for all P+1 boundaries of a P-way partition, one independent
+ * search per interior boundary (Section 3.2; Section 4.2.3).
+ *   ops[k]        coiterated operands (1 <= k <= NACHO_MAX_OPERANDS)
+ *   cost_scale    >= 1; every stored non-zero costs this much (the extent of a
+ *                 broadcast dense inner loop, Section 4.2.2).  Queries are then
+ *                 interpreted in scaled units and boundaries never fall inside
+ *                 the dense loop: the boundary of query Q is that of
+ *                 floor(Q / cost_scale) in unscaled units.
+ *   P             number of partitions (>= 1)
+ *   queries       device int64[P+1] or NULL.  NULL: Q_p = floor(p*Q_total/P).
+ *                 Entries 0 and P are ignored (origin / end); an interior
+ *                 query >= Q_total yields the end boundary.
+ *   out           coord/posn/cost arrays of the sizes documented above
+ * Errors: INVALID_ARG (null/size/kind), UNSUPPORTED (format), WORKSPACE, HIP.
+ */
+int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, int64_t P,
+                        const int64_t *queries, const nacho_parts *out,
+                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * y = A x with A in CSR (Section 4.2.2 uses this expression for the broadcast
+ * rule; the cost of a partition is its number of stored non-zeros of A, the
+ * dense x is only located into).  One wavefront executes one partition; a row
+ * split across partitions is completed by a deterministic carry fix-up pass.
+ *   A      CSR, val of type `dtype`;  x[n_cols], y[n_rows] of type `dtype`
+ *   P      0 = automatic, else the minimum number of partitions
+ * Every y[i] is written (exactly 0 for an empty row).
+ */
+int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * C = A B with A in CSR and B, C dense row-major (loop order i -> j -> k, dense
+ * k innermost; cost of a stored non-zero = n, the broadcast extent).
+ *   B[n_cols(A) x n] leading dimension ldb,  C[n_rows(A) x n] leading dimension
+ *   ldc (elements); 1 <= n <= 64 per call in this version.
+ */
+int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
+                   void *C, int64_t ldc, int32_t dtype, int64_t P,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Z = sum_t ops[t]: the union of k sparse vectors, CSR or DCSR matrices with
+ * sorted output coordinates; coinciding values are added in operand order.
+ * Pipeline: partition -> count -> exclusive scan -> fill.
+ */
+int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks (not part of the hot path).  While enabled,
+ * every fused call brackets each of its kernels with HIP events on the call's
+ * stream.  nacho_profile_read synchronises on those events and returns the
+ * number of kernels of the last call; ms[i] and names[i] (static strings,
+ * host) are filled for i < min(n, max_n).
+ */
+int32_t nacho_profile_enable(int32_t on);
+int32_t nacho_profile_read(float *ms /* host */, const char **names /* host */, int32_t max_n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NACHO_H */

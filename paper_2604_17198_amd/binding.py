@@ -1,0 +1,278 @@
+"""Thin ctypes binding over libnacho.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers through the C ABI declared in include/nacho.h and returns the
+status code handling to `_check`.  PyTorch is used for device memory and the
+current stream; no step of the hot path runs in Python or in torch.
+
+The library must have been built (`paper_2604_17198_amd.build.build()`); a
+missing library is an error, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+F32, F64 = 0, 1
+DENSE, COMPRESSED = 0, 1
+OP_PARTITION, OP_SPMV, OP_SPMM, OP_SPADD = 0, 1, 2, 3
+MAX_OPERANDS, MAX_LEVELS = 8, 2
+
+EXPORTS = [
+    "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
+    "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k",
+    "nacho_profile_enable", "nacho_profile_read",
+]
+
+
+class NachoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _Level(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("extent", C.c_int64), ("pos", C.c_void_p),
+                ("crd", C.c_void_p), ("count", C.c_int64)]
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("nlevels", C.c_int32), ("lvl", _Level * MAX_LEVELS), ("val", C.c_void_p)]
+
+
+class _Parts(C.Structure):
+    _fields_ = [("k", C.c_int32), ("d", C.c_int32), ("P", C.c_int64), ("coord", C.c_void_p),
+                ("posn", C.c_void_p), ("cost", C.c_void_p)]
+
+
+class _SparseOut(C.Structure):
+    _fields_ = [("pos0", C.c_void_p), ("crd0", C.c_void_p), ("pos1", C.c_void_p),
+                ("crd1", C.c_void_p), ("val", C.c_void_p), ("cap_rows", C.c_int64),
+                ("cap_nnz", C.c_int64), ("counts", C.c_void_p), ("status", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            raise RuntimeError(
+                f"{_build.LIB} is missing: build it with `python -m paper_2604_17198_amd.build` "
+                "(the HIP path has no fallback)")
+        L = C.CDLL(_build.LIB)
+        L.nacho_status_string.restype = C.c_char_p
+        L.nacho_num_partitions.restype = C.c_int64
+        L.nacho_num_partitions.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64]
+        L.nacho_workspace_bytes.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                                            C.c_int64, C.POINTER(C.c_size_t)]
+        L.nacho_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
+                                 C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                 C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_spadd_k.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().nacho_status_string(C.c_int32(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise NachoError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_code(dt) -> int:
+    if dt == torch.float32:
+        return F32
+    if dt == torch.float64:
+        return F64
+    raise TypeError(f"unsupported value type {dt}")
+
+
+# --------------------------------------------------------------------------- #
+# operand descriptors (host structs holding device pointers)
+# --------------------------------------------------------------------------- #
+class Operand:
+    """Keeps the tensors alive and exposes the C descriptor."""
+
+    def __init__(self, levels, val=None):
+        self.keep = []
+        c = _Tensor()
+        c.nlevels = len(levels)
+        for m, l in enumerate(levels):
+            c.lvl[m].extent = int(l["extent"])
+            if l["kind"] == "dense":
+                c.lvl[m].kind = DENSE
+                c.lvl[m].pos = None
+                c.lvl[m].crd = None
+                c.lvl[m].count = 0
+            else:
+                pos, crd = l["pos"], l["crd"]
+                assert pos.dtype == torch.int32 and crd.dtype == torch.int32
+                self.keep += [pos, crd]
+                c.lvl[m].kind = COMPRESSED
+                c.lvl[m].pos = pos.data_ptr()
+                c.lvl[m].crd = crd.data_ptr() if crd.numel() else None
+                c.lvl[m].count = int(crd.numel())
+        if val is not None:
+            self.keep.append(val)
+            c.val = val.data_ptr() if val.numel() else None
+        self.c = c
+        self.nlevels = len(levels)
+        self.nnz = int(levels[-1]["crd"].numel())
+        self.val = val
+
+
+def vector(idx, extent, val=None):
+    pos = torch.tensor([0, idx.numel()], dtype=torch.int32, device=idx.device)
+    return Operand([{"kind": "compressed", "extent": extent, "pos": pos, "crd": idx}], val)
+
+
+def csr(pos, crd, n_rows, n_cols, val=None):
+    return Operand([{"kind": "dense", "extent": n_rows},
+                    {"kind": "compressed", "extent": n_cols, "pos": pos, "crd": crd}], val)
+
+
+def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols, val=None):
+    return Operand([{"kind": "compressed", "extent": n_rows, "pos": pos0, "crd": crd0},
+                    {"kind": "compressed", "extent": n_cols, "pos": pos1, "crd": crd1}], val)
+
+
+def _pack(ops):
+    arr = (_Tensor * len(ops))()
+    for t, o in enumerate(ops):
+        arr[t] = o.c
+    return arr
+
+
+# --------------------------------------------------------------------------- #
+# entry points
+# --------------------------------------------------------------------------- #
+def version() -> int:
+    return int(lib().nacho_version())
+
+
+def num_partitions(op, dtype, k, total_cost, n_dense=0, P=0) -> int:
+    return int(lib().nacho_num_partitions(op, dtype, k, total_cost, n_dense, P))
+
+
+def workspace_bytes(op, ops, dtype, n_dense=0, P=0) -> int:
+    n = C.c_size_t(0)
+    arr = _pack(ops)
+    _check(lib().nacho_workspace_bytes(op, C.cast(arr, C.c_void_p), len(ops), dtype, n_dense, P,
+                                       C.byref(n)), "nacho_workspace_bytes")
+    return int(n.value)
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def nacho_partition(ops, P, queries=None, cost_scale=1):
+    """Boundaries 0..P.  Returns dict(coord[P+1, d], posn[P+1, k, d] int32, cost[P+1] int64)
+    as device tensors."""
+    k, d = len(ops), ops[0].nlevels
+    dev = ops[0].keep[0].device
+    coord = torch.empty((P + 1, d), dtype=torch.int32, device=dev)
+    posn = torch.empty((P + 1, k, d), dtype=torch.int32, device=dev)
+    cost = torch.empty(P + 1, dtype=torch.int64, device=dev)
+    parts = _Parts(k, d, P, coord.data_ptr(), posn.data_ptr(), cost.data_ptr())
+    arr = _pack(ops)
+    if queries is not None:
+        assert queries.dtype == torch.int64 and queries.numel() == P + 1
+    _check(lib().nacho_partition(C.cast(arr, C.c_void_p), k, cost_scale, P, _ptr(queries),
+                                 C.byref(parts), None, 0, _stream()), "nacho_partition")
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
+def nacho_spmv(A: Operand, x, y=None, P=0, ws=None):
+    """y = A x.  A is a CSR Operand with values; x, y device tensors of A's value type."""
+    dt = dtype_code(x.dtype)
+    if y is None:
+        y = torch.empty(A.c.lvl[0].extent, dtype=x.dtype, device=x.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPMV, [A], dt, 0, P), x.device)
+    arr = _pack([A])
+    _check(lib().nacho_spmv(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dt, P, _ptr(ws),
+                            ws.numel(), _stream()), "nacho_spmv")
+    return y
+
+
+def nacho_spmm(A: Operand, B, Cout=None, P=0, ws=None):
+    """C = A B with B, C dense row-major device tensors."""
+    dt = dtype_code(B.dtype)
+    n = int(B.shape[1])
+    if Cout is None:
+        Cout = torch.empty((A.c.lvl[0].extent, n), dtype=B.dtype, device=B.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPMM, [A], dt, n, P), B.device)
+    arr = _pack([A])
+    _check(lib().nacho_spmm(C.cast(arr, C.c_void_p), _ptr(B), n, int(B.stride(0)), _ptr(Cout),
+                            int(Cout.stride(0)), dt, P, _ptr(ws), ws.numel(), _stream()), "nacho_spmm")
+    return Cout
+
+
+class SparseOut:
+    """Caller-allocated result arrays of nacho_spadd_k."""
+
+    def __init__(self, fmt, cap_rows, cap_nnz, dtype, device, n_rows=0):
+        i32 = dict(dtype=torch.int32, device=device)
+        self.fmt = fmt
+        self.pos0 = torch.zeros(2, **i32) if fmt == "dcsr" else None
+        self.crd0 = torch.empty(max(cap_rows, 1), **i32) if fmt == "dcsr" else None
+        n_pos1 = {"vector": 2, "csr": n_rows + 1, "dcsr": cap_rows + 1}[fmt]
+        self.pos1 = torch.zeros(n_pos1, **i32)
+        self.crd1 = torch.empty(max(cap_nnz, 1), **i32)
+        self.val = torch.empty(max(cap_nnz, 1), dtype=dtype, device=device)
+        self.counts = torch.zeros(2, dtype=torch.int64, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.c = _SparseOut(_ptr(self.pos0), _ptr(self.crd0), _ptr(self.pos1), _ptr(self.crd1),
+                            _ptr(self.val), cap_rows, cap_nnz, _ptr(self.counts), _ptr(self.status))
+
+
+def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):
+    """Z = sum of the operands (union add).  Enqueues only; read out.counts / out.status after
+    synchronising."""
+    dt = dtype_code(ops[0].val.dtype)
+    dev = ops[0].val.device
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPADD, ops, dt, 0, P), dev)
+    arr = _pack(ops)
+    _check(lib().nacho_spadd_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
+                               ws.numel(), _stream()), "nacho_spadd_k")
+    return out
+
+
+def profile_enable(on: bool):
+    lib().nacho_profile_enable(1 if on else 0)
+
+
+def profile_read():
+    """[(kernel name, ms)] of the last fused call (synchronises)."""
+    ms = (C.c_float * 16)()
+    names = (C.c_char_p * 16)()
+    n = lib().nacho_profile_read(C.cast(ms, C.c_void_p), C.cast(names, C.c_void_p), 16)
+    if n < 0:
+        raise NachoError(n, "nacho_profile_read")
+    return [(names[i].decode(), float(ms[i])) for i in range(min(n, 16))]

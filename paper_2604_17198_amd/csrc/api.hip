@@ -1,0 +1,289 @@
+// C-ABI entry points: argument checks, workspace carving, kernel sequencing.
+// Nothing here computes; every step of the hot path runs in the kernels.
+#include <cstring>
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace nacho_host {
+
+Profiler &profiler()
+{
+    static Profiler p;
+    return p;
+}
+
+void profile_begin(hipStream_t s)
+{
+    Profiler &p = profiler();
+    if (!p.enabled) return;
+    if (!p.created) {
+        for (int i = 0; i <= Profiler::kMax; ++i) (void)hipEventCreate(&p.ev[i]);
+        p.created = true;
+    }
+    p.n = 0;
+    p.stream = s;
+    (void)hipEventRecord(p.ev[0], s);
+}
+
+void profile_mark(const char *kernel_name)
+{
+    Profiler &p = profiler();
+    if (!p.enabled || p.n >= Profiler::kMax) return;
+    p.name[p.n] = kernel_name;
+    ++p.n;
+    (void)hipEventRecord(p.ev[p.n], p.stream);
+}
+
+}  // namespace nacho_host
+
+using namespace nacho;
+using namespace nacho_host;
+
+namespace {
+
+enum Format { FMT_BAD = 0, FMT_VECTOR, FMT_CSR, FMT_DCSR };
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Format tensor_format(const nacho_tensor &t)
+{
+    if (t.nlevels == 1 && t.lvl[0].kind == NACHO_COMPRESSED) return FMT_VECTOR;
+    if (t.nlevels == 2 && t.lvl[0].kind == NACHO_DENSE && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_CSR;
+    if (t.nlevels == 2 && t.lvl[0].kind == NACHO_COMPRESSED && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_DCSR;
+    return FMT_BAD;
+}
+
+// Checks shapes and pointers of the operands of one call; fills the device
+// descriptor and the total number of stored non-zeros.
+int32_t check_operands(const nacho_tensor *ops, int32_t k, bool need_arrays, DevOperands *dev,
+                       int64_t *total_nnz, Format *fmt_out)
+{
+    if (!ops || k < 1) return NACHO_ERR_INVALID_ARG;
+    if (k > NACHO_MAX_OPERANDS) return NACHO_ERR_UNSUPPORTED;
+    const Format fmt = tensor_format(ops[0]);
+    if (fmt == FMT_BAD) return NACHO_ERR_UNSUPPORTED;
+    std::memset(dev, 0, sizeof(*dev));
+    dev->k = k;
+    dev->d = ops[0].nlevels;
+    int64_t total = 0;
+    for (int t = 0; t < k; ++t) {
+        if (tensor_format(ops[t]) != fmt) return NACHO_ERR_INVALID_ARG;
+        for (int m = 0; m < ops[t].nlevels; ++m) {
+            const nacho_level &L = ops[t].lvl[m];
+            if (L.extent < 0 || L.extent > 0x7fffffffLL) return NACHO_ERR_INVALID_ARG;
+            if (L.extent != ops[0].lvl[m].extent) return NACHO_ERR_INVALID_ARG;
+            DevLevel &D = dev->lvl[t][m];
+            D.kind = L.kind;
+            D.extent = L.extent;
+            if (L.kind == NACHO_COMPRESSED) {
+                if (L.count < 0 || L.count > 0x7fffffffLL) return NACHO_ERR_INVALID_ARG;
+                if (need_arrays && (!L.pos || (L.count > 0 && !L.crd))) return NACHO_ERR_INVALID_ARG;
+                if (need_arrays && !aligned16(L.crd)) return NACHO_ERR_INVALID_ARG;
+                D.pos = L.pos;
+                D.crd = L.crd;
+                D.count = L.count;
+            }
+        }
+        total += ops[t].lvl[ops[t].nlevels - 1].count;
+    }
+    if (total > 0x7fffffffLL) return NACHO_ERR_INVALID_ARG;
+    *total_nnz = total;
+    if (fmt_out) *fmt_out = fmt;
+    return NACHO_OK;
+}
+
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T> T *take(size_t n)
+    {
+        off = align_up(off, 256);
+        T *r = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += n * sizeof(T);
+        return r;
+    }
+};
+
+struct PartsWs {
+    int32_t *coord;
+    int32_t *posn;
+    int64_t *cost;
+};
+
+PartsWs carve_parts(Carver &c, int64_t P, int k, int d)
+{
+    PartsWs w;
+    w.coord = c.take<int32_t>((size_t)(P + 1) * d);
+    w.posn = c.take<int32_t>((size_t)(P + 1) * k * d);
+    w.cost = c.take<int64_t>((size_t)(P + 1));
+    return w;
+}
+
+size_t dtype_size(int32_t dtype) { return dtype == NACHO_F64 ? 8 : 4; }
+
+struct SpmvWs {
+    PartsWs parts;
+    void *carry_val;
+    int32_t *carry_row;
+    size_t bytes;
+};
+
+SpmvWs carve_spmv(void *ws, int64_t P, int32_t dtype)
+{
+    Carver c(ws);
+    SpmvWs w;
+    w.parts = carve_parts(c, P, 1, 2);
+    w.carry_val = c.take<char>((size_t)P * dtype_size(dtype));
+    w.carry_row = c.take<int32_t>((size_t)P);
+    w.bytes = align_up(c.off, 256);
+    return w;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t nacho_version(void) { return 100; }
+
+const char *nacho_status_string(int32_t status)
+{
+    switch (status) {
+    case NACHO_OK: return "ok";
+    case NACHO_ERR_INVALID_ARG: return "invalid argument";
+    case NACHO_ERR_UNSUPPORTED: return "unsupported format or operand count";
+    case NACHO_ERR_WORKSPACE: return "workspace too small";
+    case NACHO_ERR_CAPACITY: return "output capacity too small";
+    case NACHO_ERR_HIP: return "HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+int64_t nacho_num_partitions(int32_t op, int32_t dtype, int32_t k, int64_t total_cost,
+                             int64_t n_dense, int64_t P)
+{
+    (void)k;
+    (void)n_dense;
+    if (total_cost < 0 || P < 0 || (dtype != NACHO_F32 && dtype != NACHO_F64)) return 0;
+    switch (op) {
+    case NACHO_OP_PARTITION: return P > 0 ? P : 0;
+    case NACHO_OP_SPMV: {
+        const int64_t need = total_cost > 0 ? ceil_div(total_cost, spmv_capacity(dtype)) : 1;
+        return P > need ? P : need;
+    }
+    default: return 0;
+    }
+}
+
+int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
+                              int64_t n_dense, int64_t P, size_t *bytes)
+{
+    if (!bytes || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    int32_t rc = check_operands(ops, k, false, &dev, &total, &fmt);
+    if (rc != NACHO_OK) return rc;
+    switch (op) {
+    case NACHO_OP_PARTITION: *bytes = 0; return NACHO_OK;
+    case NACHO_OP_SPMV: {
+        if (k != 1 || fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+        const int64_t Pe = nacho_num_partitions(op, dtype, k, total, n_dense, P);
+        *bytes = carve_spmv(nullptr, Pe, dtype).bytes;
+        return NACHO_OK;
+    }
+    default: return NACHO_ERR_UNSUPPORTED;
+    }
+}
+
+int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, int64_t P,
+                        const int64_t *queries, const nacho_parts *out,
+                        void *ws, size_t ws_bytes, void *hip_stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    if (!out || !out->coord || !out->posn || !out->cost) return NACHO_ERR_INVALID_ARG;
+    if (P < 1 || P > 0x7ffffff0LL || cost_scale < 1) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    int32_t rc = check_operands(ops, k, true, &dev, &total, nullptr);
+    if (rc != NACHO_OK) return rc;
+    if (out->k != k || out->d != dev.d || out->P != P) return NACHO_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    if (launch_partition(dev, cost_scale, P, 0, queries, total, out->coord, out->posn, out->cost, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    return NACHO_OK;
+}
+
+int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
+                   void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!A || !x || !y || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &nnz, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
+    const int64_t n_rows = A->lvl[0].extent;
+    const int64_t Pe = nacho_num_partitions(NACHO_OP_SPMV, dtype, 1, nnz, 0, P);
+    SpmvWs w = carve_spmv(ws, Pe, dtype);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    const int64_t grain = (P == 0) ? spmv_capacity(dtype) : 0;
+    if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
+                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_exec");
+    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_fixup");
+    return NACHO_OK;
+}
+
+int32_t nacho_spmm(const nacho_tensor *, const void *, int64_t, int64_t, void *, int64_t, int32_t,
+                   int64_t, void *, size_t, void *)
+{
+    return NACHO_ERR_UNSUPPORTED;
+}
+
+int32_t nacho_spadd_k(const nacho_tensor *, int32_t, int32_t, int64_t, const nacho_sparse_out *,
+                      void *, size_t, void *)
+{
+    return NACHO_ERR_UNSUPPORTED;
+}
+
+int32_t nacho_profile_enable(int32_t on)
+{
+    profiler().enabled = on != 0;
+    profiler().n = 0;
+    return NACHO_OK;
+}
+
+int32_t nacho_profile_read(float *ms, const char **names, int32_t max_n)
+{
+    Profiler &p = profiler();
+    if (!p.enabled || p.n == 0) return 0;
+    if (hipEventSynchronize(p.ev[p.n]) != hipSuccess) return NACHO_ERR_HIP;
+    for (int i = 0; i < p.n && i < max_n; ++i) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, p.ev[i], p.ev[i + 1]) != hipSuccess) return NACHO_ERR_HIP;
+        if (ms) ms[i] = t;
+        if (names) names[i] = p.name[i];
+    }
+    return p.n;
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Shared device helpers of the nacho HIP library (gfx950, 64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "nacho.h"
+
+#define NACHO_WAVE 64
+
+namespace nacho {
+
+// Device-side copy of the operands' level descriptors (passed by value as a
+// kernel argument; k <= NACHO_MAX_OPERANDS, d <= NACHO_MAX_LEVELS).
+struct DevLevel {
+    int32_t kind;
+    int32_t pad_;
+    int64_t extent;
+    const int32_t *pos;
+    const int32_t *crd;
+    int64_t count;
+};
+struct DevOperands {
+    int32_t k, d;
+    DevLevel lvl[NACHO_MAX_OPERANDS][NACHO_MAX_LEVELS];
+};
+
+// floor(p * total / P) for 0 <= p <= P < 2^31 without leaving int64.
+__host__ __device__ inline int64_t equal_query(int64_t p, int64_t total, int64_t P)
+{
+    int64_t q = total / P, r = total % P;
+    return p * q + (p * r) / P;
+}
+
+__device__ inline int lane_id() { return (int)(threadIdx.x & (NACHO_WAVE - 1)); }
+
+// Butterfly sum over the 64 lanes in a fixed order: every lane ends with the
+// same bits, and the same inputs always give the same result.
+template <typename T>
+__device__ inline T wave_sum(T v)
+{
+#pragma unroll
+    for (int off = NACHO_WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, NACHO_WAVE);
+    return v;
+}
+
+__device__ inline int wave_max(int v)
+{
+#pragma unroll
+    for (int off = NACHO_WAVE / 2; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, NACHO_WAVE));
+    return v;
+}
+
+// Inclusive prefix sum over the lanes of a wavefront.
+__device__ inline int wave_inclusive_scan(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < NACHO_WAVE; off <<= 1) {
+        int n = __shfl_up(v, off, NACHO_WAVE);
+        if (lane >= off) v += n;
+    }
+    return v;
+}
+
+// Least position in [lo, hi) whose coordinate is >= x; hi if there is none.
+__device__ inline int lower_bound_global(const int32_t *__restrict__ crd, int lo, int hi, int64_t x)
+{
+    while (lo < hi) {
+        int mid = lo + ((hi - lo) >> 1);
+        if ((int64_t)crd[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+}  // namespace nacho
+
+// Host-side bookkeeping shared by the translation units.
+namespace nacho_host {
+
+struct Profiler {
+    static constexpr int kMax = 16;
+    bool enabled = false;
+    int n = 0;
+    hipEvent_t ev[kMax + 1] = {};
+    const char *name[kMax] = {};
+    bool created = false;
+    hipStream_t stream = nullptr;
+};
+Profiler &profiler();
+// Call before the first kernel of an entry point, then after every kernel.
+void profile_begin(hipStream_t s);
+void profile_mark(const char *kernel_name);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace nacho_host

@@ -1,0 +1,222 @@
+// SpMV execution: one wavefront per partition (the compute kernel of Section
+// 4.4 with loop bounds taken from the stored partitions), plus the carry
+// fix-up for rows split across partitions.
+//
+// Partition p owns the stored non-zeros at positions [n_p, n_{p+1}) of A.  Its
+// wavefront
+//   1. streams crd/val of that range with 16-byte loads, gathers x and leaves
+//      the products in LDS;
+//   2. walks the rows that overlap the range (their pos entries staged in LDS),
+//      one lane per row; rows with many products are summed by the whole
+//      wavefront instead;
+//   3. stores y[r] for every row that STARTS inside the partition (a row that
+//      ends later gets its first piece here), and hands the piece of the one
+//      row that started earlier to the fix-up pass as a carry.
+// The fix-up pass adds the carries of a row, in a fixed order, to y[r].  There
+// are no floating-point atomics anywhere: results repeat bit for bit.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace nacho {
+
+namespace {
+
+constexpr int kLongRow = 192;  // products per row above which the wavefront sums it together
+
+template <typename T> struct Vec4;
+template <> struct Vec4<float> {
+    static __device__ inline void load(const float *p, float v[4])
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+};
+template <> struct Vec4<double> {
+    static __device__ inline void load(const double *p, double v[4])
+    {
+        const double2 a = *reinterpret_cast<const double2 *>(p);
+        const double2 b = *reinterpret_cast<const double2 *>(p + 2);
+        v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+    }
+};
+
+template <typename T, int G, int RBLK>
+__global__ void __launch_bounds__(NACHO_WAVE)
+spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                 const T *__restrict__ val, const T *__restrict__ x, T *__restrict__ y,
+                 int nnz, const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
+                 T *__restrict__ carry_val, int32_t *__restrict__ carry_row)
+{
+    __shared__ T prod[G + 8];
+    __shared__ int32_t spos[RBLK + 1];
+
+    const int p = blockIdx.x;
+    const int lane = threadIdx.x;
+    // k = 1, d = 2: coord[b*2 + 0] = row, posn[b*2 + 1] = position in crd/val
+    const int r0 = coord[2 * p], r1 = coord[2 * p + 2];
+    const int n0 = posn[2 * p + 1], n1 = posn[2 * p + 3];
+    const int pr0 = pos[r0], pr1 = pos[r1];
+    const bool has_head = n0 > pr0;                    // row r0 started in an earlier partition
+    const int next_first = (n1 > pr1) ? r1 + 1 : r1;   // first row that starts after this partition
+    const int nrows = next_first - r0;                 // rows overlapping or starting here
+    const int a0 = n0 & ~3;                            // 16-byte aligned start of the window
+
+    // pos entries of the first row block, requested before the streamed data
+    int nr = nrows < RBLK ? nrows : RBLK;
+    if (nrows > 0)
+        for (int i = lane; i <= nr; i += NACHO_WAVE) spos[i] = pos[r0 + i];
+
+    // All streamed loads are issued before the first gather, all gathers before
+    // the first LDS store, so one wavefront keeps its whole window in flight.
+    constexpr int kIter = G / (NACHO_WAVE * 4) + 1;    // +1: a misaligned start adds up to 3 items
+    int c[kIter][4];
+    T v[kIter][4];
+#pragma unroll
+    for (int j = 0; j < kIter; ++j) {
+        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
+        if (base < n1) {
+            if (base + 4 <= nnz) {
+                const int4 q = *reinterpret_cast<const int4 *>(crd + base);
+                c[j][0] = q.x; c[j][1] = q.y; c[j][2] = q.z; c[j][3] = q.w;
+                Vec4<T>::load(val + base, v[j]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool in = base + e < nnz;
+                    c[j][e] = in ? crd[base + e] : 0;
+                    v[j][e] = in ? val[base + e] : T(0);
+                }
+            }
+        }
+    }
+    T xv[kIter][4];
+#pragma unroll
+    for (int j = 0; j < kIter; ++j) {
+        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = base + e;
+            const bool in = idx >= n0 && idx < n1;
+            xv[j][e] = in ? x[c[j][e]] : T(0);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kIter; ++j) {
+        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
+        if (base < n1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int idx = base + e;
+                const bool in = idx >= n0 && idx < n1;
+                prod[base - a0 + e] = in ? v[j][e] * xv[j][e] : T(0);
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int rb = 0; rb < nrows; rb += RBLK) {
+        if (rb > 0) {
+            nr = nrows - rb < RBLK ? nrows - rb : RBLK;
+            __syncthreads();
+            for (int i = lane; i <= nr; i += NACHO_WAVE) spos[i] = pos[r0 + rb + i];
+            __syncthreads();
+        }
+        for (int rr0 = 0; rr0 < nr; rr0 += NACHO_WAVE) {
+            const int rr = rr0 + lane;
+            const bool valid = rr < nr;
+            const int a = valid ? spos[rr] : 0;
+            const int b = valid ? spos[rr + 1] : 0;
+            const int lo = (a > n0 ? a : n0) - a0;
+            const int hi = (b < n1 ? b : n1) - a0;
+            const int len = valid && hi > lo ? hi - lo : 0;
+            T sum = T(0);
+            if (len < kLongRow)
+                for (int i = lo; i < lo + len; ++i) sum += prod[i];
+            unsigned long long heavy = __ballot(len >= kLongRow);
+            while (heavy) {
+                const int L = __ffsll((long long)heavy) - 1;
+                heavy &= heavy - 1;
+                const int llo = __shfl(lo, L, NACHO_WAVE), lhi = __shfl(hi, L, NACHO_WAVE);
+                T s = T(0);
+                for (int i = llo + lane; i < lhi; i += NACHO_WAVE) s += prod[i];
+                s = wave_sum(s);
+                if (lane == L) sum = s;
+            }
+            if (valid) {
+                const int r = r0 + rb + rr;
+                if (has_head && r == r0) carry_val[p] = sum;
+                else y[r] = sum;
+            }
+        }
+    }
+    if (lane == 0) carry_row[p] = has_head ? r0 : -1;
+}
+
+// One wavefront per partition; the first partition of a run of carries for the
+// same row adds the whole run to y[row].
+template <typename T>
+__global__ void __launch_bounds__(256)
+spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
+                  const int32_t *__restrict__ carry_row)
+{
+    const int p = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE);
+    if (p >= P) return;
+    const int lane = lane_id();
+    const int r = carry_row[p];
+    if (r < 0) return;
+    if (p > 0 && carry_row[p - 1] == r) return;        // not the head of its run
+    int e = p + 1;                                     // one past the run's last partition
+    for (;;) {
+        const int q = e + lane;
+        const bool same = q < P && carry_row[q] == r;
+        const unsigned long long m = __ballot(same);
+        if (m == ~0ull) { e += NACHO_WAVE; continue; }
+        e += __ffsll((long long)~m) - 1;
+        break;
+    }
+    T s = T(0);
+    for (int q = p + lane; q < e; q += NACHO_WAVE) s += carry_val[q];
+    s = wave_sum(s);
+    if (lane == 0) y[r] += s;
+}
+
+constexpr int kGrainF64 = 1024, kRowsF64 = 1024;
+constexpr int kGrainF32 = 2048, kRowsF32 = 1024;
+
+}  // namespace
+
+int spmv_capacity(int dtype) { return dtype == NACHO_F64 ? kGrainF64 : kGrainF32; }
+
+hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, const void *val,
+                            const void *x, void *y, int64_t n_rows, int64_t nnz,
+                            const int32_t *coord, const int32_t *posn, int64_t P,
+                            void *carry_val, int32_t *carry_row, hipStream_t stream)
+{
+    (void)n_rows;
+    if (dtype == NACHO_F64)
+        hipLaunchKernelGGL((spmv_exec_kernel<double, kGrainF64, kRowsF64>), dim3((unsigned)P),
+                           dim3(NACHO_WAVE), 0, stream, pos, crd, (const double *)val,
+                           (const double *)x, (double *)y, (int)nnz, coord, posn,
+                           (double *)carry_val, carry_row);
+    else
+        hipLaunchKernelGGL((spmv_exec_kernel<float, kGrainF32, kRowsF32>), dim3((unsigned)P),
+                           dim3(NACHO_WAVE), 0, stream, pos, crd, (const float *)val,
+                           (const float *)x, (float *)y, (int)nnz, coord, posn,
+                           (float *)carry_val, carry_row);
+    return hipGetLastError();
+}
+
+hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
+                             const int32_t *carry_row, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)((P * NACHO_WAVE + 255) / 256);
+    if (dtype == NACHO_F64)
+        hipLaunchKernelGGL((spmv_fixup_kernel<double>), dim3(grid), dim3(256), 0, stream,
+                           (double *)y, (int)P, (const double *)carry_val, carry_row);
+    else
+        hipLaunchKernelGGL((spmv_fixup_kernel<float>), dim3(grid), dim3(256), 0, stream,
+                           (float *)y, (int)P, (const float *)carry_val, carry_row);
+    return hipGetLastError();
+}
+
+}  // namespace nacho

@@ -1,0 +1,112 @@
+"""GPU parity: nacho_partition vs the oracle's Algorithm 1, bit-exact on every
+boundary coordinate, position and cost."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_17198_amd import binding as nb
+from paper_2604_17198_amd import workloads
+from gpu_util import csr_operand, dcsr_operand, dev, parts_to_numpy, vector_operand
+from util import random_coords, to_csr, to_dcsr, to_vector
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare(got, ref, tag):
+    assert np.array_equal(got["cost"], ref["cost"]), tag
+    assert np.array_equal(got["posn"].astype(np.int64), ref["posn"]), tag
+    assert np.array_equal(got["coord"].astype(np.int64), ref["coord"][:, :got["coord"].shape[1]]), tag
+
+
+def _vec_ops(vs, extent):
+    g = [nb.vector(dev(v), extent) for v in vs]
+    o = [oracle.vector(v, extent) for v in vs]
+    return g, o
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 8])
+def test_vectors_random_small(k):
+    rng = np.random.default_rng(100 + k)
+    for trial in range(6):
+        extent = int(rng.choice([1, 7, 300, 100_000, 2**31 - 1]))
+        vs = []
+        for t in range(k):
+            n = int(rng.integers(0, min(extent, 3000) + 1))
+            v = to_vector(random_coords(rng, (extent,), n)) if extent < 10**6 else \
+                np.unique(rng.integers(0, extent, n)).astype(np.int32)
+            if trial == 1 and t > 0:
+                v = vs[0].copy()                       # every coordinate tied across operands
+            vs.append(v)
+        g, o = _vec_ops(vs, extent)
+        total = sum(len(v) for v in vs)
+        for P in (1, 2, 5, 64, 257, total + 3):
+            print(f"partition vec k={k} trial={trial} extent={extent} total={total} P={P}", flush=True)
+            got = parts_to_numpy(nb.nacho_partition(g, P))
+            _compare(got, oracle.partition(o, P), (k, trial, P))
+
+
+def test_vectors_explicit_queries_and_cost_scale():
+    rng = np.random.default_rng(7)
+    vs = [to_vector(random_coords(rng, (5000,), n)) for n in (900, 2000, 10)]
+    g, o = _vec_ops(vs, 5000)
+    total = 2910
+    q = np.sort(rng.integers(0, total + 50, 41)).astype(np.int64)
+    got = parts_to_numpy(nb.nacho_partition(g, 40, queries=dev(q)))
+    _compare(got, oracle.partition(o, 40, queries=q), "explicit")
+    # scaled cost: boundaries of floor(Q / scale), costs in scaled units
+    scale = 64
+    qs = (np.arange(41, dtype=np.int64) * (total * scale // 40) // scale) * scale
+    got = parts_to_numpy(nb.nacho_partition(g, 40, queries=dev(qs), cost_scale=scale))
+    ref = oracle.partition(o, 40, queries=qs // scale)
+    assert np.array_equal(got["posn"].astype(np.int64), ref["posn"])
+    assert np.array_equal(got["coord"].astype(np.int64), ref["coord"])
+    assert np.array_equal(got["cost"][:-1], ref["cost"][:-1] * scale)
+
+
+@pytest.mark.parametrize("fmt", ["csr", "dcsr"])
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_matrices_random_small(fmt, k):
+    rng = np.random.default_rng(200 + k)
+    for trial in range(6):
+        shape = (int(rng.integers(1, 400)), int(rng.integers(1, 400)))
+        g, o, total = [], [], 0
+        for t in range(k):
+            n = int(rng.integers(0, min(shape[0] * shape[1], 6000) + 1))
+            c = random_coords(rng, shape, n)
+            total += c.shape[0]
+            if fmt == "csr":
+                pos, crd = to_csr(c, shape[0])
+                g.append(nb.csr(dev(pos), dev(crd), *shape))
+                o.append(oracle.csr(pos, crd, *shape))
+            else:
+                p0, c0, p1, c1 = to_dcsr(c)
+                g.append(nb.dcsr(dev(p0), dev(c0), dev(p1), dev(c1), *shape))
+                o.append(oracle.dcsr(p0, c0, p1, c1, *shape))
+        for P in (1, 3, 17, 300, total + 2):
+            print(f"partition {fmt} k={k} trial={trial} shape={shape} total={total} P={P}", flush=True)
+            got = parts_to_numpy(nb.nacho_partition(g, P))
+            _compare(got, oracle.partition(o, P), (fmt, k, trial, P))
+
+
+def test_config1_and_scaled_configs():
+    c1 = workloads.config(1)
+    A = c1["A"]
+    for P in (20, 39, 4096):
+        print(f"partition config1 P={P}", flush=True)
+        got = parts_to_numpy(nb.nacho_partition([csr_operand(A)], P))
+        _compare(got, oracle.partition([oracle.csr(A["pos"], A["crd"], A["n_rows"], A["n_cols"])], P), P)
+    c3 = workloads.config(3, scale=0.02)
+    print("partition config3 scaled", flush=True)
+    got = parts_to_numpy(nb.nacho_partition([vector_operand(v) for v in c3["ops"]], 999))
+    _compare(got, oracle.partition([oracle.vector(v["i"], v["extent"]) for v in c3["ops"]], 999), "c3")
+    c4 = workloads.config(4, scale=0.02)
+    print("partition config4 scaled", flush=True)
+    got = parts_to_numpy(nb.nacho_partition([dcsr_operand(m) for m in c4["ops"]], 777))
+    ref = oracle.partition([oracle.dcsr(m["pos0"], m["crd0"], m["pos1"], m["crd1"], m["n_rows"], m["n_cols"])
+                            for m in c4["ops"]], 777)
+    _compare(got, ref, "c4")
+    # Theorem 1 on the GPU result: work per partition within k-1 of the ideal
+    work = np.diff(got["cost"])
+    ideal = np.diff([(p * int(got["cost"][-1])) // 777 for p in range(778)])
+    assert np.all(np.abs(work - ideal) <= 1)
