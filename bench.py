@@ -112,7 +112,7 @@ def bench_spmv(args):
     proto_ms = _paper_protocol(step)
 
     # algorithmic bytes: every input array once, the output once, the partition table
-    P = nb.num_partitions(nb.OP_SPMV, nb.F64, 1, nnz)
+    P = nb.num_partitions(nb.OP_SPMV, [op], nb.F64)
     exec_bytes = nnz * 12 + (n_rows + 1) * 4 + n_cols * 8 + n_rows * 8 + (P + 1) * 16 + P * 12
     call_bytes = exec_bytes
     exec_ms = kms["spmv_exec"]

@@ -125,11 +125,12 @@ typedef struct {
 int32_t nacho_version(void);
 const char *nacho_status_string(int32_t status);
 
-/* Number of partitions a fused call uses for total cost `total_cost` when the
- * caller asks for `P` (0 = automatic).  Fused calls never use fewer partitions
- * than fit one wavefront's staging buffer, so the result is >= P.
- * `n_dense`: SpMM's dense extent (ignored otherwise); returns 0 on bad input. */
-int64_t nacho_num_partitions(int32_t op, int32_t dtype, int32_t k, int64_t total_cost,
+/* Number of partitions a fused call uses for these operands (host descriptors;
+ * only counts/extents are read) when the caller asks for `P` (0 = automatic).
+ * Fused calls never use fewer partitions than needed for one partition's work
+ * to fit a wavefront's staging buffer, so the result is >= P.  `n_dense`:
+ * SpMM's dense extent (0 otherwise).  Returns 0 on bad input. */
+int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                              int64_t n_dense, int64_t P);
 
 /* Bytes of device workspace `op` needs for these operands (host descriptors;

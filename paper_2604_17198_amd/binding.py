@@ -69,7 +69,7 @@ def lib():
         L = C.CDLL(_build.LIB)
         L.nacho_status_string.restype = C.c_char_p
         L.nacho_num_partitions.restype = C.c_int64
-        L.nacho_num_partitions.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64]
+        L.nacho_num_partitions.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64]
         L.nacho_workspace_bytes.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
                                             C.c_int64, C.POINTER(C.c_size_t)]
         L.nacho_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
@@ -173,8 +173,9 @@ def version() -> int:
     return int(lib().nacho_version())
 
 
-def num_partitions(op, dtype, k, total_cost, n_dense=0, P=0) -> int:
-    return int(lib().nacho_num_partitions(op, dtype, k, total_cost, n_dense, P))
+def num_partitions(op, ops, dtype, n_dense=0, P=0) -> int:
+    arr = _pack(ops)
+    return int(lib().nacho_num_partitions(op, C.cast(arr, C.c_void_p), len(ops), dtype, n_dense, P))
 
 
 def workspace_bytes(op, ops, dtype, n_dense=0, P=0) -> int:

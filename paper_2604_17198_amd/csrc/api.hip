@@ -123,25 +123,97 @@ PartsWs carve_parts(Carver &c, int64_t P, int k, int d)
 
 size_t dtype_size(int32_t dtype) { return dtype == NACHO_F64 ? 8 : 4; }
 
-struct SpmvWs {
+struct CarryWs {
     PartsWs parts;
     void *carry_val;
     int32_t *carry_row;
     size_t bytes;
 };
 
-SpmvWs carve_spmv(void *ws, int64_t P, int32_t dtype)
+// SpMV: one carry value per partition; SpMM: one 64-wide carry row per partition.
+CarryWs carve_carry(void *ws, int64_t P, int32_t dtype, int width)
 {
     Carver c(ws);
-    SpmvWs w;
+    CarryWs w;
     w.parts = carve_parts(c, P, 1, 2);
-    w.carry_val = c.take<char>((size_t)P * dtype_size(dtype));
+    w.carry_val = c.take<char>((size_t)P * width * dtype_size(dtype));
     w.carry_row = c.take<int32_t>((size_t)P);
     w.bytes = align_up(c.off, 256);
     return w;
 }
 
+struct SpaddWs {
+    PartsWs parts;
+    int32_t *cnt_nnz;
+    int32_t *cnt_rows;
+    size_t bytes;
+};
+
+SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
+{
+    Carver c(ws);
+    SpaddWs w;
+    w.parts = carve_parts(c, P, k, d);
+    w.cnt_nnz = c.take<int32_t>((size_t)P);
+    w.cnt_rows = c.take<int32_t>((size_t)P);
+    w.bytes = align_up(c.off, 256);
+    return w;
+}
+
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int spadd_fmt(Format f) { return f == FMT_VECTOR ? SPADD_VECTOR : (f == FMT_CSR ? SPADD_CSR : SPADD_DCSR); }
+
+// Partitions a fused call uses: at least P, and enough that one partition's work
+// (ideal share + k - 1 by the tightness bound of Section 3.2.2) fits a wavefront.
+int64_t fused_partitions(int32_t op, Format fmt, int32_t dtype, int32_t k, int64_t total_nnz, int64_t P)
+{
+    int64_t cap;
+    if (op == NACHO_OP_SPMV) cap = spmv_capacity(dtype);
+    else if (op == NACHO_OP_SPMM) cap = spmm_capacity(dtype);
+    else cap = spadd_capacity(spadd_fmt(fmt)) - k;
+    const int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
+    return P > need ? P : need;
+}
+
+// Optimal tree of adjacent two-way merges for operand sizes sz[0..k): minimises
+// the number of entries moved (interval dynamic programme, k <= 8).
+struct PlanBuilder {
+    int64_t sz[NACHO_MAX_OPERANDS];
+    int64_t cost[NACHO_MAX_OPERANDS + 1][NACHO_MAX_OPERANDS + 1];
+    int split[NACHO_MAX_OPERANDS + 1][NACHO_MAX_OPERANDS + 1];
+    MergePlan plan;
+    void emit(int a, int b, int depth)
+    {
+        if (b - a == 1) { plan.leaf_buf[a] = (int8_t)(depth & 1); return; }
+        const int m = split[a][b];
+        emit(a, m, depth + 1);
+        emit(m, b, depth + 1);
+        const int e = plan.n_nodes++;
+        plan.a[e] = (int8_t)a; plan.m[e] = (int8_t)m; plan.b[e] = (int8_t)b;
+        plan.out_buf[e] = (int8_t)(depth & 1);
+    }
+    MergePlan build(int k)
+    {
+        std::memset(&plan, 0, sizeof(plan));
+        for (int a = 0; a <= k; ++a)
+            for (int b = 0; b <= k; ++b) cost[a][b] = 0;
+        for (int len = 2; len <= k; ++len)
+            for (int a = 0; a + len <= k; ++a) {
+                const int b = a + len;
+                int64_t sum = 0;
+                for (int t = a; t < b; ++t) sum += sz[t];
+                int64_t best = -1;
+                for (int m = a + 1; m < b; ++m) {
+                    const int64_t c = cost[a][m] + cost[m][b] + sum;
+                    if (best < 0 || c < best) { best = c; split[a][b] = m; }
+                }
+                cost[a][b] = best;
+            }
+        emit(0, k, 0);
+        return plan;
+    }
+};
 
 }  // namespace
 
@@ -162,18 +234,22 @@ const char *nacho_status_string(int32_t status)
     }
 }
 
-int64_t nacho_num_partitions(int32_t op, int32_t dtype, int32_t k, int64_t total_cost,
+int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                              int64_t n_dense, int64_t P)
 {
-    (void)k;
     (void)n_dense;
-    if (total_cost < 0 || P < 0 || (dtype != NACHO_F32 && dtype != NACHO_F64)) return 0;
+    if (P < 0 || (dtype != NACHO_F32 && dtype != NACHO_F64)) return 0;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    if (check_operands(ops, k, false, &dev, &total, &fmt) != NACHO_OK) return 0;
     switch (op) {
-    case NACHO_OP_PARTITION: return P > 0 ? P : 0;
-    case NACHO_OP_SPMV: {
-        const int64_t need = total_cost > 0 ? ceil_div(total_cost, spmv_capacity(dtype)) : 1;
-        return P > need ? P : need;
-    }
+    case NACHO_OP_PARTITION: return P;
+    case NACHO_OP_SPMV:
+    case NACHO_OP_SPMM:
+        if (k != 1 || fmt != FMT_CSR) return 0;
+        return fused_partitions(op, fmt, dtype, k, total, P);
+    case NACHO_OP_SPADD: return fused_partitions(op, fmt, dtype, k, total, P);
     default: return 0;
     }
 }
@@ -190,10 +266,16 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
     if (rc != NACHO_OK) return rc;
     switch (op) {
     case NACHO_OP_PARTITION: *bytes = 0; return NACHO_OK;
-    case NACHO_OP_SPMV: {
+    case NACHO_OP_SPMV:
+    case NACHO_OP_SPMM: {
         if (k != 1 || fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
-        const int64_t Pe = nacho_num_partitions(op, dtype, k, total, n_dense, P);
-        *bytes = carve_spmv(nullptr, Pe, dtype).bytes;
+        const int64_t Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        *bytes = carve_carry(nullptr, Pe, dtype, op == NACHO_OP_SPMM ? NACHO_WAVE : 1).bytes;
+        return NACHO_OK;
+    }
+    case NACHO_OP_SPADD: {
+        const int64_t Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        *bytes = carve_spadd(nullptr, Pe, k, dev.d).bytes;
         return NACHO_OK;
     }
     default: return NACHO_ERR_UNSUPPORTED;
@@ -234,8 +316,8 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
     if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
     if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
     const int64_t n_rows = A->lvl[0].extent;
-    const int64_t Pe = nacho_num_partitions(NACHO_OP_SPMV, dtype, 1, nnz, 0, P);
-    SpmvWs w = carve_spmv(ws, Pe, dtype);
+    const int64_t Pe = fused_partitions(NACHO_OP_SPMV, fmt, dtype, 1, nnz, P);
+    CarryWs w = carve_carry(ws, Pe, dtype, 1);
     if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     profile_begin(s);
@@ -253,16 +335,88 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
     return NACHO_OK;
 }
 
-int32_t nacho_spmm(const nacho_tensor *, const void *, int64_t, int64_t, void *, int64_t, int32_t,
-                   int64_t, void *, size_t, void *)
+int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb, void *C, int64_t ldc,
+                   int32_t dtype, int64_t P, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    return NACHO_ERR_UNSUPPORTED;
+    if (!A || !B || !C || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    if (n < 1 || ldb < n || ldc < n) return NACHO_ERR_INVALID_ARG;
+    if (n > NACHO_WAVE) return NACHO_ERR_UNSUPPORTED;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &nnz, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (nnz > 0 && !A->val) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = fused_partitions(NACHO_OP_SPMM, fmt, dtype, 1, nnz, P);
+    CarryWs w = carve_carry(ws, Pe, dtype, NACHO_WAVE);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    // cost of a stored non-zero = n (broadcast over the dense loop); queries are multiples of n
+    const int64_t grain = (P == 0) ? (int64_t)spmm_capacity(dtype) * n : 0;
+    if (launch_partition(dev, n, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    if (launch_spmm_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, B, (int)n, ldb, C, ldc,
+                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmm_exec");
+    if (launch_spmm_fixup(dtype, C, ldc, (int)n, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmm_fixup");
+    return NACHO_OK;
 }
 
-int32_t nacho_spadd_k(const nacho_tensor *, int32_t, int32_t, int64_t, const nacho_sparse_out *,
-                      void *, size_t, void *)
+int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    return NACHO_ERR_UNSUPPORTED;
+    if (!out || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
+    if (rc != NACHO_OK) return rc;
+    SpaddValues vals;
+    PlanBuilder pb;
+    std::memset(&vals, 0, sizeof(vals));
+    for (int t = 0; t < k; ++t) {
+        const int64_t nt = ops[t].lvl[dev.d - 1].count;
+        if (nt > 0 && !ops[t].val) return NACHO_ERR_INVALID_ARG;
+        vals.v[t] = ops[t].val;
+        pb.sz[t] = nt;
+    }
+    if (!out->counts || !out->status || !out->pos1 || out->cap_nnz < 0 || out->cap_rows < 0)
+        return NACHO_ERR_INVALID_ARG;
+    if (out->cap_nnz > 0 && (!out->crd1 || !out->val)) return NACHO_ERR_INVALID_ARG;
+    if (fmt == FMT_DCSR && (!out->pos0 || (out->cap_rows > 0 && !out->crd0))) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
+    SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    const MergePlan plan = pb.build(k);
+    SpaddOut o;
+    o.pos0 = out->pos0; o.crd0 = out->crd0; o.pos1 = out->pos1; o.crd1 = out->crd1; o.val = out->val;
+    o.cap_rows = out->cap_rows; o.cap_nnz = out->cap_nnz; o.counts = out->counts; o.status = out->status;
+    const int f = spadd_fmt(fmt);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    if (launch_spadd_pass(false, f, dtype, dev, vals, plan, w.parts.coord, w.parts.posn, Pe, w.cnt_nnz,
+                          w.cnt_rows, o, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spadd_count");
+    if (launch_spadd_scan(f, Pe, w.cnt_nnz, w.cnt_rows, dev.lvl[0][0].extent, o, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spadd_scan");
+    if (launch_spadd_pass(true, f, dtype, dev, vals, plan, w.parts.coord, w.parts.posn, Pe, w.cnt_nnz,
+                          w.cnt_rows, o, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spadd_fill");
+    return NACHO_OK;
 }
 
 int32_t nacho_profile_enable(int32_t on)

@@ -20,4 +20,44 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
                              const int32_t *carry_row, hipStream_t stream);
 
+// ---- SpMM (lane per column of B, n <= 64) -----------------------------------
+int spmm_capacity(int dtype);
+hipError_t launch_spmm_exec(int dtype, const int32_t *pos, const int32_t *crd, const void *val,
+                            const void *B, int n, int64_t ldb, void *C, int64_t ldc,
+                            const int32_t *coord, const int32_t *posn, int64_t P, void *carry_val,
+                            int32_t *carry_row, hipStream_t stream);
+hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, const void *carry_val,
+                             const int32_t *carry_row, hipStream_t stream);
+
+// ---- k-way union addition ---------------------------------------------------
+enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2 };
+constexpr int kSpaddCapVector = 2048;   // entries of all operands one wavefront stages (vectors)
+constexpr int kSpaddCapMatrix = 1024;   // ... (CSR / DCSR: 64-bit keys)
+
+struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
+// Tree of stable two-way merges over adjacent operands, children before parents.
+// Node e merges operands [a, m) with [m, b) from buffer 1 - out_buf into out_buf;
+// operand t is staged in buffer leaf_buf[t]; the root writes buffer 0.
+struct MergePlan {
+    int32_t n_nodes;
+    int8_t a[NACHO_MAX_OPERANDS], m[NACHO_MAX_OPERANDS], b[NACHO_MAX_OPERANDS];
+    int8_t out_buf[NACHO_MAX_OPERANDS], leaf_buf[NACHO_MAX_OPERANDS];
+};
+struct SpaddOut {
+    int32_t *pos0, *crd0, *pos1, *crd1;
+    void *val;
+    int64_t cap_rows, cap_nnz;
+    int64_t *counts;
+    int32_t *status;
+};
+int spadd_capacity(int fmt);
+// fill == false: per-partition output counts into cnt_nnz / cnt_rows;
+// fill == true : the same arrays hold exclusive offsets and the result is written.
+hipError_t launch_spadd_pass(bool fill, int fmt, int dtype, const DevOperands &ops,
+                             const SpaddValues &vals, const MergePlan &plan, const int32_t *coord,
+                             const int32_t *posn, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows,
+                             const SpaddOut &out, hipStream_t s);
+hipError_t launch_spadd_scan(int fmt, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows, int64_t n_rows,
+                             const SpaddOut &out, hipStream_t s);
+
 }  // namespace nacho

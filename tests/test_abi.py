@@ -33,9 +33,18 @@ def test_host_side_helpers_run_without_a_gpu():
     assert lib.nacho_version() >= 100
     assert binding.status_string(0) == "ok" and "workspace" in binding.status_string(-3)
     # automatic partition count: enough partitions that each fits a wavefront's staging buffer
-    n = binding.num_partitions(binding.OP_SPMV, binding.F64, 1, 50_000_000)
-    assert n >= 50_000_000 // 4096 and binding.num_partitions(binding.OP_SPMV, binding.F64, 1, 0) == 1
-    assert binding.num_partitions(binding.OP_SPMV, binding.F64, 1, 1000, 0, 77) == 77
+    def csr_desc(nnz):
+        t = binding._Tensor()
+        t.nlevels = 2
+        t.lvl[0].kind, t.lvl[0].extent = binding.DENSE, 1000
+        t.lvl[1].kind, t.lvl[1].extent, t.lvl[1].count = binding.COMPRESSED, 1000, nnz
+        return (binding._Tensor * 1)(t)
+
+    def nparts(nnz, P=0):
+        return lib.nacho_num_partitions(binding.OP_SPMV, ctypes.cast(csr_desc(nnz), ctypes.c_void_p), 1,
+                                        binding.F64, 0, P)
+
+    assert nparts(50_000_000) >= 50_000_000 // 4096 and nparts(0) == 1 and nparts(1000, 77) == 77
 
 
 def test_argument_errors_are_reported_before_any_launch():
