@@ -144,8 +144,8 @@ CarryWs carve_carry(void *ws, int64_t P, int32_t dtype, int width)
 
 struct SpaddWs {
     PartsWs parts;
-    int32_t *cnt_nnz;
-    int32_t *cnt_rows;
+    unsigned long long *tile_state;   // look-back state word per partition
+    unsigned int *ticket;             // partition hand-out counter
     size_t bytes;
 };
 
@@ -154,8 +154,8 @@ SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
     Carver c(ws);
     SpaddWs w;
     w.parts = carve_parts(c, P, k, d);
-    w.cnt_nnz = c.take<int32_t>((size_t)P);
-    w.cnt_rows = c.take<int32_t>((size_t)P);
+    w.tile_state = c.take<unsigned long long>((size_t)P);
+    w.ticket = c.take<unsigned int>(1);
     w.bytes = align_up(c.off, 256);
     return w;
 }
@@ -402,20 +402,15 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     const int f = spadd_fmt(fmt);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     profile_begin(s);
+    if (launch_spadd_reset(Pe, w.tile_state, w.ticket, o.status, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("spadd_reset");
     if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
-    if (launch_spadd_pass(false, f, dtype, dev, vals, plan, w.parts.coord, w.parts.posn, Pe, w.cnt_nnz,
-                          w.cnt_rows, o, s) != hipSuccess)
+    if (launch_spadd(f, dtype, dev, vals, plan, Pe, w.parts.coord, w.parts.posn, w.tile_state, w.ticket,
+                     o, s) != hipSuccess)
         return NACHO_ERR_HIP;
-    profile_mark("spadd_count");
-    if (launch_spadd_scan(f, Pe, w.cnt_nnz, w.cnt_rows, dev.lvl[0][0].extent, o, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spadd_scan");
-    if (launch_spadd_pass(true, f, dtype, dev, vals, plan, w.parts.coord, w.parts.posn, Pe, w.cnt_nnz,
-                          w.cnt_rows, o, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spadd_fill");
+    profile_mark("spadd_merge");
     return NACHO_OK;
 }
 

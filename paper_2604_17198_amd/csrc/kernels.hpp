@@ -31,7 +31,7 @@ hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, 
 
 // ---- k-way union addition ---------------------------------------------------
 enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2 };
-constexpr int kSpaddCapVector = 2048;   // entries of all operands one wavefront stages (vectors)
+constexpr int kSpaddCapVector = 1024;   // entries of all operands one wavefront stages (vectors)
 constexpr int kSpaddCapMatrix = 1024;   // ... (CSR / DCSR: 64-bit keys)
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
@@ -51,13 +51,13 @@ struct SpaddOut {
     int32_t *status;
 };
 int spadd_capacity(int fmt);
-// fill == false: per-partition output counts into cnt_nnz / cnt_rows;
-// fill == true : the same arrays hold exclusive offsets and the result is written.
-hipError_t launch_spadd_pass(bool fill, int fmt, int dtype, const DevOperands &ops,
-                             const SpaddValues &vals, const MergePlan &plan, const int32_t *coord,
-                             const int32_t *posn, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows,
-                             const SpaddOut &out, hipStream_t s);
-hipError_t launch_spadd_scan(int fmt, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows, int64_t n_rows,
-                             const SpaddOut &out, hipStream_t s);
+// Clears the per-call look-back state (P state words, ticket) and the status word.
+hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, unsigned int *ticket,
+                              int32_t *status, hipStream_t s);
+// Count, look-back prefix sum and fill in one kernel, one wavefront per partition.
+hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals,
+                        const MergePlan &plan, int64_t P, const int32_t *coord, const int32_t *posn,
+                        unsigned long long *tile_state, unsigned int *ticket, const SpaddOut &out,
+                        hipStream_t s);
 
 }  // namespace nacho

@@ -1,5 +1,6 @@
-// k-way sparse union addition: assembly (count), prefix sum, compute (fill)
-// -- Section 4.3 and 4.4, pipeline of Figure 7(a) -- one wavefront per partition.
+// k-way sparse union addition: assembly (count), prefix sum and compute (fill)
+// of Section 4.3 / 4.4 (pipeline of Figure 7(a)) in ONE kernel, one wavefront
+// per partition.
 //
 // A partition owns, in every operand t, the stored entries at last-level
 // positions [q_t(p), q_t(p+1)) found by the partition search; because the
@@ -8,18 +9,25 @@
 // so a partition's output is independent of its neighbours: there is no carry.
 //
 // Per partition the wavefront
-//   1. stages the operands' coordinate segments in LDS as sorted runs of keys
-//      (vectors: the index; matrices: row<<32 | column, the row of every entry
-//      recovered from the pos array with a marker + running-maximum scan);
+//   1. stages the operands' coordinate segments (and values) in LDS as sorted
+//      runs of keys (vectors: the index; matrices: row<<32 | column, the row of
+//      every entry recovered from the pos array with a marker + running-maximum
+//      scan); all global loads are issued in batches before they are consumed;
 //   2. merges the k runs with a tree of stable two-way merges (merge-path split
 //      per lane, serial merge of each lane's share), ties kept in operand order;
-//   3. marks the first entry of every group of equal keys; the number of marks
-//      is the partition's output count (assembly), their prefix ranks are the
-//      write offsets inside the partition (compute);
-//   4. in the compute pass writes coordinate and the sum of the group's values
-//      (added in operand order) at partition_offset + rank, and the hierarchical
-//      arrays (crd0/pos1 of a DCSR result, pos of a CSR result) for the rows
-//      whose first output entry it owns -- one writer per row.
+//   3. assembly: marks the first entry of every group of equal keys; the number
+//      of marks is the partition's output count (and the number of rows whose
+//      first output entry lies in the partition);
+//   4. prefix sum: publishes its counts and adds up the counts of all earlier
+//      partitions with a decoupled look-back over a per-partition state word
+//      (partitions are handed out through an atomic ticket, so every partition a
+//      wavefront waits for has already started; the wait is bounded anyway);
+//   5. compute: writes coordinate and the sum of each group's values (added in
+//      operand order) at offset + rank, and the hierarchical arrays (crd0/pos1 of
+//      a DCSR result, pos of a CSR result) for the rows whose first output entry
+//      it owns -- exactly one writer per row.
+// What differs from the paper's three kernels: the inputs are read once instead
+// of twice and there is no separate scan launch; the arithmetic is the same.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -33,11 +41,21 @@ template <> struct KeyOf<SPADD_VECTOR> { typedef uint32_t type; };
 template <int FMT> struct Cap { static constexpr int value = kSpaddCapMatrix; };
 template <> struct Cap<SPADD_VECTOR> { static constexpr int value = kSpaddCapVector; };
 
+// state word of a partition: bits 63..62 status, 61..31 rows, 30..0 nnz
+constexpr unsigned long long kStatusShift = 62;
+constexpr unsigned long long kAggregate = 1ull, kInclusive = 2ull;
+constexpr int kSpinLimit = 1 << 20;   // look-back polls before a wavefront gives up
+
+__device__ inline unsigned long long pack_state(unsigned long long status, long long rows, long long nnz)
+{
+    return (status << kStatusShift) | ((unsigned long long)rows << 31) | (unsigned long long)nnz;
+}
+
 // Stable two-way merge of the adjacent sorted runs [lo, mid) and [mid, hi) of
-// (sk, sp) into the same range of (dk, dp).  Every lane finds the merge-path
+// (sk, sv) into the same range of (dk, dv).  Every lane finds the merge-path
 // split of its first output and merges its share serially.
-template <typename KeyT>
-__device__ inline void merge_runs(const KeyT *sk, const uint16_t *sp, KeyT *dk, uint16_t *dp,
+template <typename KeyT, typename T>
+__device__ inline void merge_runs(const KeyT *sk, const T *sv, KeyT *dk, T *dv,
                                   int lo, int mid, int hi, int lane)
 {
     const int nA = mid - lo, nB = hi - mid, n = nA + nB;
@@ -57,7 +75,7 @@ __device__ inline void merge_runs(const KeyT *sk, const uint16_t *sp, KeyT *dk, 
     for (int o = d0; o < d1; ++o) {
         const bool takeA = (j >= nB) || (i < nA && ka <= kb);
         dk[lo + o] = takeA ? ka : kb;
-        dp[lo + o] = takeA ? sp[lo + i] : sp[mid + j];
+        dv[lo + o] = takeA ? sv[lo + i] : sv[mid + j];
         if (takeA) { ++i; if (i < nA) ka = A[i]; }
         else { ++j; if (j < nB) kb = B[j]; }
     }
@@ -84,24 +102,29 @@ __device__ inline bool row_continues(const DevOperands &ops, const int32_t *coor
     return cont;
 }
 
-template <int FMT, typename T, bool kFill>
+template <int FMT, typename T>
 __global__ void __launch_bounds__(NACHO_WAVE)
-spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
+spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
-             int32_t *__restrict__ cnt_nnz, int32_t *__restrict__ cnt_rows,   // count: out; fill: exclusive offsets
+             unsigned long long *__restrict__ tile_state, unsigned int *__restrict__ ticket,
              SpaddOut out)
 {
     typedef typename KeyOf<FMT>::type KeyT;
     constexpr int CAP = Cap<FMT>::value;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
+    constexpr int U = 8;                       // global loads in flight per lane and batch
     __shared__ KeyT keys[2][CAP];
-    __shared__ uint16_t pay[2][CAP];
+    __shared__ T lval[2][CAP];
     __shared__ int32_t rowtmp[FMT == SPADD_VECTOR ? 1 : CAP];
     __shared__ int32_t soff[NACHO_MAX_OPERANDS + 1];
+    __shared__ unsigned int s_tile;
 
-    const int64_t p = blockIdx.x;
     const int lane = threadIdx.x;
     const int k = ops.k;
+    if (lane == 0) s_tile = atomicAdd(ticket, 1u);
+    __syncthreads();
+    const int64_t p = s_tile;                  // partitions are taken in ticket order
+    if (p >= P) return;
 
     // ---- 1. segments of this partition --------------------------------------
     int q_lo[NACHO_MAX_OPERANDS], off[NACHO_MAX_OPERANDS + 1];
@@ -119,32 +142,25 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
         if (lane == 0) soff[t] = off[t];
         if (t == k) n = off[t];
     }
+    // Only an operand that violates its preconditions (unsorted or repeated
+    // coordinates) can overflow the staging buffer: such a partition contributes
+    // nothing and the call reports INVALID_ARG, but the look-back chain goes on.
+    const bool broken = n > CAP || n < 0;
+    if (broken) n = 0;
 
-    if (n > CAP || n < 0) {
-        // only possible when an operand violates its preconditions (unsorted or
-        // repeated coordinates): refuse the partition instead of overrunning LDS
-        if (lane == 0) {
-            if (kFill) *out.status = NACHO_ERR_INVALID_ARG;
-            else { cnt_nnz[p] = 0; if (FMT == SPADD_DCSR) cnt_rows[p] = 0; }
-        }
-        return;
-    }
 #pragma unroll
     for (int t = 0; t < NACHO_MAX_OPERANDS; ++t) {
         if (t >= k) break;
-        const int nt = off[t + 1] - off[t];
-        const int32_t *crd = ops.lvl[t][D - 1].crd;
+        const int nt = broken ? 0 : off[t + 1] - off[t];
+        const int32_t *crd = ops.lvl[t][D - 1].crd + q_lo[t];
+        const T *val = static_cast<const T *>(vals.v[t]) + q_lo[t];
         KeyT *kb = keys[plan.leaf_buf[t]] + off[t];
-        uint16_t *pb = pay[plan.leaf_buf[t]] + off[t];
-        if (D == 1) {
-            for (int i = lane; i < nt; i += NACHO_WAVE) {
-                kb[i] = (KeyT)(uint32_t)crd[q_lo[t] + i];
-                pb[i] = (uint16_t)(off[t] + i);
-            }
-        } else {
+        T *vb = lval[plan.leaf_buf[t]] + off[t];
+        if (D == 2) {
             // rows overlapping [q_lo, q_hi): mark each row's first entry, then a running maximum
             const int32_t *pos1 = ops.lvl[t][1].pos;
-            const int qh = q_lo[t] + nt;
+            const int32_t *crd0 = ops.lvl[t][0].crd;
+            const int ql = q_lo[t], qh = ql + nt;
             const int i_lo = posn[(p * k + t) * 2 + 0];
             int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
             const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
@@ -153,12 +169,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
             for (int i = lane; i < nt; i += NACHO_WAVE) mark[i] = 0;
             __syncthreads();
             if (nt > 0)
-                for (int i = i_lo + lane; i < i_hi; i += NACHO_WAVE) {
-                    const int a = pos1[i], b = pos1[i + 1];
-                    const int s = a > q_lo[t] ? a : q_lo[t];
-                    if (b > s && s < qh) {
-                        const int row = FMT == SPADD_CSR ? i : ops.lvl[t][0].crd[i];
-                        mark[s - q_lo[t]] = row + 1;
+                for (int i0 = i_lo + lane; i0 < i_hi; i0 += NACHO_WAVE * 4) {
+                    int a[4], b[4], row[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * NACHO_WAVE;
+                        if (i < i_hi) {
+                            a[u] = pos1[i];
+                            b[u] = pos1[i + 1];
+                            row[u] = FMT == SPADD_CSR ? i : crd0[i];
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * NACHO_WAVE;
+                        if (i < i_hi) {
+                            const int s = a[u] > ql ? a[u] : ql;
+                            if (b[u] > s && s < qh) mark[s - ql] = row[u] + 1;
+                        }
                     }
                 }
             __syncthreads();
@@ -178,30 +206,46 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
             run = before;
             for (int i = c0; i < c1; ++i) {
                 run = max(run, mark[i]);
-                const uint32_t row = (uint32_t)(run - 1);
-                kb[i] = (KeyT)(((uint64_t)row << 32) | (uint32_t)crd[q_lo[t] + i]);
-                pb[i] = (uint16_t)(off[t] + i);
+                mark[i] = run;
             }
             __syncthreads();
+        }
+        const int32_t *mark = rowtmp + (D == 2 ? off[t] : 0);
+        for (int i0 = lane; i0 < nt; i0 += NACHO_WAVE * U) {
+            int c[U];
+            T v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * NACHO_WAVE;
+                if (i < nt) { c[u] = crd[i]; v[u] = val[i]; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * NACHO_WAVE;
+                if (i < nt) {
+                    if (D == 1) kb[i] = (KeyT)(uint32_t)c[u];
+                    else kb[i] = (KeyT)(((uint64_t)(uint32_t)(mark[i] - 1) << 32) | (uint32_t)c[u]);
+                    vb[i] = v[u];
+                }
+            }
         }
     }
     __syncthreads();
 
     // ---- 2. merge tree --------------------------------------------------------
-    for (int e = 0; e < plan.n_nodes; ++e) {
-        const int ob = plan.out_buf[e];
-        merge_runs<KeyT>(keys[1 - ob], pay[1 - ob], keys[ob], pay[ob],
-                         soff[plan.a[e]], soff[plan.m[e]], soff[plan.b[e]], lane);
-        __syncthreads();
-    }
+    if (!broken)
+        for (int e = 0; e < plan.n_nodes; ++e) {
+            const int ob = plan.out_buf[e];
+            merge_runs<KeyT, T>(keys[1 - ob], lval[1 - ob], keys[ob], lval[ob],
+                                soff[plan.a[e]], soff[plan.m[e]], soff[plan.b[e]], lane);
+            __syncthreads();
+        }
     const KeyT *mk = keys[0];
-    const uint16_t *mp = pay[0];
+    const T *mv = lval[0];
 
-    // ---- 3./4. heads, ranks, output -------------------------------------------
+    // ---- 3. assembly: count group heads and row heads ---------------------------
     bool cont = false;                 // the partition starts inside a row whose head is elsewhere
     if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
-    const int64_t base_nnz = kFill ? (int64_t)cnt_nnz[p] : 0;
-    const int64_t base_rows = (kFill && FMT == SPADD_DCSR) ? (int64_t)cnt_rows[p] : 0;
     int heads = 0, rheads = 0;
     for (int i0 = 0; i0 < n; i0 += NACHO_WAVE) {
         const int i = i0 + lane;
@@ -209,52 +253,103 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
         const KeyT key = valid ? mk[i] : KeyT(0);
         const KeyT prev = (valid && i > 0) ? mk[i - 1] : KeyT(0);
         const bool head = valid && (i == 0 || key != prev);
+        heads += __popcll(__ballot(head));
+        if (FMT == SPADD_DCSR) {
+            const bool rhead = head && (i == 0 ? !cont : (uint32_t)((uint64_t)key >> 32) != (uint32_t)((uint64_t)prev >> 32));
+            rheads += __popcll(__ballot(rhead));
+        }
+    }
+
+    // ---- 4. prefix sum by decoupled look-back -----------------------------------
+    long long base_rows = 0, base_nnz = 0;
+    bool gave_up = false;
+    if (p > 0) {
+        if (lane == 0)
+            __hip_atomic_store(&tile_state[p], pack_state(kAggregate, rheads, heads), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        int64_t first = p - 1;          // lane L looks at partition first - L
+        int spins = 0;
+        for (;;) {
+            const int64_t j = first - lane;
+            unsigned long long s = pack_state(kInclusive, 0, 0);     // before partition 0: nothing
+            if (j >= 0) s = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long st = s >> kStatusShift;
+            const unsigned long long incl = __ballot(st == kInclusive);
+            const int stop = incl ? __ffsll((long long)incl) - 1 : NACHO_WAVE;   // nearest inclusive
+            const unsigned long long need = stop >= NACHO_WAVE - 1 ? ~0ull : ((2ull << stop) - 1);
+            if (__ballot(st == 0) & need) {                // a needed predecessor has not published yet
+                if (++spins > kSpinLimit) { gave_up = true; break; }
+                __builtin_amdgcn_s_sleep(2);
+                continue;
+            }
+            const bool use = lane <= stop;
+            base_nnz += wave_sum<long long>(use ? (long long)(s & 0x7fffffffull) : 0ll);
+            base_rows += wave_sum<long long>(use ? (long long)((s >> 31) & 0x7fffffffull) : 0ll);
+            if (stop < NACHO_WAVE) break;
+            first -= NACHO_WAVE;
+        }
+    }
+    if (lane == 0)
+        __hip_atomic_store(&tile_state[p], pack_state(kInclusive, base_rows + rheads, base_nnz + heads),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (gave_up || broken) {
+        if (lane == 0) *out.status = gave_up ? NACHO_ERR_HIP : NACHO_ERR_INVALID_ARG;
+        if (gave_up) return;
+    }
+    if (p == P - 1 && lane == 0) {
+        // totals, tails and the capacity verdict (the only writer of these words)
+        const long long total_nnz = base_nnz + heads;
+        const long long total_rows = FMT == SPADD_DCSR ? base_rows + rheads
+                                                       : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
+        out.counts[0] = total_rows;
+        out.counts[1] = total_nnz;
+        const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
+        if (!fits) *out.status = NACHO_ERR_CAPACITY;
+        if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
+        if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
+        if (FMT == SPADD_DCSR) {
+            out.pos0[0] = 0;
+            out.pos0[1] = (int32_t)total_rows;
+            if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
+        }
+    }
+
+    // ---- 5. compute: write the partition's output ------------------------------
+    int hcount = 0, rcount = 0;
+    for (int i0 = 0; i0 < n; i0 += NACHO_WAVE) {
+        const int i = i0 + lane;
+        const bool valid = i < n;
+        const KeyT key = valid ? mk[i] : KeyT(0);
+        const KeyT prev = (valid && i > 0) ? mk[i - 1] : KeyT(0);
+        const bool head = valid && (i == 0 || key != prev);
         const unsigned long long hm = __ballot(head);
-        const int j = heads + __popcll(hm & ((1ull << lane) - 1));
+        const int j = hcount + __popcll(hm & ((1ull << lane) - 1));
         bool rhead = false;
         int jr = 0;
         if (FMT == SPADD_DCSR) {
-            rhead = head && (i == 0 ? !cont : (uint32_t)(key >> 32) != (uint32_t)((uint64_t)prev >> 32));
+            rhead = head && (i == 0 ? !cont : (uint32_t)((uint64_t)key >> 32) != (uint32_t)((uint64_t)prev >> 32));
             const unsigned long long rm = __ballot(rhead);
-            jr = rheads + __popcll(rm & ((1ull << lane) - 1));
-            rheads += __popcll(rm);
+            jr = rcount + __popcll(rm & ((1ull << lane) - 1));
+            rcount += __popcll(rm);
         }
-        if (kFill && FMT == SPADD_CSR && valid) rowtmp[i] = j;   // heads before item i
-        if (kFill && head) {
-            // sum of the group, in operand order (the merge is stable)
-            T sum = T(0);
-            int g = i;
-            do {
-                const int idx = mp[g];
-                int t_off = 0, t_q = q_lo[0];
-                const void *t_v = vals.v[0];
-#pragma unroll
-                for (int s = 1; s < NACHO_MAX_OPERANDS; ++s)
-                    if (s < k && idx >= off[s]) { t_off = off[s]; t_q = q_lo[s]; t_v = vals.v[s]; }
-                sum += static_cast<const T *>(t_v)[t_q + (idx - t_off)];
-                ++g;
-            } while (g < n && mk[g] == key);
-            const int64_t w = base_nnz + j;
+        if (FMT == SPADD_CSR && valid) rowtmp[i] = j;       // heads before item i
+        if (head) {
+            T sum = mv[i];                                  // group sum in operand order (stable merge)
+            for (int g = i + 1; g < n && mk[g] == key; ++g) sum += mv[g];
+            const long long w = base_nnz + j;
             if (w < out.cap_nnz) {
                 out.crd1[w] = (int32_t)(uint32_t)key;
                 static_cast<T *>(out.val)[w] = sum;
             }
             if (FMT == SPADD_DCSR && rhead) {
-                const int64_t wr = base_rows + jr;
+                const long long wr = base_rows + jr;
                 if (wr < out.cap_rows) {
                     out.crd0[wr] = (int32_t)(uint32_t)((uint64_t)key >> 32);
                     out.pos1[wr] = (int32_t)w;
                 }
             }
         }
-        heads += __popcll(hm);
-    }
-    if (!kFill) {
-        if (lane == 0) {
-            cnt_nnz[p] = heads;
-            if (FMT == SPADD_DCSR) cnt_rows[p] = rheads;
-        }
-        return;
+        hcount += __popcll(hm);
     }
     if (FMT == SPADD_CSR) {
         // pos of every row that starts inside this partition: offset of the first
@@ -274,100 +369,51 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan,
     }
 }
 
-// Exclusive prefix sums of the per-partition counts (in place), totals, output
-// tails and the capacity check.  One workgroup.
-__global__ void __launch_bounds__(1024)
-spadd_scan_kernel(int fmt, int64_t P, int32_t *__restrict__ cnt_nnz, int32_t *__restrict__ cnt_rows,
-                  int64_t n_rows, SpaddOut out)
+// Clears the look-back state of a call: P state words, the ticket and the status.
+__global__ void __launch_bounds__(256)
+spadd_reset_kernel(int64_t P, unsigned long long *__restrict__ tile_state,
+                   unsigned int *__restrict__ ticket, int32_t *__restrict__ status)
 {
-    __shared__ long long part_nnz[1024];
-    __shared__ long long part_rows[1024];
-    const int tid = threadIdx.x;
-    const int64_t chunk = (P + 1023) / 1024;
-    const int64_t b = (int64_t)tid * chunk < P ? (int64_t)tid * chunk : P;
-    const int64_t e = b + chunk < P ? b + chunk : P;
-    long long s_nnz = 0, s_rows = 0;
-    for (int64_t i = b; i < e; ++i) {
-        s_nnz += cnt_nnz[i];
-        if (fmt == SPADD_DCSR) s_rows += cnt_rows[i];
-    }
-    part_nnz[tid] = s_nnz;
-    part_rows[tid] = s_rows;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {          // Hillis-Steele inclusive scan
-        long long a = 0, r = 0;
-        if (tid >= o) { a = part_nnz[tid - o]; r = part_rows[tid - o]; }
-        __syncthreads();
-        part_nnz[tid] += a;
-        part_rows[tid] += r;
-        __syncthreads();
-    }
-    long long run_nnz = part_nnz[tid] - s_nnz, run_rows = part_rows[tid] - s_rows;
-    for (int64_t i = b; i < e; ++i) {
-        const int c = cnt_nnz[i];
-        cnt_nnz[i] = (int32_t)run_nnz;
-        run_nnz += c;
-        if (fmt == SPADD_DCSR) {
-            const int r = cnt_rows[i];
-            cnt_rows[i] = (int32_t)run_rows;
-            run_rows += r;
-        }
-    }
-    if (tid == 1023) {
-        const long long total_nnz = part_nnz[1023];
-        const long long total_rows = fmt == SPADD_DCSR ? part_rows[1023] : (fmt == SPADD_CSR ? n_rows : 1);
-        out.counts[0] = total_rows;
-        out.counts[1] = total_nnz;
-        const bool fits = total_nnz <= out.cap_nnz && (fmt != SPADD_DCSR || total_rows <= out.cap_rows);
-        *out.status = fits ? NACHO_OK : NACHO_ERR_CAPACITY;
-        if (fmt == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
-        if (fmt == SPADD_CSR) out.pos1[n_rows] = (int32_t)total_nnz;
-        if (fmt == SPADD_DCSR) {
-            out.pos0[0] = 0;
-            out.pos0[1] = (int32_t)total_rows;
-            if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
-        }
-    }
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < P) tile_state[i] = 0ull;
+    if (i == 0) { *ticket = 0u; *status = NACHO_OK; }
 }
 
 template <int FMT, typename T>
-void launch_pair(bool fill, const DevOperands &ops, const SpaddValues &vals, const MergePlan &plan,
-                 const int32_t *coord, const int32_t *posn, int64_t P, int32_t *cnt_nnz,
-                 int32_t *cnt_rows, const SpaddOut &out, hipStream_t s)
+void launch_one(const DevOperands &ops, const SpaddValues &vals, const MergePlan &plan, int64_t P,
+                const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
+                unsigned int *ticket, const SpaddOut &out, hipStream_t s)
 {
-    if (fill)
-        hipLaunchKernelGGL((spadd_kernel<FMT, T, true>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, s, ops,
-                           vals, plan, coord, posn, cnt_nnz, cnt_rows, out);
-    else
-        hipLaunchKernelGGL((spadd_kernel<FMT, T, false>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, s, ops,
-                           vals, plan, coord, posn, cnt_nnz, cnt_rows, out);
+    hipLaunchKernelGGL((spadd_kernel<FMT, T>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, s, ops, vals, plan,
+                       P, coord, posn, tile_state, ticket, out);
 }
 
 }  // namespace
 
 int spadd_capacity(int fmt) { return fmt == SPADD_VECTOR ? kSpaddCapVector : kSpaddCapMatrix; }
 
-hipError_t launch_spadd_pass(bool fill, int fmt, int dtype, const DevOperands &ops,
-                             const SpaddValues &vals, const MergePlan &plan, const int32_t *coord,
-                             const int32_t *posn, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows,
-                             const SpaddOut &out, hipStream_t s)
+hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, unsigned int *ticket,
+                              int32_t *status, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((P + 255) / 256);
+    hipLaunchKernelGGL(spadd_reset_kernel, dim3(grid ? grid : 1), dim3(256), 0, s, P, tile_state, ticket, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals,
+                        const MergePlan &plan, int64_t P, const int32_t *coord, const int32_t *posn,
+                        unsigned long long *tile_state, unsigned int *ticket, const SpaddOut &out,
+                        hipStream_t s)
 {
 #define NACHO_SPADD_CASE(F)                                                                          \
     if (fmt == F) {                                                                                  \
-        if (dtype == NACHO_F64) launch_pair<F, double>(fill, ops, vals, plan, coord, posn, P, cnt_nnz, cnt_rows, out, s); \
-        else launch_pair<F, float>(fill, ops, vals, plan, coord, posn, P, cnt_nnz, cnt_rows, out, s); \
+        if (dtype == NACHO_F64) launch_one<F, double>(ops, vals, plan, P, coord, posn, tile_state, ticket, out, s); \
+        else launch_one<F, float>(ops, vals, plan, P, coord, posn, tile_state, ticket, out, s);      \
     }
     NACHO_SPADD_CASE(SPADD_VECTOR)
     NACHO_SPADD_CASE(SPADD_CSR)
     NACHO_SPADD_CASE(SPADD_DCSR)
 #undef NACHO_SPADD_CASE
-    return hipGetLastError();
-}
-
-hipError_t launch_spadd_scan(int fmt, int64_t P, int32_t *cnt_nnz, int32_t *cnt_rows, int64_t n_rows,
-                             const SpaddOut &out, hipStream_t s)
-{
-    hipLaunchKernelGGL(spadd_scan_kernel, dim3(1), dim3(1024), 0, s, fmt, P, cnt_nnz, cnt_rows, n_rows, out);
     return hipGetLastError();
 }
 

@@ -121,9 +121,18 @@ spmm_fixup_kernel(T *__restrict__ C, int64_t ldc, int n, int P, const T *__restr
         break;
     }
     if (lane >= n) return;
-    T s = T(0);
-    for (int q = p; q < e; ++q) s += carry_val[(int64_t)q * NACHO_WAVE + lane];
-    C[(int64_t)r * ldc + lane] += s;
+    // eight independent partial sums keep eight carry rows in flight; the order
+    // of the additions is fixed, so the result repeats bit for bit
+    T s[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s[u] = T(0);
+    int q = p;
+    for (; q + 8 <= e; q += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s[u] += carry_val[(int64_t)(q + u) * NACHO_WAVE + lane];
+    }
+    for (; q < e; ++q) s[0] += carry_val[(int64_t)q * NACHO_WAVE + lane];
+    C[(int64_t)r * ldc + lane] += ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
 }
 
 constexpr int kGrain = 512, kRows = 512;
