@@ -34,6 +34,17 @@ __host__ __device__ inline int64_t equal_query(int64_t p, int64_t total, int64_t
 
 __device__ inline int lane_id() { return (int)(threadIdx.x & (NACHO_WAVE - 1)); }
 
+// Orders the LDS traffic of ONE wavefront: writes issued before it are visible
+// to reads of other lanes of the same wavefront issued after it.  (The LDS
+// executes a wavefront's instructions in order; this keeps the compiler from
+// moving accesses across the point.)  It does not synchronise wavefronts.
+__device__ inline void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Butterfly sum over the 64 lanes in a fixed order: every lane ends with the
 // same bits, and the same inputs always give the same result.
 template <typename T>

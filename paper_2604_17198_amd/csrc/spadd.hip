@@ -45,6 +45,7 @@ template <> struct Cap<SPADD_VECTOR> { static constexpr int value = kSpaddCapVec
 constexpr unsigned long long kStatusShift = 62;
 constexpr unsigned long long kAggregate = 1ull, kInclusive = 2ull;
 constexpr int kSpinLimit = 1 << 20;   // look-back polls before a wavefront gives up
+constexpr int kWavesPerGroup = 4;     // partitions handed out per ticket
 
 __device__ inline unsigned long long pack_state(unsigned long long status, long long rows, long long nnz)
 {
@@ -103,7 +104,7 @@ __device__ inline bool row_continues(const DevOperands &ops, const int32_t *coor
 }
 
 template <int FMT, typename T>
-__global__ void __launch_bounds__(NACHO_WAVE)
+__global__ void __launch_bounds__(kWavesPerGroup * NACHO_WAVE)
 spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
              unsigned long long *__restrict__ tile_state, unsigned int *__restrict__ ticket,
@@ -113,25 +114,38 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
     constexpr int CAP = Cap<FMT>::value;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
     constexpr int U = 8;                       // global loads in flight per lane and batch
-    __shared__ KeyT keys[2][CAP];
-    __shared__ T lval[2][CAP];
-    __shared__ int32_t rowtmp[FMT == SPADD_VECTOR ? 1 : CAP];
-    __shared__ int32_t soff[NACHO_MAX_OPERANDS + 1];
+    // every wavefront of the workgroup owns a private slice of LDS and works on
+    // its own partition; only the ticket is shared
+    __shared__ KeyT s_keys[kWavesPerGroup][2][CAP];
+    __shared__ T s_lval[kWavesPerGroup][2][CAP];
+    __shared__ int32_t s_rowtmp[kWavesPerGroup][FMT == SPADD_VECTOR ? 1 : CAP];
+    __shared__ int32_t s_soff[kWavesPerGroup][NACHO_MAX_OPERANDS + 1];
     __shared__ unsigned int s_tile;
+    __shared__ unsigned long long s_cnt[kWavesPerGroup];   // per-wavefront counts (rows<<31 | nnz)
+    __shared__ unsigned long long s_base;                  // the workgroup's exclusive prefix
 
-    const int lane = threadIdx.x;
+    const int lane = lane_id();
+    const int wave = threadIdx.x / NACHO_WAVE;
     const int k = ops.k;
-    if (lane == 0) s_tile = atomicAdd(ticket, 1u);
+    // One ticket per workgroup hands out kWavesPerGroup consecutive partitions:
+    // a partition's predecessors belong to workgroups that drew earlier tickets
+    // (or to earlier wavefronts of the same workgroup), so they are all running.
+    if (threadIdx.x == 0) s_tile = atomicAdd(ticket, 1u);
     __syncthreads();
-    const int64_t p = s_tile;                  // partitions are taken in ticket order
-    if (p >= P) return;
+    const int64_t group = s_tile;
+    const int64_t p = group * kWavesPerGroup + wave;
+    const bool active = p < P;                 // idle wavefronts of the last workgroup only keep the barriers
+    KeyT (*keys)[CAP] = s_keys[wave];
+    T (*lval)[CAP] = s_lval[wave];
+    int32_t *rowtmp = s_rowtmp[wave];
+    int32_t *soff = s_soff[wave];
 
     // ---- 1. segments of this partition --------------------------------------
     int q_lo[NACHO_MAX_OPERANDS], off[NACHO_MAX_OPERANDS + 1];
     off[0] = 0;
 #pragma unroll
     for (int t = 0; t < NACHO_MAX_OPERANDS; ++t) {
-        if (t >= k) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
+        if (t >= k || !active) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
         q_lo[t] = posn[(p * k + t) * D + (D - 1)];
         const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
         off[t + 1] = off[t] + (q_hi - q_lo[t]);
@@ -167,7 +181,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
             if (i_hi > i_max) i_hi = i_max;
             int32_t *mark = rowtmp + off[t];
             for (int i = lane; i < nt; i += NACHO_WAVE) mark[i] = 0;
-            __syncthreads();
+            wave_sync();
             if (nt > 0)
                 for (int i0 = i_lo + lane; i0 < i_hi; i0 += NACHO_WAVE * 4) {
                     int a[4], b[4], row[4];
@@ -189,7 +203,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
                         }
                     }
                 }
-            __syncthreads();
+            wave_sync();
             const int chunk = (nt + NACHO_WAVE - 1) / NACHO_WAVE;
             const int c0 = lane * chunk < nt ? lane * chunk : nt;
             const int c1 = c0 + chunk < nt ? c0 + chunk : nt;
@@ -208,7 +222,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
                 run = max(run, mark[i]);
                 mark[i] = run;
             }
-            __syncthreads();
+            wave_sync();
         }
         const int32_t *mark = rowtmp + (D == 2 ? off[t] : 0);
         for (int i0 = lane; i0 < nt; i0 += NACHO_WAVE * U) {
@@ -230,7 +244,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
             }
         }
     }
-    __syncthreads();
+    wave_sync();
 
     // ---- 2. merge tree --------------------------------------------------------
     if (!broken)
@@ -238,14 +252,14 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
             const int ob = plan.out_buf[e];
             merge_runs<KeyT, T>(keys[1 - ob], lval[1 - ob], keys[ob], lval[ob],
                                 soff[plan.a[e]], soff[plan.m[e]], soff[plan.b[e]], lane);
-            __syncthreads();
+            wave_sync();
         }
     const KeyT *mk = keys[0];
     const T *mv = lval[0];
 
     // ---- 3. assembly: count group heads and row heads ---------------------------
     bool cont = false;                 // the partition starts inside a row whose head is elsewhere
-    if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
+    if (D == 2 && active) cont = row_continues<FMT>(ops, coord, posn, p);
     int heads = 0, rheads = 0;
     for (int i0 = 0; i0 < n; i0 += NACHO_WAVE) {
         const int i = i0 + lane;
@@ -260,59 +274,79 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
         }
     }
 
-    // ---- 4. prefix sum by decoupled look-back -----------------------------------
-    long long base_rows = 0, base_nnz = 0;
-    bool gave_up = false;
-    if (p > 0) {
-        if (lane == 0)
-            __hip_atomic_store(&tile_state[p], pack_state(kAggregate, rheads, heads), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        int64_t first = p - 1;          // lane L looks at partition first - L
-        int spins = 0;
-        for (;;) {
-            const int64_t j = first - lane;
-            unsigned long long s = pack_state(kInclusive, 0, 0);     // before partition 0: nothing
-            if (j >= 0) s = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned long long st = s >> kStatusShift;
-            const unsigned long long incl = __ballot(st == kInclusive);
-            const int stop = incl ? __ffsll((long long)incl) - 1 : NACHO_WAVE;   // nearest inclusive
-            const unsigned long long need = stop >= NACHO_WAVE - 1 ? ~0ull : ((2ull << stop) - 1);
-            if (__ballot(st == 0) & need) {                // a needed predecessor has not published yet
-                if (++spins > kSpinLimit) { gave_up = true; break; }
-                __builtin_amdgcn_s_sleep(2);
-                continue;
+    // ---- 4. prefix sum: one decoupled look-back per workgroup ---------------------
+    // The wavefronts pool their counts; wavefront 0 publishes the workgroup's
+    // aggregate, walks back over earlier workgroups' state words (64 per round,
+    // nearest first) up to the nearest known inclusive prefix, and publishes its
+    // own inclusive prefix.
+    if (lane == 0) s_cnt[wave] = pack_state(0, rheads, heads);
+    __syncthreads();
+    if (wave == 0) {
+        unsigned long long tot = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerGroup; ++w) tot += s_cnt[w];
+        long long b_rows = 0, b_nnz = 0;
+        bool gave_up = false;
+        if (group > 0) {
+            if (lane == 0)
+                __hip_atomic_store(&tile_state[group], (kAggregate << kStatusShift) | tot, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            int64_t first = group - 1;      // lane L looks at workgroup first - L
+            int spins = 0;
+            for (;;) {
+                const int64_t j = first - lane;
+                unsigned long long s = pack_state(kInclusive, 0, 0);     // before workgroup 0: nothing
+                if (j >= 0) s = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long st = s >> kStatusShift;
+                const unsigned long long incl = __ballot(st == kInclusive);
+                const int stop = incl ? __ffsll((long long)incl) - 1 : NACHO_WAVE;   // nearest inclusive
+                const unsigned long long need = stop >= NACHO_WAVE - 1 ? ~0ull : ((2ull << stop) - 1);
+                if (__ballot(st == 0) & need) {            // a needed predecessor has not published yet
+                    if (++spins > kSpinLimit) { gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(8);
+                    continue;
+                }
+                const bool use = lane <= stop;
+                b_nnz += wave_sum<long long>(use ? (long long)(s & 0x7fffffffull) : 0ll);
+                b_rows += wave_sum<long long>(use ? (long long)((s >> 31) & 0x7fffffffull) : 0ll);
+                if (stop < NACHO_WAVE) break;
+                first -= NACHO_WAVE;
             }
-            const bool use = lane <= stop;
-            base_nnz += wave_sum<long long>(use ? (long long)(s & 0x7fffffffull) : 0ll);
-            base_rows += wave_sum<long long>(use ? (long long)((s >> 31) & 0x7fffffffull) : 0ll);
-            if (stop < NACHO_WAVE) break;
-            first -= NACHO_WAVE;
+        }
+        const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
+        if (lane == 0) {
+            __hip_atomic_store(&tile_state[group], pack_state(kInclusive, b_rows + t_rows, b_nnz + t_nnz),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_base = pack_state(0, b_rows, b_nnz);
+            if (gave_up) *out.status = NACHO_ERR_HIP;
+            if (group == (P + kWavesPerGroup - 1) / kWavesPerGroup - 1) {
+                // totals, tails and the capacity verdict (the only writer of these words)
+                const long long total_nnz = b_nnz + t_nnz;
+                const long long total_rows = FMT == SPADD_DCSR ? b_rows + t_rows
+                                                               : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
+                out.counts[0] = total_rows;
+                out.counts[1] = total_nnz;
+                const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
+                if (!fits) *out.status = NACHO_ERR_CAPACITY;
+                if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
+                if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
+                if (FMT == SPADD_DCSR) {
+                    out.pos0[0] = 0;
+                    out.pos0[1] = (int32_t)total_rows;
+                    if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
+                }
+            }
         }
     }
-    if (lane == 0)
-        __hip_atomic_store(&tile_state[p], pack_state(kInclusive, base_rows + rheads, base_nnz + heads),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (gave_up || broken) {
-        if (lane == 0) *out.status = gave_up ? NACHO_ERR_HIP : NACHO_ERR_INVALID_ARG;
-        if (gave_up) return;
-    }
-    if (p == P - 1 && lane == 0) {
-        // totals, tails and the capacity verdict (the only writer of these words)
-        const long long total_nnz = base_nnz + heads;
-        const long long total_rows = FMT == SPADD_DCSR ? base_rows + rheads
-                                                       : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
-        out.counts[0] = total_rows;
-        out.counts[1] = total_nnz;
-        const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
-        if (!fits) *out.status = NACHO_ERR_CAPACITY;
-        if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
-        if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
-        if (FMT == SPADD_DCSR) {
-            out.pos0[0] = 0;
-            out.pos0[1] = (int32_t)total_rows;
-            if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
-        }
-    }
+    __syncthreads();
+    unsigned long long mine = s_base;
+#pragma unroll
+    for (int w = 0; w < kWavesPerGroup; ++w)
+        if (w < wave) mine += s_cnt[w];
+    const long long base_nnz = (long long)(mine & 0x7fffffffull);
+    const long long base_rows = (long long)((mine >> 31) & 0x7fffffffull);
+    if (broken && lane == 0) *out.status = NACHO_ERR_INVALID_ARG;
+    if (!active) return;                       // no barrier below this point
 
     // ---- 5. compute: write the partition's output ------------------------------
     int hcount = 0, rcount = 0;
@@ -354,7 +388,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, MergePlan plan, int64_t P,
     if (FMT == SPADD_CSR) {
         // pos of every row that starts inside this partition: offset of the first
         // output entry whose row is not smaller
-        __syncthreads();
+        wave_sync();
         const int first = coord[p * 2] + (cont ? 1 : 0);
         const int next_first = coord[(p + 1) * 2] + (row_continues<FMT>(ops, coord, posn, p + 1) ? 1 : 0);
         for (int r = first + lane; r < next_first; r += NACHO_WAVE) {
@@ -384,8 +418,9 @@ void launch_one(const DevOperands &ops, const SpaddValues &vals, const MergePlan
                 const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
                 unsigned int *ticket, const SpaddOut &out, hipStream_t s)
 {
-    hipLaunchKernelGGL((spadd_kernel<FMT, T>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, s, ops, vals, plan,
-                       P, coord, posn, tile_state, ticket, out);
+    const unsigned grid = (unsigned)((P + kWavesPerGroup - 1) / kWavesPerGroup);
+    hipLaunchKernelGGL((spadd_kernel<FMT, T>), dim3(grid), dim3(kWavesPerGroup * NACHO_WAVE), 0, s, ops, vals,
+                       plan, P, coord, posn, tile_state, ticket, out);
 }
 
 }  // namespace
