@@ -148,35 +148,60 @@ __device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, 
     return r;
 }
 
-// Compressed level.  seg_lo/seg_hi: every operand's segment.  Requires
-// 0 <= R < total cost of the segments (an interior query), so the boundary is a
-// stored coordinate.  Invariant of the windows [l, h]: the position of the
-// boundary coordinate x in operand t lies in [l_t, h_t], and so does the
-// position of x + 1.  With that, clamping any coordinate's lower bounds into
-// the windows preserves "cost <= R  <=>  coordinate <= x".
+// Search windows of one compressed level: for operand t the boundary's position
+// lies in [l, h]; cl/ch are the costs of the entries before l / before h,
+// relative to the segment start (base = cost offset of the segment start).
+template <int K>
+struct Windows {
+    int base[K], l[K], h[K], cl[K], ch[K];
+};
+
 template <bool kLast, int K>
-__device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
-                                      const int *seg_lo, const int *seg_hi, int *p)
+__device__ inline void windows_init(const DevOperands &ops, int m, const int *seg_lo, const int *seg_hi,
+                                    Windows<K> &W)
 {
-    const int lane = lane_id();
-    const int k = ops.k;
-    int base[K], l[K], h[K], cl[K], ch[K];          // costs relative to the segment start
 #pragma unroll
     for (int t = 0; t < K; ++t) {
-        l[t] = h[t] = cl[t] = ch[t] = base[t] = 0;  // operands beyond k: empty windows, no cost
-        if (t < k) {
-            l[t] = seg_lo[t];
-            h[t] = seg_hi[t];
+        W.l[t] = W.h[t] = W.cl[t] = W.ch[t] = W.base[t] = 0;   // operands beyond k: empty, no cost
+        if (t < ops.k) {
+            W.l[t] = seg_lo[t];
+            W.h[t] = seg_hi[t];
             if (kLast) {
-                base[t] = seg_lo[t];
-                ch[t] = seg_hi[t] - seg_lo[t];
+                W.base[t] = seg_lo[t];
+                W.ch[t] = seg_hi[t] - seg_lo[t];
             } else {
                 const int32_t *pos = ops.lvl[t][m + 1].pos;
-                base[t] = pos[seg_lo[t]];
-                ch[t] = pos[seg_hi[t]] - base[t];
+                W.base[t] = pos[seg_lo[t]];
+                W.ch[t] = pos[seg_hi[t]] - W.base[t];
             }
         }
     }
+}
+
+// Compressed level.  Requires 0 <= R_lo <= R_hi < total cost of the segments
+// (interior queries), so the boundaries are stored coordinates.  Invariant of
+// the windows [l, h]: for every query R in [R_lo, R_hi] the position of its
+// boundary coordinate x in operand t lies in [l_t, h_t], and so does the
+// position of x + 1.  With that, clamping any coordinate's lower bounds into
+// the windows preserves "cost <= R  <=>  coordinate <= x".
+//   narrow_only: shrink the windows around the whole query range while that
+//                pays (used once for a group of neighbouring boundaries) and
+//                return; the result is in W.
+//   otherwise:   R_lo == R_hi; runs until the boundary is found.
+template <bool kLast, int K>
+__device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo, int64_t R_hi,
+                                      Windows<K> &W, bool narrow_only, int *p)
+{
+    const int lane = lane_id();
+    const int k = ops.k;
+    int base[K], l[K], h[K], cl[K], ch[K];
+#pragma unroll
+    for (int t = 0; t < K; ++t) {
+        base[t] = W.base[t]; l[t] = W.l[t]; h[t] = W.h[t]; cl[t] = W.cl[t]; ch[t] = W.ch[t];
+    }
+    LevelResult r;
+    r.x = 0;
+    r.c = 0;
     // position of sample j of a window (l, w): every entry when w <= 64, else 64 evenly spaced ones
     auto sample_pos = [](int lo, int w, int j) -> int {
         return lo + (w <= NACHO_WAVE ? j : (int)(((int64_t)j * w) >> 6));
@@ -192,6 +217,17 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
             mt[t] = w[t] < NACHO_WAVE ? w[t] : NACHO_WAVE;
             total += w[t];
             if (w[t] > NACHO_WAVE) all_small = false;
+        }
+        if (narrow_only && (all_small || total * 4 > prev_total)) break;   // no longer pays
+        if (!all_small && total >= prev_total) {
+            int64_t c0 = 0;
+#pragma unroll
+            for (int t = 0; t < K; ++t) c0 += cl[t];
+            return tracked_search<kLast, K>(ops, m, R_lo, base, l, h, c0, p);
+        }
+        prev_total = total;
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
             const bool valid = lane < mt[t];
             const int s = valid ? sample_pos(l[t], w[t], lane) : l[t];
             v[t] = INT32_MAX;
@@ -206,13 +242,6 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
                 }
             }
         }
-        if (!all_small && total >= prev_total) {
-            int64_t c0 = 0;
-#pragma unroll
-            for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K>(ops, m, R, base, l, h, c0, p);
-        }
-        prev_total = total;
 
         // rank of every sample of t among the samples of u: K*(K-1) binary searches
         // over the lanes, advanced in lockstep so their shuffles overlap
@@ -262,11 +291,11 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
             }
             const bool valid = lane < mt[t];
             const int64_t vv = v[t];
-            if (valid && ghi <= R && vv > best_le) best_le = vv;
-            if (valid && glo > R && vv < best_gt) best_gt = vv;
+            if (valid && ghi <= R_lo && vv > best_le) best_le = vv;
+            if (valid && glo > R_hi && vv < best_gt) best_gt = vv;
         }
-        const int64_t vminus = wave_max64(best_le);     // largest sample known not to be after the boundary
-        const int64_t vplus = wave_min64(best_gt);      // smallest sample known to be after it
+        const int64_t vminus = wave_max64(best_le);     // largest sample not after the first boundary
+        const int64_t vplus = wave_min64(best_gt);      // smallest sample after the last boundary
 
 #pragma unroll
         for (int u = 0; u < K; ++u) {
@@ -296,17 +325,17 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
             }
             l[u] = nl; cl[u] = ncl; h[u] = nh; ch[u] = nch;
         }
-        if (all_small) {
+        if (all_small && !narrow_only) {
             if (vminus < 0) {                           // cannot happen for an interior query
+                int64_t c0 = 0;
 #pragma unroll
                 for (int t = 0; t < K; ++t) {
-                    if (t < k) { l[t] = seg_lo[t]; h[t] = seg_hi[t]; }
+                    l[t] = W.l[t]; h[t] = W.h[t];
+                    c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K>(ops, m, R, base, l, h, 0, p);
+                return tracked_search<kLast, K>(ops, m, R_lo, base, l, h, c0, p);
             }
-            LevelResult r;
             r.x = vminus;
-            r.c = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) {
                 if (t < k) p[t] = l[t];
@@ -315,148 +344,203 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R,
             return r;
         }
     }
-}
-
-// One level of Algorithm 1.  On return p[t] = position of operand t's first
-// entry with coordinate >= x inside its segment.  All arguments are wave-uniform.
-template <bool kLast, int K>
-__device__ LevelResult search_level(const DevOperands &ops, int m, int64_t R,
-                                    const int *seg_lo, const int *seg_hi, int *p)
-{
-    const int k = ops.k;
-    if (ops.lvl[0][m].kind == NACHO_DENSE) return dense_search<K>(ops, m, R, p);
-
-    int64_t total = 0;
-    int nonempty = 0, which = 0;
 #pragma unroll
     for (int t = 0; t < K; ++t) {
-        if (t >= k) break;
-        if (seg_hi[t] > seg_lo[t]) { ++nonempty; which = t; }
-        if (kLast) total += seg_hi[t] - seg_lo[t];
-        else total += ops.lvl[t][m + 1].pos[seg_hi[t]] - ops.lvl[t][m + 1].pos[seg_lo[t]];
+        W.l[t] = l[t]; W.h[t] = h[t]; W.cl[t] = cl[t]; W.ch[t] = ch[t];
     }
+    return r;
+}
+
+// One level of Algorithm 1 for one query, starting from windows that bracket the
+// boundary.  `total` = cost of the level's whole segments.  On return p[t] =
+// position of operand t's first entry with coordinate >= x inside its segment.
+template <bool kLast, int K>
+__device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
+                                        const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p)
+{
+    const int k = ops.k;
+    LevelResult r;
     if (R >= total) {
         // the query reaches past this level's segments: highest coordinate is the extent
 #pragma unroll
-        for (int t = 0; t < K; ++t) {
-            if (t >= k) break;
-            p[t] = seg_hi[t];
-        }
-        LevelResult r;
+        for (int t = 0; t < K; ++t)
+            if (t < k) p[t] = seg_hi[t];
         r.x = ops.lvl[0][m].extent;
         r.c = total;
         return r;
     }
+    int nonempty = 0, which = 0;
+#pragma unroll
+    for (int t = 0; t < K; ++t)
+        if (t < k && seg_hi[t] > seg_lo[t]) { ++nonempty; which = t; }
     if (kLast && nonempty == 1) {
         // exactly one operand with a non-empty segment: the residual indexes it
 #pragma unroll
-        for (int t = 0; t < K; ++t) {
-            if (t >= k) break;
-            p[t] = seg_lo[t];
-        }
+        for (int t = 0; t < K; ++t)
+            if (t < k) p[t] = seg_lo[t];
         p[which] = seg_lo[which] + (int)R;
-        LevelResult r;
         r.x = ops.lvl[which][m].crd[p[which]];
         r.c = R;
         return r;
     }
-    return sampled_search<kLast, K>(ops, m, R, seg_lo, seg_hi, p);
+    return sampled_search<kLast, K>(ops, m, R, R, W, false, p);
 }
+
+template <bool kLast, int K>
+__device__ inline int64_t level_total(const DevOperands &ops, int m, const int *seg_lo, const int *seg_hi)
+{
+    int64_t total = 0;
+#pragma unroll
+    for (int t = 0; t < K; ++t)
+        if (t < ops.k) {
+            if (kLast) total += seg_hi[t] - seg_lo[t];
+            else total += ops.lvl[t][m + 1].pos[seg_hi[t]] - ops.lvl[t][m + 1].pos[seg_lo[t]];
+        }
+    return total;
+}
+
+constexpr int kGroup = 4;   // neighbouring boundaries one wavefront searches
 
 }  // namespace
 
+// One wavefront searches kGroup neighbouring boundaries: their searches share
+// the first rounds (the windows are narrowed once around the whole group), then
+// every boundary is finished on its own from the shared windows.
 template <int K>
 __global__ void __launch_bounds__(256)
 partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
-                 const int64_t *__restrict__ queries, int64_t total_unscaled, int32_t *__restrict__ coord, int32_t *__restrict__ posn,
-                 int64_t *__restrict__ cost)
+                 const int64_t *__restrict__ queries, int64_t total_unscaled,
+                 int32_t *__restrict__ coord, int32_t *__restrict__ posn, int64_t *__restrict__ cost)
 {
-    const int64_t b = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE;
-    if (b > P) return;                      // whole wavefront leaves together
+    const int64_t b0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE) * kGroup;
+    if (b0 > P) return;                      // whole wavefront leaves together
     const int lane = lane_id();
     const int k = ops.k, d = ops.d;
-
     const int64_t total_scaled = total_unscaled * cost_scale;
-    int64_t Q;
-    if (queries) Q = queries[b];
-    else if (grain > 0) Q = b * grain < total_scaled ? b * grain : total_scaled;
-    else Q = equal_query(b, total_scaled, P);
-    if (Q < 0) Q = 0;
-    const int64_t Qu = Q / cost_scale;
+    const bool dense0 = ops.lvl[0][0].kind == NACHO_DENSE;
 
-    int32_t *cb = coord + b * d;
-    int32_t *pb = posn + b * (int64_t)k * d;
-
-    if (b == 0 || b == P || Qu >= total_unscaled) {
-        const bool end = (b != 0);
-        if (lane == 0) {
-            for (int m = 0; m < d; ++m) cb[m] = 0;
-            if (end) cb[0] = (int32_t)ops.lvl[0][0].extent;
-            for (int t = 0; t < k; ++t)
-                for (int m = 0; m < d; ++m) {
-                    const DevLevel &L = ops.lvl[t][m];
-                    int32_t at = 0;
-                    if (end) at = (L.kind == NACHO_DENSE) ? (int32_t)L.extent : (int32_t)L.count;
-                    pb[t * d + m] = at;
-                }
-            cost[b] = end ? total_scaled : 0;
+    int64_t Qu[kGroup];
+    bool interior[kGroup];
+    int64_t q_first = -1, q_last = -1;
+#pragma unroll
+    for (int g = 0; g < kGroup; ++g) {
+        const int64_t b = b0 + g;
+        int64_t Q = 0;
+        if (b <= P) {
+            if (queries) Q = queries[b];
+            else if (grain > 0) Q = b * grain < total_scaled ? b * grain : total_scaled;
+            else Q = equal_query(b, total_scaled, P);
         }
-        return;
+        if (Q < 0) Q = 0;
+        Qu[g] = Q / cost_scale;
+        interior[g] = b > 0 && b < P && Qu[g] < total_unscaled;
+        if (interior[g]) {
+            if (q_first < 0 || Qu[g] < q_first) q_first = Qu[g];
+            if (Qu[g] > q_last) q_last = Qu[g];
+        }
     }
 
-    int seg_lo[K], seg_hi[K], p[K];
+    // level-0 segments and, for a compressed level 0, windows shared by the group
+    int seg0_lo[K], seg0_hi[K];
 #pragma unroll
     for (int t = 0; t < K; ++t) {
-        if (t >= k) break;
-        const DevLevel &L = ops.lvl[t][0];
-        seg_lo[t] = 0;
-        seg_hi[t] = (L.kind == NACHO_DENSE) ? (int)L.extent : (int)L.count;
+        seg0_lo[t] = seg0_hi[t] = 0;
+        if (t < k) {
+            const DevLevel &L = ops.lvl[t][0];
+            seg0_hi[t] = (L.kind == NACHO_DENSE) ? (int)L.extent : (int)L.count;
+        }
     }
-    int64_t R = Qu;
-    if (d == 1) {
-        LevelResult r = search_level<true, K>(ops, 0, R, seg_lo, seg_hi, p);
-        R -= r.c;
-        if (lane == 0) {
-            cb[0] = (int32_t)r.x;
-            for (int t = 0; t < k; ++t) pb[t] = p[t];
+    Windows<K> W0;
+    if (!dense0 && q_first >= 0) {
+        int dummy[K];
+        if (d == 1) {
+            windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
+            if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy);
+        } else {
+            windows_init<false, K>(ops, 0, seg0_lo, seg0_hi, W0);
+            if (q_last > q_first) sampled_search<false, K>(ops, 0, q_first, q_last, W0, true, dummy);
         }
-    } else {
-        LevelResult r0 = search_level<false, K>(ops, 0, R, seg_lo, seg_hi, p);
-        R -= r0.c;
-        const bool dense0 = ops.lvl[0][0].kind == NACHO_DENSE;
-        int p0[K];
+    }
+
+    for (int g = 0; g < kGroup; ++g) {
+        const int64_t b = b0 + g;
+        if (b > P) break;
+        int32_t *cb = coord + b * d;
+        int32_t *pb = posn + b * (int64_t)k * d;
+        if (!interior[g]) {
+            const bool end = (b != 0);
+            if (lane == 0) {
+                for (int m = 0; m < d; ++m) cb[m] = 0;
+                if (end) cb[0] = (int32_t)ops.lvl[0][0].extent;
+                for (int t = 0; t < k; ++t)
+                    for (int m = 0; m < d; ++m) {
+                        const DevLevel &L = ops.lvl[t][m];
+                        int32_t at = 0;
+                        if (end) at = (L.kind == NACHO_DENSE) ? (int32_t)L.extent : (int32_t)L.count;
+                        pb[t * d + m] = at;
+                    }
+                cost[b] = end ? total_scaled : 0;
+            }
+            continue;
+        }
+        int seg_lo[K], seg_hi[K], p[K];
+        int64_t R = Qu[g];
+        if (d == 1) {
+            Windows<K> W = W0;
+            LevelResult r = compressed_level<true, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p);
+            R -= r.c;
+            if (lane == 0) {
+                cb[0] = (int32_t)r.x;
+                for (int t = 0; t < k; ++t) pb[t] = p[t];
+            }
+        } else {
+            LevelResult r0;
+            if (dense0) r0 = dense_search<K>(ops, 0, R, p);
+            else {
+                Windows<K> W = W0;
+                r0 = compressed_level<false, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p);
+            }
+            R -= r0.c;
+            int p0[K];
 #pragma unroll
-        for (int t = 0; t < K; ++t) {
-            if (t >= k) break;
-            p0[t] = p[t];
-            const DevLevel &L0 = ops.lvl[t][0];
-            const int32_t *pos1 = ops.lvl[t][1].pos;
-            bool present;
-            if (dense0) present = r0.x < L0.extent;
-            else present = p[t] < seg_hi[t] && (int64_t)L0.crd[p[t]] == r0.x;
-            const int lo1 = pos1[p[t]];
-            seg_lo[t] = lo1;
-            seg_hi[t] = present ? pos1[p[t] + 1] : lo1;
-        }
-        LevelResult r1 = search_level<true, K>(ops, 1, R, seg_lo, seg_hi, p);
-        R -= r1.c;
-        if (lane == 0) {
-            cb[0] = (int32_t)r0.x;
-            cb[1] = (int32_t)r1.x;
-            for (int t = 0; t < k; ++t) {
-                pb[t * 2 + 0] = p0[t];
-                pb[t * 2 + 1] = p[t];
+            for (int t = 0; t < K; ++t) {
+                p0[t] = 0;
+                seg_lo[t] = seg_hi[t] = 0;
+                if (t < k) {
+                    p0[t] = p[t];
+                    const DevLevel &L0 = ops.lvl[t][0];
+                    const int32_t *pos1 = ops.lvl[t][1].pos;
+                    bool present;
+                    if (dense0) present = r0.x < L0.extent;
+                    else present = p[t] < seg0_hi[t] && (int64_t)L0.crd[p[t]] == r0.x;
+                    const int lo1 = pos1[p[t]];
+                    seg_lo[t] = lo1;
+                    seg_hi[t] = present ? pos1[p[t] + 1] : lo1;
+                }
+            }
+            Windows<K> W1;
+            windows_init<true, K>(ops, 1, seg_lo, seg_hi, W1);
+            const int64_t tot1 = level_total<true, K>(ops, 1, seg_lo, seg_hi);
+            LevelResult r1 = compressed_level<true, K>(ops, 1, R, tot1, seg_lo, seg_hi, W1, p);
+            R -= r1.c;
+            if (lane == 0) {
+                cb[0] = (int32_t)r0.x;
+                cb[1] = (int32_t)r1.x;
+                for (int t = 0; t < k; ++t) {
+                    pb[t * 2 + 0] = p0[t];
+                    pb[t * 2 + 1] = p[t];
+                }
             }
         }
+        if (lane == 0) cost[b] = (Qu[g] - R) * cost_scale;
     }
-    if (lane == 0) cost[b] = (Qu - R) * cost_scale;
 }
 
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream)
 {
-    const int64_t waves = P + 1;
+    const int64_t waves = (P + 1 + kGroup - 1) / kGroup;
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);
     // instantiated for 1, 2, 3, 4 and 8 operands so that small calls keep their state in registers
