@@ -144,8 +144,7 @@ CarryWs carve_carry(void *ws, int64_t P, int32_t dtype, int width)
 
 struct SpaddWs {
     PartsWs parts;
-    unsigned long long *tile_state;   // look-back state word per partition
-    unsigned int *ticket;             // partition hand-out counter
+    unsigned long long *tile_state;   // look-back state word per workgroup
     size_t bytes;
 };
 
@@ -154,8 +153,7 @@ SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
     Carver c(ws);
     SpaddWs w;
     w.parts = carve_parts(c, P, k, d);
-    w.tile_state = c.take<unsigned long long>((size_t)P);
-    w.ticket = c.take<unsigned int>(1);
+    w.tile_state = c.take<unsigned long long>((size_t)spadd_groups(P));
     w.bytes = align_up(c.off, 256);
     return w;
 }
@@ -175,45 +173,6 @@ int64_t fused_partitions(int32_t op, Format fmt, int32_t dtype, int32_t k, int64
     const int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
     return P > need ? P : need;
 }
-
-// Optimal tree of adjacent two-way merges for operand sizes sz[0..k): minimises
-// the number of entries moved (interval dynamic programme, k <= 8).
-struct PlanBuilder {
-    int64_t sz[NACHO_MAX_OPERANDS];
-    int64_t cost[NACHO_MAX_OPERANDS + 1][NACHO_MAX_OPERANDS + 1];
-    int split[NACHO_MAX_OPERANDS + 1][NACHO_MAX_OPERANDS + 1];
-    MergePlan plan;
-    void emit(int a, int b, int depth)
-    {
-        if (b - a == 1) { plan.leaf_buf[a] = (int8_t)(depth & 1); return; }
-        const int m = split[a][b];
-        emit(a, m, depth + 1);
-        emit(m, b, depth + 1);
-        const int e = plan.n_nodes++;
-        plan.a[e] = (int8_t)a; plan.m[e] = (int8_t)m; plan.b[e] = (int8_t)b;
-        plan.out_buf[e] = (int8_t)(depth & 1);
-    }
-    MergePlan build(int k)
-    {
-        std::memset(&plan, 0, sizeof(plan));
-        for (int a = 0; a <= k; ++a)
-            for (int b = 0; b <= k; ++b) cost[a][b] = 0;
-        for (int len = 2; len <= k; ++len)
-            for (int a = 0; a + len <= k; ++a) {
-                const int b = a + len;
-                int64_t sum = 0;
-                for (int t = a; t < b; ++t) sum += sz[t];
-                int64_t best = -1;
-                for (int m = a + 1; m < b; ++m) {
-                    const int64_t c = cost[a][m] + cost[m][b] + sum;
-                    if (best < 0 || c < best) { best = c; split[a][b] = m; }
-                }
-                cost[a][b] = best;
-            }
-        emit(0, k, 0);
-        return plan;
-    }
-};
 
 }  // namespace
 
@@ -380,13 +339,11 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
     if (rc != NACHO_OK) return rc;
     SpaddValues vals;
-    PlanBuilder pb;
     std::memset(&vals, 0, sizeof(vals));
     for (int t = 0; t < k; ++t) {
         const int64_t nt = ops[t].lvl[dev.d - 1].count;
         if (nt > 0 && !ops[t].val) return NACHO_ERR_INVALID_ARG;
         vals.v[t] = ops[t].val;
-        pb.sz[t] = nt;
     }
     if (!out->counts || !out->status || !out->pos1 || out->cap_nnz < 0 || out->cap_rows < 0)
         return NACHO_ERR_INVALID_ARG;
@@ -395,20 +352,18 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
     if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
-    const MergePlan plan = pb.build(k);
     SpaddOut o;
     o.pos0 = out->pos0; o.crd0 = out->crd0; o.pos1 = out->pos1; o.crd1 = out->crd1; o.val = out->val;
     o.cap_rows = out->cap_rows; o.cap_nnz = out->cap_nnz; o.counts = out->counts; o.status = out->status;
     const int f = spadd_fmt(fmt);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     profile_begin(s);
-    if (launch_spadd_reset(Pe, w.tile_state, w.ticket, o.status, s) != hipSuccess) return NACHO_ERR_HIP;
+    if (launch_spadd_reset(Pe, w.tile_state, o.status, s) != hipSuccess) return NACHO_ERR_HIP;
     profile_mark("spadd_reset");
     if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
-    if (launch_spadd(f, dtype, dev, vals, plan, Pe, w.parts.coord, w.parts.posn, w.tile_state, w.ticket,
-                     o, s) != hipSuccess)
+    if (launch_spadd(f, dtype, dev, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, o, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spadd_merge");
     return NACHO_OK;

@@ -35,14 +35,6 @@ constexpr int kSpaddCapVector = 1024;   // entries of all operands one wavefront
 constexpr int kSpaddCapMatrix = 1024;   // ... (CSR / DCSR: 64-bit keys)
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
-// Tree of stable two-way merges over adjacent operands, children before parents.
-// Node e merges operands [a, m) with [m, b) from buffer 1 - out_buf into out_buf;
-// operand t is staged in buffer leaf_buf[t]; the root writes buffer 0.
-struct MergePlan {
-    int32_t n_nodes;
-    int8_t a[NACHO_MAX_OPERANDS], m[NACHO_MAX_OPERANDS], b[NACHO_MAX_OPERANDS];
-    int8_t out_buf[NACHO_MAX_OPERANDS], leaf_buf[NACHO_MAX_OPERANDS];
-};
 struct SpaddOut {
     int32_t *pos0, *crd0, *pos1, *crd1;
     void *val;
@@ -51,13 +43,13 @@ struct SpaddOut {
     int32_t *status;
 };
 int spadd_capacity(int fmt);
-// Clears the per-call look-back state (P state words, ticket) and the status word.
-hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, unsigned int *ticket,
-                              int32_t *status, hipStream_t s);
+// Workgroups (look-back state words) a call with P partitions uses.
+int64_t spadd_groups(int64_t P);
+// Clears the per-call look-back state (one state word per workgroup) and the status word.
+hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s);
 // Count, look-back prefix sum and fill in one kernel, one wavefront per partition.
-hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals,
-                        const MergePlan &plan, int64_t P, const int32_t *coord, const int32_t *posn,
-                        unsigned long long *tile_state, unsigned int *ticket, const SpaddOut &out,
-                        hipStream_t s);
+hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
+                        const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
+                        const SpaddOut &out, hipStream_t s);
 
 }  // namespace nacho
