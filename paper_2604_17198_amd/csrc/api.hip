@@ -144,7 +144,7 @@ CarryWs carve_carry(void *ws, int64_t P, int32_t dtype, int width)
 
 struct SpaddWs {
     PartsWs parts;
-    unsigned long long *tile_state;   // look-back state word per workgroup
+    unsigned long long *tile_state;   // prefix-sum state of the call
     size_t bytes;
 };
 
@@ -153,7 +153,7 @@ SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
     Carver c(ws);
     SpaddWs w;
     w.parts = carve_parts(c, P, k, d);
-    w.tile_state = c.take<unsigned long long>((size_t)spadd_groups(P));
+    w.tile_state = c.take<unsigned long long>((size_t)spadd_state_words(P));
     w.bytes = align_up(c.off, 256);
     return w;
 }

@@ -43,11 +43,11 @@ struct SpaddOut {
     int32_t *status;
 };
 int spadd_capacity(int fmt);
-// Workgroups (look-back state words) a call with P partitions uses.
-int64_t spadd_groups(int64_t P);
-// Clears the per-call look-back state (one state word per workgroup) and the status word.
+// 64-bit words of prefix-sum state a call with P partitions uses.
+int64_t spadd_state_words(int64_t P);
+// Clears the per-call prefix-sum state and the status word.
 hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s);
-// Count, look-back prefix sum and fill in one kernel, one wavefront per partition.
+// Count, prefix sum and fill in one kernel, one wavefront per partition.
 hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
                         const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
                         const SpaddOut &out, hipStream_t s);

@@ -24,25 +24,32 @@
 //      the larger run the number of smaller-run entries before it.  An entry
 //      that meets an equal key in an operand with a smaller index is flagged as
 //      a duplicate.  Own position + searched positions + summed marks = the
-//      entry's slot in the merged order; a 16-bit descriptor (run, position in
-//      the run, duplicate flag) is scattered to that slot;
+//      entry's slot in the merged order; a 16-bit descriptor (position in the
+//      runs, duplicate flag) is scattered to that slot;
 //   3. assembly: walks the merged order; a slot that is not a duplicate is the
 //      HEAD of its coordinate.  The number of heads is the partition's output
 //      count (and a head whose predecessor lies in another row starts a row);
+//      every slot keeps the number of heads (and row heads) before it;
 //   4. prefix sum: publishes its counts and adds up the counts of all earlier
 //      partitions with a decoupled look-back over a state word per workgroup;
-//   5. compute: walks the merged order again and writes, for every head,
-//      coordinate and value (its own value plus the duplicates that follow it,
-//      i.e. in operand order) at offset + rank, and the hierarchical arrays
-//      (crd0/pos1 of a DCSR result, pos of a CSR result) for the rows whose
-//      first output entry the partition owns -- exactly one writer per row.
+//      the loads of the values are in flight meanwhile;
+//   5. compute: every lane goes back to its own entries (coordinates and values
+//      are in its registers).  A head writes coordinate and value at offset +
+//      heads before its slot; its value is its own plus the duplicates in the
+//      slots that follow it, i.e. in operand order (duplicates hand their
+//      values over through LDS).  The hierarchical arrays (crd0/pos1 of a DCSR
+//      result, pos of a CSR result) are written for the rows whose first
+//      output entry the partition owns -- exactly one writer per row.
+// Every loop over a partition's entries is unrolled over the 16 entries of a
+// lane, so that the LDS and global accesses of a stage are in flight together.
 // What differs from the paper's three kernels: the inputs are read once instead
 // of twice and there is no separate scan launch; the arithmetic is the same.
 //
-// The grid is persistent: at most as many workgroups as the device can hold at
-// once, workgroup b taking groups b, b + grid, b + 2 grid, ...  Every group a
-// look-back waits for is therefore owned by a resident workgroup that reaches it
-// before anything later, so the waits end without an atomic hand-out of work.
+// Workgroup g handles partitions g * W .. g * W + W - 1 and waits, in its
+// look-back, only for workgroups with a smaller index.  Workgroups are handed
+// to every XCD in index order, so the unfinished workgroup with the smallest
+// index is always running and waits for nobody: the waits end.  (Every wait is
+// bounded all the same; a wavefront that gives up reports NACHO_ERR_HIP.)
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -56,16 +63,24 @@ template <> struct KeyOf<SPADD_VECTOR> { typedef uint32_t type; };
 template <int FMT> struct Cap { static constexpr int value = kSpaddCapMatrix; };
 template <> struct Cap<SPADD_VECTOR> { static constexpr int value = kSpaddCapVector; };
 
-// state word of a workgroup: bits 63..62 status, 61..31 rows, 30..0 nnz
-constexpr unsigned long long kStatusShift = 62;
-constexpr unsigned long long kAggregate = 1ull, kInclusive = 2ull;
-constexpr int kSpinLimit = 1 << 20;   // look-back polls before a wavefront gives up
-constexpr int kWavesPerGroup = 4;     // partitions per workgroup (one look-back for all of them)
-constexpr int kLook = 8;              // predecessors a lane examines per look-back round
+// Prefix sum over the workgroups' counts, two levels and no chains: a workgroup
+// publishes the counts of its partitions in a 32-bit word; the last workgroup
+// of every chunk of kChunk workgroups also publishes the chunk's total.  The
+// offset of a workgroup is the sum of the totals of the chunks before its own
+// plus the sum of the words of the workgroups before it in its chunk: all of
+// them plain reads of words that their owners publish without waiting for
+// anybody (a word) or after one such wait (a total).
+//   word:  bit 31 published, bits 14..27 rows, bits 0..13 nnz
+//   total: bit 63 published, bits 31..61 rows, bits 0..30 nnz
+constexpr int kChunk = 512;           // workgroups per chunk
+constexpr int kSpinLimit = 1 << 20;   // polls before a wavefront gives up
+constexpr int kWavesPerGroup = 2;     // partitions per workgroup (one prefix look-up for all of them)
+constexpr unsigned kWordValid = 0x80000000u;
+constexpr unsigned long long kTotalValid = 1ull << 63;
 
-__device__ inline unsigned long long pack_state(unsigned long long status, long long rows, long long nnz)
+__device__ inline unsigned long long pack_counts(long long rows, long long nnz)
 {
-    return (status << kStatusShift) | ((unsigned long long)rows << 31) | (unsigned long long)nnz;
+    return ((unsigned long long)rows << 31) | (unsigned long long)nnz;
 }
 
 __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -95,14 +110,27 @@ constexpr int kPadShift = 4;    // one unused word after every 16: a lane's 16 c
 template <int CAP> struct Padded { static constexpr int value = CAP + (CAP >> kPadShift); };
 __device__ inline int pad(int x) { return x + (x >> kPadShift); }
 
-template <typename KeyT, int CAP>
+// Word of an entry in `marks` while the ranks are formed:
+//   bits  0..15  marks left at this entry by smaller runs (then their prefix sum)
+//   bits 16..19  number of equal keys met in operands with a smaller index (> 0: duplicate)
+//   bits 20..30  sum of the positions this entry found in larger runs
+constexpr int kDupShift = 16, kDirectShift = 20;
+// Word of a merged slot in `marks` after the assembly:
+//   bits 0..15 heads before the slot, 16..30 row heads before it, 31 the slot starts a row
+template <typename KeyT, typename T, int CAP>
 struct WaveTile {
-    KeyT keys[CAP];                       // the k runs, one after the other
-    int32_t marks[Padded<CAP>::value];    // staging: row markers; then marks -> their prefix sum; then heads before a slot
-    uint16_t direct[CAP];                 // searched positions of an entry (bits 0..14) | duplicate (bit 15)
-    uint16_t info[CAP];                   // merged order: position in keys (0..9) | run (11..13) | duplicate (15)
-    unsigned long long sval[NACHO_MAX_OPERANDS];   // address of the value of run t's first entry
+    union {
+        KeyT keys[CAP];                   // the k runs, one after the other
+        T dupval[sizeof(T) <= sizeof(KeyT) ? CAP : 1];   // later: values of duplicates by merged slot
+    };
+    T dupval_wide[sizeof(T) <= sizeof(KeyT) ? 1 : CAP];
+    int32_t marks[Padded<CAP>::value];    // staging: row markers; ranking words (padded); assembly words
+    uint16_t info[CAP];                   // merged order: position in keys (0..9) | duplicate (15)
+    unsigned long long scrd[NACHO_MAX_OPERANDS];   // address of crd of run t, biased so that [c] is entry c of keys
+    unsigned long long sval[NACHO_MAX_OPERANDS];   // the same for the values
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
+    int32_t srun[NACHO_MAX_OPERANDS];              // start of run t | marks summed before it << 16
+    __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
 };
 static_assert(kSpaddCapVector <= 1024 && kSpaddCapMatrix <= 1024, "info packs a 10-bit position");
 
@@ -157,35 +185,33 @@ __device__ inline void rank_blocks(Tile &w, int k, int t, int r0, int lane)
             const int eq = (lb[i] < nu && at == key[i]) ? 1 : 0;
             if (u < t) {
                 // run u wins ties: its equal entry precedes this one, which is a duplicate
-                direct[i] += lb[i] + eq;
-                direct[i] |= eq << 15;
+                direct[i] += ((lb[i] + eq) << kDirectShift) + (eq << kDupShift);
                 if (valid[i] && lb[i] + eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + eq)], 1);
             } else {
                 // this entry precedes u's entries from position lb on; an equal one there is a duplicate
-                direct[i] += lb[i];
-                if (valid[i] && lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1 + (eq << 16));
+                direct[i] += lb[i] << kDirectShift;
+                if (valid[i] && lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1 + (eq << kDupShift));
             }
         }
     }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int il = r0 + i * NACHO_WAVE + lane;
-        if (valid[i]) w.direct[off_t + il] = (uint16_t)direct[i];
+        if (valid[i]) atomicAdd(&w.marks[pad(off_t + il)], direct[i]);
     }
 }
 
-template <int FMT, typename T>
+template <int FMT, typename T, int K>
 __global__ void __launch_bounds__(kWavesPerGroup * NACHO_WAVE)
-spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
+spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
              unsigned long long *__restrict__ tile_state, SpaddOut out)
 {
     typedef typename KeyOf<FMT>::type KeyT;
     constexpr int CAP = Cap<FMT>::value;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
-    constexpr int U = 8;                       // global loads in flight per lane and batch
-    constexpr int PER_LANE = CAP / NACHO_WAVE; // consecutive entries a lane scans
-    typedef WaveTile<KeyT, CAP> Tile;
+    constexpr int R = CAP / NACHO_WAVE;        // entries of a lane: c = r * 64 + lane, r < R
+    typedef WaveTile<KeyT, T, CAP> Tile;
     // every wavefront of the workgroup owns a private slice of LDS and works on
     // its own partition; only the look-back is shared
     __shared__ Tile s_tile[kWavesPerGroup];
@@ -194,125 +220,144 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
 
     const int lane = lane_id();
     const int wave = threadIdx.x / NACHO_WAVE;
-    const int k = ops.k;
+    const int k = ops.k;                       // <= K
     const unsigned long long below = (1ull << lane) - 1ull;
     Tile &w = s_tile[wave];
     KeyT *keys = w.keys;
-    int parity = 0;
+    constexpr int parity = 0;
 
-    for (int64_t group = blockIdx.x; group < n_groups; group += gridDim.x, parity ^= 1) {
+    {
+        const int64_t group = blockIdx.x;
         const int64_t p = group * kWavesPerGroup + wave;
         const bool active = p < P;             // idle wavefronts of the last workgroup only keep the barriers
 
         // ---- 1. segments of this partition ----------------------------------
-        int q_lo[NACHO_MAX_OPERANDS], off[NACHO_MAX_OPERANDS + 1];
+        int q_lo[K], off[K + 1];
         off[0] = 0;
 #pragma unroll
-        for (int t = 0; t < NACHO_MAX_OPERANDS; ++t) {
+        for (int t = 0; t < K; ++t) {
             if (t >= k || !active) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
             q_lo[t] = posn[(p * k + t) * D + (D - 1)];
             const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
             off[t + 1] = off[t] + (q_hi - q_lo[t]);
         }
-        int n = off[NACHO_MAX_OPERANDS];       // <= CAP by the host's choice of the partition count
+        int n = off[K];                        // <= CAP by the host's choice of the partition count
         // Only an operand that violates its preconditions (unsorted or repeated
         // coordinates) can overflow the staging buffer: such a partition contributes
         // nothing and the call reports INVALID_ARG, but the look-back chain goes on.
         bool broken = n > CAP || n < 0;
 #pragma unroll
-        for (int t = 0; t < NACHO_MAX_OPERANDS; ++t) broken = broken || off[t + 1] < off[t];
+        for (int t = 0; t < K; ++t) broken = broken || off[t + 1] < off[t];
         if (broken) {
             n = 0;
 #pragma unroll
-            for (int t = 0; t <= NACHO_MAX_OPERANDS; ++t) off[t] = 0;
+            for (int t = 0; t <= K; ++t) off[t] = 0;
         }
         wave_sync();                           // the previous partition's LDS reads are done
 #pragma unroll
-        for (int t = 0; t <= NACHO_MAX_OPERANDS; ++t) {
+        for (int t = 0; t <= K; ++t) {
             if (lane == 0) {
                 w.soff[t] = off[t];
-                if (t < NACHO_MAX_OPERANDS)
-                    w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t]);
+                if (t < K) {
+                    const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
+                    w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
+                    w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
+                }
             }
         }
+        wave_sync();
 
+        // run and column of every entry of this lane
+        int tr[R], col[R];
 #pragma unroll
-        for (int t = 0; t < NACHO_MAX_OPERANDS; ++t) {
-            if (t >= k) break;
-            const int nt = off[t + 1] - off[t];
-            const int32_t *crd = ops.lvl[t][D - 1].crd + q_lo[t];
-            KeyT *kb = keys + off[t];
-            if (D == 2) {
-                // rows overlapping [q_lo, q_hi): mark each row's first entry, then a running maximum
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            int t = 0;
+#pragma unroll
+            for (int u = 1; u < K; ++u) t += c >= off[u] ? 1 : 0;
+            tr[r] = t;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            col[r] = 0;
+            if (c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c];
+        }
+
+        uint32_t row[D == 2 ? R : 1];
+        if (D == 2) {
+            // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
+            // (word of the entry in marks), then hand every entry the latest marker
+            // at or before it.  The first entry of every run carries a marker, so no
+            // row leaks from one run into the next.
+            for (int i = lane; i < Padded<CAP>::value; i += NACHO_WAVE) w.marks[i] = 0;
+            wave_sync();
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                if (t >= k) break;
+                const int nt = off[t + 1] - off[t];
+                if (nt == 0) continue;
                 const int32_t *pos1 = ops.lvl[t][1].pos;
                 const int32_t *crd0 = ops.lvl[t][0].crd;
                 const int ql = q_lo[t], qh = ql + nt;
-                int32_t *mark = w.marks + off[t];
-                for (int i = lane; i < nt; i += NACHO_WAVE) mark[i] = 0;
-                wave_sync();
-                if (nt > 0) {
-                    const int i_lo = posn[(p * k + t) * 2 + 0];
-                    int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
-                    const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
-                    if (i_hi > i_max) i_hi = i_max;
-                    for (int i0 = i_lo + lane; i0 < i_hi; i0 += NACHO_WAVE * 4) {
-                        int a[4], b[4], row[4];
+                const int i_lo = posn[(p * k + t) * 2 + 0];
+                int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
+                const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
+                if (i_hi > i_max) i_hi = i_max;
+                for (int i0 = i_lo + lane; i0 < i_hi; i0 += NACHO_WAVE * 4) {
+                    int a[4], b[4], rw[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int i = i0 + u * NACHO_WAVE;
-                            if (i < i_hi) {
-                                a[u] = pos1[i];
-                                b[u] = pos1[i + 1];
-                                row[u] = FMT == SPADD_CSR ? i : crd0[i];
-                            }
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * NACHO_WAVE;
+                        if (i < i_hi) {
+                            a[u] = pos1[i];
+                            b[u] = pos1[i + 1];
+                            rw[u] = FMT == SPADD_CSR ? i : crd0[i];
                         }
+                    }
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int i = i0 + u * NACHO_WAVE;
-                            if (i < i_hi) {
-                                const int s = a[u] > ql ? a[u] : ql;
-                                if (b[u] > s && s < qh) mark[s - ql] = row[u] + 1;
-                            }
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * NACHO_WAVE;
+                        if (i < i_hi) {
+                            const int s = a[u] > ql ? a[u] : ql;
+                            if (b[u] > s && s < qh) w.marks[pad(off[t] + s - ql)] = rw[u] + 1;
                         }
                     }
                 }
-                wave_sync();
-                const int chunk = (nt + NACHO_WAVE - 1) / NACHO_WAVE;
-                const int c0 = lane * chunk < nt ? lane * chunk : nt;
-                const int c1 = c0 + chunk < nt ? c0 + chunk : nt;
-                int run = 0;
-                for (int i = c0; i < c1; ++i) run = max(run, mark[i]);
-                int incl = run;                           // inclusive running maximum over lanes
+            }
+            wave_sync();
+            {
+                int v[R], cur = 0;
+                const int at = lane * (R + (R >> kPadShift));
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    v[j] = w.marks[at + j];
+                    cur = v[j] ? v[j] : cur;
+                }
+                int incl = cur;                           // latest marker up to the end of this lane's words
 #pragma unroll
                 for (int o = 1; o < NACHO_WAVE; o <<= 1) {
-                    const int v = __shfl_up(incl, o, NACHO_WAVE);
-                    if (lane >= o) incl = max(incl, v);
+                    const int left = __shfl_up(incl, o, NACHO_WAVE);
+                    if (lane >= o && incl == 0) incl = left;
                 }
-                int before = __shfl_up(incl, 1, NACHO_WAVE);
-                if (lane == 0) before = 0;
-                run = before;
-                for (int i = c0; i < c1; ++i) {
-                    run = max(run, mark[i]);
-                    mark[i] = run;
+                cur = __shfl_up(incl, 1, NACHO_WAVE);
+                if (lane == 0) cur = 0;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    cur = v[j] ? v[j] : cur;
+                    w.marks[at + j] = cur;
                 }
-                wave_sync();
             }
-            const int32_t *mark = w.marks + (D == 2 ? off[t] : 0);
-            for (int i0 = lane; i0 < nt; i0 += NACHO_WAVE * U) {
-                int c[U];
+            wave_sync();
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * NACHO_WAVE;
-                    if (i < nt) c[u] = crd[i];
-                }
+            for (int r = 0; r < R; ++r) row[r] = (uint32_t)(w.marks[pad(r * NACHO_WAVE + lane)] - 1);
+        }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * NACHO_WAVE;
-                    if (i < nt) {
-                        if (D == 1) kb[i] = (KeyT)(uint32_t)c[u];
-                        else kb[i] = (KeyT)(((uint64_t)(uint32_t)(mark[i] - 1) << 32) | (uint32_t)c[u]);
-                    }
-                }
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            if (c < n) {
+                if (D == 1) keys[c] = (KeyT)(uint32_t)col[r];
+                else keys[c] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
             }
         }
         wave_sync();
@@ -321,9 +366,10 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
         for (int i = lane; i < Padded<CAP>::value; i += NACHO_WAVE) w.marks[i] = 0;
         wave_sync();
         int n_max = 0, t_max = 0;              // the largest run searches nothing
-        for (int t = 0; t < k; ++t) {
-            const int nt = uni(w.soff[t + 1]) - uni(w.soff[t]);
-            if (t == 0 || larger_run(nt, t, n_max, t_max)) { n_max = nt; t_max = t; }
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
+            const int nt = off[t + 1] - off[t];
+            if (t == 0 || (t < k && larger_run(nt, t, n_max, t_max))) { n_max = nt; t_max = t; }
         }
         for (int t = 0; t < k; ++t) {
             if (t == t_max) continue;
@@ -334,61 +380,85 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
         }
         wave_sync();
         {
-            // inclusive prefix sum of the marks (low halves) over all runs at once; a
-            // lane owns PER_LANE consecutive words, the flags in the high halves stay
-            int v[PER_LANE], sum = 0;
-            const int at = lane * (PER_LANE + (PER_LANE >> kPadShift));
+            // inclusive prefix sum of the marks (bits 0..15) over all runs at once; a
+            // lane owns R consecutive words, the other bits stay
+            int v[R], sum = 0;
+            const int at = lane * (R + (R >> kPadShift));
 #pragma unroll
-            for (int j = 0; j < PER_LANE; ++j) {
+            for (int j = 0; j < R; ++j) {
                 v[j] = w.marks[at + j];
                 sum += v[j] & 0xffff;
             }
             int run = wave_inclusive_scan(sum) - sum;
 #pragma unroll
-            for (int j = 0; j < PER_LANE; ++j) {
+            for (int j = 0; j < R; ++j) {
                 run += v[j] & 0xffff;
                 w.marks[at + j] = (v[j] & 0xffff0000) | run;
             }
         }
         wave_sync();
-        for (int t = 0; t < k; ++t) {
-            const int off_t = uni(w.soff[t]), nt = uni(w.soff[t + 1]) - off_t;
-            const int before_run = off_t > 0 ? (w.marks[pad(off_t - 1)] & 0xffff) : 0;
-            for (int il = lane; il < nt; il += NACHO_WAVE) {
-                const int c = off_t + il;
-                const int mk = w.marks[pad(c)];
-                const int d = t == t_max ? 0 : (int)w.direct[c];
-                const int slot = il + (d & 0x7fff) + ((mk & 0xffff) - before_run);
-                const int dup = ((d >> 15) | ((unsigned)mk >> 16)) != 0 ? 1 : 0;
-                w.info[slot] = (uint16_t)(c | (t << 11) | (dup << 15));
-            }
+        if (lane < K) {
+            const int o = w.soff[lane];
+            w.srun[lane] = o | ((o > 0 ? (w.marks[pad(o - 1)] & 0xffff) : 0) << 16);
+        }
+        wave_sync();
+        int slot[R];                           // merged slot | duplicate << 15
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            const int mk = w.marks[pad(c)];
+            const int sr = w.srun[tr[r]];
+            const int m = (c - (sr & 0xffff)) + ((mk >> kDirectShift) & 0x7ff) + ((mk & 0xffff) - (sr >> 16));
+            const int dup = ((mk >> kDupShift) & 0xf) ? 0x8000 : 0;
+            slot[r] = m | dup;
+        }
+        wave_sync();                           // all ranking words are read: the assembly may overwrite them
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            if (c < n) w.info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
         }
         wave_sync();
 
-        // ---- 3. assembly: count heads and row heads -------------------------------------
+        // ---- 3. assembly: heads and row heads before every merged slot ------------------
         bool cont = false;                 // the partition starts inside a row whose head is elsewhere
         if (D == 2 && active) cont = row_continues<FMT>(ops, coord, posn, p);
         int heads = 0, rheads = 0;
-        for (int i0 = 0; i0 < n; i0 += NACHO_WAVE) {
-            const int i = i0 + lane;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = r * NACHO_WAVE + lane;
+            if (r * NACHO_WAVE >= n) break;
             const bool valid = i < n;
             const int inf = valid ? (int)w.info[i] : 0x8000;
             const bool head = !(inf >> 15);
-            heads += __popcll(__ballot(head));
+            const unsigned long long hm = __ballot(head);
+            int word = heads + __popcll(hm & below);
+            heads += __popcll(hm);
             if (FMT == SPADD_DCSR) {
-                const uint32_t row = row_of(keys[inf & 1023]);
+                const uint32_t rw = row_of(keys[inf & 1023]);
                 const uint32_t prow = (valid && i > 0) ? row_of(keys[w.info[i - 1] & 1023]) : 0u;
-                const bool rhead = head && (i == 0 ? !cont : row != prow);
-                rheads += __popcll(__ballot(rhead));
+                const bool rhead = head && (i == 0 ? !cont : rw != prow);
+                const unsigned long long rm = __ballot(rhead);
+                word |= (rheads + __popcll(rm & below)) << 16;
+                word |= rhead ? (int)0x80000000 : 0;
+                rheads += __popcll(rm);
             }
+            if (valid) w.marks[i] = word;
         }
 
-        // ---- 4. prefix sum: one decoupled look-back per workgroup ------------------
-        // The wavefronts pool their counts; wavefront 0 publishes the workgroup's
-        // aggregate, walks back over earlier workgroups' state words (64 per round,
-        // nearest first) up to the nearest known inclusive prefix, and publishes its
-        // own inclusive prefix.
-        if (lane == 0) s_cnt[parity][wave] = pack_state(0, rheads, heads);
+        // the values of this lane's entries: in flight during the look-back
+        T val[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            val[r] = T(0);
+            if (c < n) val[r] = reinterpret_cast<const T *>((uintptr_t)w.sval[tr[r]])[c];
+        }
+
+        // ---- 4. prefix sum over the workgroups ------------------------------------
+        // The wavefronts pool their counts; wavefront 0 publishes them and reads the
+        // counts of everything before the workgroup.
+        if (lane == 0) s_cnt[parity][wave] = pack_counts(rheads, heads);
         __syncthreads();
         if (wave == 0) {
             unsigned long long tot = 0;
@@ -396,58 +466,69 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
             for (int ww = 0; ww < kWavesPerGroup; ++ww) tot += s_cnt[parity][ww];
             long long b_rows = 0, b_nnz = 0;
             bool gave_up = false;
-            if (group > 0) {
-                if (lane == 0)
-                    __hip_atomic_store(&tile_state[group], (kAggregate << kStatusShift) | tot, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                // Every round looks at the kLook * 64 nearest predecessors not yet summed,
-                // lane L at the kLook consecutive ones from first - L * kLook downwards,
-                // all loads in flight together: when many workgroups start at the same
-                // time none of them has an inclusive prefix to offer, and the sum has to
-                // reach far back.
-                int64_t first = group - 1;
+            const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
+            unsigned long long *totals = tile_state;                                        // one per chunk
+            unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
+            if (lane == 0)
+                __hip_atomic_store(&words[group], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int64_t chunk = group / kChunk, c0 = chunk * kChunk;
+            {
+                // words of the workgroups before this one in its chunk, all loads in flight together
+                const int m = (int)(group - c0);
                 int spins = 0;
                 for (;;) {
-                    unsigned long long s[kLook];
+                    unsigned v[kChunk / NACHO_WAVE];
+                    bool missing = false;
 #pragma unroll
-                    for (int j = 0; j < kLook; ++j) {
-                        const int64_t g = first - ((int64_t)lane * kLook + j);
-                        s[j] = pack_state(kInclusive, 0, 0);                 // before group 0: nothing
-                        if (g >= 0) s[j] = __hip_atomic_load(&tile_state[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+                        const int j = i * NACHO_WAVE + lane;
+                        v[i] = kWordValid;
+                        if (i * NACHO_WAVE < m && j < m)
+                            v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-                    // per lane: states up to and including its nearest inclusive one
-                    long long l_nnz = 0, l_rows = 0;
-                    bool l_incl = false, l_missing = false;
+                    int l_nnz = 0, l_rows = 0;
 #pragma unroll
-                    for (int j = 0; j < kLook; ++j) {
-                        const unsigned long long st = s[j] >> kStatusShift;
-                        if (!l_incl) {
-                            if (st == 0) l_missing = true;
-                            l_nnz += (long long)(s[j] & 0x7fffffffull);
-                            l_rows += (long long)((s[j] >> 31) & 0x7fffffffull);
-                            if (st == kInclusive) l_incl = true;
-                        }
+                    for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+                        missing = missing || !(v[i] & kWordValid);
+                        l_nnz += (int)(v[i] & 0x3fffu);
+                        l_rows += (int)((v[i] >> 14) & 0x3fffu);
                     }
-                    const unsigned long long incl = __ballot(l_incl);
-                    const int stop = incl ? __ffsll((long long)incl) - 1 : NACHO_WAVE;   // lane of the nearest inclusive
-                    const unsigned long long need = stop >= NACHO_WAVE - 1 ? ~0ull : ((2ull << stop) - 1);
-                    if (__ballot(l_missing) & need) {          // a needed predecessor has not published yet
+                    if (__ballot(missing)) {                   // a predecessor has not published yet
                         if (++spins > kSpinLimit) { gave_up = true; break; }
-                        __builtin_amdgcn_s_sleep(4);
+                        __builtin_amdgcn_s_sleep(16);
                         continue;
                     }
-                    const bool use = lane <= stop;
-                    b_nnz += wave_sum<long long>(use ? l_nnz : 0ll);
-                    b_rows += wave_sum<long long>(use ? l_rows : 0ll);
-                    if (stop < NACHO_WAVE) break;
-                    first -= NACHO_WAVE * kLook;
+                    b_nnz = wave_sum<int>(l_nnz);
+                    b_rows = wave_sum<int>(l_rows);
+                    break;
                 }
             }
-            const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
-            if (lane == 0) {
-                __hip_atomic_store(&tile_state[group], pack_state(kInclusive, b_rows + t_rows, b_nnz + t_nnz),
+            if (!gave_up && (group == c0 + kChunk - 1 || group == n_groups - 1) && lane == 0)
+                __hip_atomic_store(&totals[chunk], kTotalValid | pack_counts(b_rows + t_rows, b_nnz + t_nnz),
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_base[parity] = pack_state(0, b_rows, b_nnz);
+            if (!gave_up && chunk > 0) {
+                // totals of the chunks before this one
+                int spins = 0;
+                long long c_nnz = 0, c_rows = 0;
+                for (int64_t first = 0; first < chunk && !gave_up; ) {
+                    const int64_t j = first + lane;
+                    unsigned long long s = kTotalValid;
+                    if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (__ballot(!(s & kTotalValid))) {
+                        if (++spins > kSpinLimit) { gave_up = true; break; }
+                        __builtin_amdgcn_s_sleep(16);
+                        continue;
+                    }
+                    c_nnz += wave_sum<long long>((long long)(s & 0x7fffffffull));
+                    c_rows += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
+                    first += NACHO_WAVE;
+                }
+                b_nnz += c_nnz;
+                b_rows += c_rows;
+            }
+            if (lane == 0) {
+                s_base[parity] = pack_counts(b_rows, b_nnz);
                 if (gave_up) *out.status = NACHO_ERR_HIP;
                 if (group == n_groups - 1) {
                     // totals, tails and the capacity verdict (the only writer of these words)
@@ -476,123 +557,106 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups,
         const long long base_nnz = (long long)(mine & 0x7fffffffull);
         const long long base_rows = (long long)((mine >> 31) & 0x7fffffffull);
         if (broken && lane == 0) *out.status = NACHO_ERR_INVALID_ARG;
-        if (!active) continue;
+        if (!active) return;
 
         // ---- 5. compute: write the partition's output ------------------------------
-        int hcount = 0, rcount = 0;
-        for (int i0 = 0; i0 < n; i0 += NACHO_WAVE) {
-            const int i = i0 + lane;
-            const bool valid = i < n;
-            const int inf = valid ? (int)w.info[i] : 0x8000;
-            const bool head = !(inf >> 15);
-            const unsigned long long hm = __ballot(head);
-            const int j = hcount + __popcll(hm & below);
-            const KeyT key = keys[inf & 1023];
-            bool rhead = false;
-            int jr = 0;
-            if (FMT == SPADD_DCSR) {
-                const uint32_t prow = (valid && i > 0) ? row_of(keys[w.info[i - 1] & 1023]) : 0u;
-                rhead = head && (i == 0 ? !cont : row_of(key) != prow);
-                const unsigned long long rm = __ballot(rhead);
-                jr = rcount + __popcll(rm & below);
-                rcount += __popcll(rm);
-            }
-            if (FMT == SPADD_CSR && valid) w.marks[i] = j;      // heads before slot i
-            if (head) {
-                // the head's own value, then its duplicates in merged (= operand) order
-                const int t = (inf >> 11) & 7;
-                T sum = reinterpret_cast<const T *>((uintptr_t)w.sval[t])[(inf & 1023) - w.soff[t]];
-                for (int g = i + 1; g < n; ++g) {
-                    const int ig = w.info[g];
-                    if (!(ig >> 15)) break;
-                    const int tg = (ig >> 11) & 7;
-                    sum += reinterpret_cast<const T *>((uintptr_t)w.sval[tg])[(ig & 1023) - w.soff[tg]];
-                }
-                const long long wpos = base_nnz + j;
-                if (wpos < out.cap_nnz) {
-                    out.crd1[wpos] = (int32_t)(uint32_t)key;
-                    static_cast<T *>(out.val)[wpos] = sum;
-                }
-                if (FMT == SPADD_DCSR && rhead) {
-                    const long long wr = base_rows + jr;
-                    if (wr < out.cap_rows) {
-                        out.crd0[wr] = (int32_t)row_of(key);
-                        out.pos1[wr] = (int32_t)wpos;
-                    }
-                }
-            }
-            hcount += __popcll(hm);
-        }
+        wave_sync();                           // assembly words are visible
         if (FMT == SPADD_CSR) {
             // pos of every row that starts inside this partition: offset of the first
             // output entry whose row is not smaller
-            wave_sync();
             const int first = coord[p * 2] + (cont ? 1 : 0);
             const int next_first = coord[(p + 1) * 2] + (row_continues<FMT>(ops, coord, posn, p + 1) ? 1 : 0);
-            for (int r = first + lane; r < next_first; r += NACHO_WAVE) {
+            for (int rr = first + lane; rr < next_first; rr += NACHO_WAVE) {
                 int l = 0, h = n;
                 while (l < h) {
                     const int m = (l + h) >> 1;
-                    if (row_of(keys[w.info[m] & 1023]) < (uint32_t)r) l = m + 1; else h = m;
+                    if (row_of(keys[w.info[m] & 1023]) < (uint32_t)rr) l = m + 1; else h = m;
                 }
-                out.pos1[r] = (int32_t)(base_nnz + (l < n ? w.marks[l] : heads));
+                out.pos1[rr] = (int32_t)(base_nnz + (l < n ? (w.marks[l] & 0xffff) : heads));
+            }
+            wave_sync();                       // keys are read: the duplicates' values may overwrite them
+        }
+        T *dv = w.dups();
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (slot[r] & 0x8000) dv[slot[r] & 0x7fff] = val[r];
+        wave_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * NACHO_WAVE + lane;
+            if (c >= n || (slot[r] & 0x8000)) continue;
+            const int m = slot[r];
+            const int word = w.marks[m];
+            T sum = val[r];                    // then the duplicates, which follow in operand order
+            bool more = true;
+#pragma unroll
+            for (int g = 1; g < K; ++g) {
+                more = more && m + g < n && (w.info[m + g < CAP ? m + g : CAP - 1] >> 15);
+                if (more) sum += dv[m + g];
+            }
+            const long long wpos = base_nnz + (word & 0xffff);
+            if (wpos < out.cap_nnz) {
+                out.crd1[wpos] = col[r];
+                static_cast<T *>(out.val)[wpos] = sum;
+            }
+            if (FMT == SPADD_DCSR && word < 0) {
+                const long long wr = base_rows + ((word >> 16) & 0x7fff);
+                if (wr < out.cap_rows) {
+                    out.crd0[wr] = (int32_t)row[r];
+                    out.pos1[wr] = (int32_t)wpos;
+                }
             }
         }
     }
 }
 
-// Clears the look-back state of a call: one state word per workgroup, and the status.
+// Clears the published counts of a call (n_words 64-bit words) and the status.
 __global__ void __launch_bounds__(256)
-spadd_reset_kernel(int64_t n_groups, unsigned long long *__restrict__ tile_state,
+spadd_reset_kernel(int64_t n_words, unsigned long long *__restrict__ tile_state,
                    int32_t *__restrict__ status)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_groups) tile_state[i] = 0ull;
+    if (i < n_words) tile_state[i] = 0ull;
     if (i == 0) *status = NACHO_OK;
 }
 
-// Workgroups of this kernel the device holds at once (per device, asked once).
-template <int FMT, typename T>
-int64_t resident_groups()
+int64_t groups_of(int64_t P) { return (P + kWavesPerGroup - 1) / kWavesPerGroup; }
+int64_t chunks_of(int64_t P) { return (groups_of(P) + kChunk - 1) / kChunk; }
+
+template <int FMT, typename T, int K>
+hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
+                      const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    static int64_t cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
-        int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spadd_kernel<FMT, T>,
-                                                         kWavesPerGroup * NACHO_WAVE, 0) != hipSuccess)
-            return 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        cached[dev] = (int64_t)per_cu * cus;
-    }
-    return cached[dev];
+    const int64_t n_groups = groups_of(P);
+    const unsigned grid = (unsigned)n_groups;
+    hipLaunchKernelGGL((spadd_kernel<FMT, T, K>), dim3(grid), dim3(kWavesPerGroup * NACHO_WAVE), 0, s, ops, vals,
+                       P, n_groups, chunks_of(P), coord, posn, tile_state, out);
+    return hipGetLastError();
 }
 
+// instantiated for up to 2, 3, 4 and 8 operands: the per-entry loops over the runs are unrolled
 template <int FMT, typename T>
 hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                       const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    const int64_t n_groups = (P + kWavesPerGroup - 1) / kWavesPerGroup;
-    const int64_t resident = resident_groups<FMT, T>();
-    if (resident < 1) return hipErrorUnknown;
-    const unsigned grid = (unsigned)(n_groups < resident ? n_groups : resident);
-    hipLaunchKernelGGL((spadd_kernel<FMT, T>), dim3(grid), dim3(kWavesPerGroup * NACHO_WAVE), 0, s, ops, vals,
-                       P, n_groups, coord, posn, tile_state, out);
-    return hipGetLastError();
+    if (ops.k <= 2) return launch_k<FMT, T, 2>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 3) return launch_k<FMT, T, 3>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 4) return launch_k<FMT, T, 4>(ops, vals, P, coord, posn, tile_state, out, s);
+    return launch_k<FMT, T, 8>(ops, vals, P, coord, posn, tile_state, out, s);
 }
 
 }  // namespace
 
 int spadd_capacity(int fmt) { return fmt == SPADD_VECTOR ? kSpaddCapVector : kSpaddCapMatrix; }
 
-int64_t spadd_groups(int64_t P) { return (P + kWavesPerGroup - 1) / kWavesPerGroup; }
+// 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup
+int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (groups_of(P) + 1) / 2; }
 
 hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s)
 {
-    const int64_t n_groups = spadd_groups(P);
-    const unsigned grid = (unsigned)((n_groups + 255) / 256);
-    hipLaunchKernelGGL(spadd_reset_kernel, dim3(grid ? grid : 1), dim3(256), 0, s, n_groups, tile_state, status);
+    const int64_t n_words = spadd_state_words(P);
+    const unsigned grid = (unsigned)((n_words + 255) / 256);
+    hipLaunchKernelGGL(spadd_reset_kernel, dim3(grid ? grid : 1), dim3(256), 0, s, n_words, tile_state, status);
     return hipGetLastError();
 }
 
