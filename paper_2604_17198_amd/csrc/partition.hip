@@ -536,10 +536,108 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
     }
 }
 
+// ---- one CSR operand: all boundaries in one pass over the rows ---------------
+// With a single operand the search of Algorithm 1 has a closed form (the CSR
+// cost functions of Section 4.2.2): boundary b lies in the row r with
+// pos[r] <= Q_b < pos[r+1], at position Q_b.  Instead of P searches over pos,
+// every row finds the boundaries that fall inside it: the queries are a
+// monotone function of b with a cheap inverse, so row r owns the boundaries
+// b_first(pos[r]) .. b_first(pos[r+1]) - 1, where b_first(y) is the first
+// boundary whose query reaches y.  One coalesced pass over pos, no dependent
+// loads; a row with many boundaries is written by its whole wavefront.
+namespace {
+
+// Built-in queries in unscaled units.  grain_u > 0: Q_b = min(b * grain_u, total);
+// grain_u == 0: Q_b = floor(b * total / P).
+struct QueryRule {
+    int64_t P, total, grain_u;
+    __device__ int64_t query(int64_t b) const
+    {
+        if (grain_u > 0) { const int64_t q = b * grain_u; return q < total ? q : total; }
+        return equal_query(b, total, P);
+    }
+    // least b in [0, P] whose query is >= y, for 0 <= y <= total
+    __device__ int64_t first_reaching(int64_t y) const
+    {
+        int64_t b;
+        if (grain_u > 0 && grain_u < 0x7fffffffLL) b = ((uint32_t)y + (uint32_t)grain_u - 1u) / (uint32_t)grain_u;   // y < 2^31
+        else if (grain_u > 0) b = y > 0 ? 1 : 0;
+        else b = total > 0 ? (y * P + total - 1) / total : 0;     // y, P < 2^31
+        return b < P ? b : P;
+    }
+};
+
+__global__ void __launch_bounds__(256)
+partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
+                      int64_t count, QueryRule rule, int64_t cost_scale, int32_t *__restrict__ coord,
+                      int32_t *__restrict__ posn, int64_t *__restrict__ cost)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = lane_id();
+    const int64_t P = rule.P;
+    const int32_t p0 = pos[0];
+    // As boundary i: everything that does not depend on the row.  Boundaries that
+    // are not searched (the origin, the end, queries that reach past the work) are
+    // complete here.
+    if (i <= P) {
+        const int64_t q = rule.query(i);
+        if (i == 0 || i == P || q >= rule.total) {
+            const bool end = i != 0;
+            coord[i * 2 + 0] = end ? (int32_t)n_rows : 0;
+            coord[i * 2 + 1] = 0;
+            posn[i * 2 + 0] = end ? (int32_t)n_rows : 0;
+            posn[i * 2 + 1] = end ? (int32_t)count : 0;
+            cost[i] = end ? rule.total * cost_scale : 0;
+        } else {
+            coord[i * 2 + 1] = crd[p0 + q];
+            posn[i * 2 + 1] = (int32_t)(p0 + q);
+            cost[i] = q * cost_scale;
+        }
+    }
+    // As row i: the row fields of the boundaries that fall inside it.
+    int64_t b_lo = 0, b_hi = 0;
+    if (i < n_rows) {
+        const int64_t a = pos[i] - p0, e = pos[i + 1] - p0;
+        if (e > a) {
+            b_lo = rule.first_reaching(a);
+            b_hi = rule.first_reaching(e);
+            if (b_lo < 1) b_lo = 1;                 // boundary 0 is the origin by definition
+            // (b < b_hi means Q_b < pos[r+1] <= total and b < P: interior)
+        }
+    }
+    unsigned long long todo = __ballot(b_hi > b_lo);
+    while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const int64_t lo = __shfl((long long)b_lo, src, NACHO_WAVE);
+        const int64_t hi = __shfl((long long)b_hi, src, NACHO_WAVE);
+        const int32_t r = (int32_t)(i - lane + src);
+        for (int64_t b = lo + lane; b < hi; b += NACHO_WAVE) {
+            coord[b * 2 + 0] = r;
+            posn[b * 2 + 0] = r;
+        }
+    }
+}
+
+}  // namespace
+
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream)
 {
+    if (ops.k == 1 && ops.d == 2 && ops.lvl[0][0].kind == NACHO_DENSE && !queries &&
+        (grain == 0 || grain % cost_scale == 0)) {
+        QueryRule rule;
+        rule.P = P;
+        rule.total = total_unscaled;
+        rule.grain_u = grain / cost_scale;
+        const int64_t n_rows = ops.lvl[0][0].extent;
+        const int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
+        hipLaunchKernelGGL(partition_csr1_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                           ops.lvl[0][1].pos, ops.lvl[0][1].crd, n_rows, ops.lvl[0][1].count, rule, cost_scale,
+                           coord, posn, cost);
+        return hipGetLastError();
+    }
     const int64_t waves = (P + 1 + kGroup - 1) / kGroup;
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);

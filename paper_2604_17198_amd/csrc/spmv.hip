@@ -152,32 +152,67 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     if (lane == 0) carry_row[p] = has_head ? r0 : -1;
 }
 
-// One wavefront per partition; the first partition of a run of carries for the
-// same row adds the whole run to y[row].
+// Carry fix-up, one lane per partition.  The carries of a row sit in
+// consecutive partitions; the wavefront that holds the first carry of a row adds
+// the whole run to y[row]: a segmented sum over its own 64 lanes, plus a walk
+// over the following partitions when the run goes on past the wavefront's last
+// lane.  One writer per row and a fixed order of additions.
 template <typename T>
 __global__ void __launch_bounds__(256)
 spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
                   const int32_t *__restrict__ carry_row)
 {
-    const int p = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE);
-    if (p >= P) return;
+    const int p = (int)((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
     const int lane = lane_id();
-    const int r = carry_row[p];
-    if (r < 0) return;
-    if (p > 0 && carry_row[p - 1] == r) return;        // not the head of its run
-    int e = p + 1;                                     // one past the run's last partition
-    for (;;) {
-        const int q = e + lane;
-        const bool same = q < P && carry_row[q] == r;
-        const unsigned long long m = __ballot(same);
-        if (m == ~0ull) { e += NACHO_WAVE; continue; }
-        e += __ffsll((long long)~m) - 1;
-        break;
+    const int p_first = p - lane;                      // partition of lane 0
+    if (p_first >= P) return;                          // whole wavefront leaves together
+    const int r = p < P ? carry_row[p] : -1;
+    T v = r >= 0 ? carry_val[p] : T(0);
+    int before = __shfl_up(r, 1, NACHO_WAVE);
+    if (lane == 0) before = p_first > 0 ? carry_row[p_first - 1] : -1;
+    const bool head = r >= 0 && r != before;           // first carry of its row
+    const bool first_here = r != before || lane == 0;  // first lane of its segment in this wavefront
+    const unsigned long long starts = __ballot(first_here);
+    const unsigned long long upto = lane == NACHO_WAVE - 1 ? ~0ull : ((2ull << lane) - 1ull);
+    const int start = 63 - __clzll((long long)(starts & upto));
+    const unsigned long long after = starts & ~upto;
+    const int end = after ? __ffsll((long long)after) - 2 : NACHO_WAVE - 1;   // last lane of the segment
+    // inclusive sum inside the segment
+#pragma unroll
+    for (int o = 1; o < NACHO_WAVE; o <<= 1) {
+        const T left = __shfl_up(v, o, NACHO_WAVE);
+        if (lane - o >= start) v += left;
     }
-    T s = T(0);
-    for (int q = p + lane; q < e; q += NACHO_WAVE) s += carry_val[q];
-    s = wave_sum(s);
-    if (lane == 0) y[r] += s;
+    const bool owned = __shfl((int)head, start, NACHO_WAVE) != 0;   // the run starts in this wavefront
+    // a run that reaches the last lane may go on in the next wavefronts
+    const int r_last = __shfl(r, NACHO_WAVE - 1, NACHO_WAVE);
+    const bool last_owned = __shfl((int)owned, NACHO_WAVE - 1, NACHO_WAVE) != 0;
+    T tail = T(0);
+    if (r_last >= 0 && last_owned) {
+        constexpr int kBatch = 4;                      // chunks of 64 partitions loaded together
+        int e = p_first + NACHO_WAVE;
+        bool more = true;
+        while (more) {
+            int rr[kBatch];
+            T vv[kBatch];
+#pragma unroll
+            for (int c = 0; c < kBatch; ++c) {
+                const int q = e + c * NACHO_WAVE + lane;
+                rr[c] = q < P ? carry_row[q] : -1;
+                vv[c] = q < P ? carry_val[q] : T(0);
+            }
+#pragma unroll
+            for (int c = 0; c < kBatch; ++c) {
+                if (!more) break;
+                const unsigned long long m = __ballot(rr[c] == r_last);
+                const int cnt = m == ~0ull ? NACHO_WAVE : __ffsll((long long)~m) - 1;   // leading lanes of the run
+                tail += wave_sum(lane < cnt ? vv[c] : T(0));
+                more = cnt == NACHO_WAVE;
+            }
+            e += kBatch * NACHO_WAVE;
+        }
+    }
+    if (r >= 0 && owned && lane == end) y[r] += v + (end == NACHO_WAVE - 1 ? tail : T(0));
 }
 
 constexpr int kGrainF64 = 1024, kRowsF64 = 1024;
@@ -209,7 +244,7 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
                              const int32_t *carry_row, hipStream_t stream)
 {
-    const unsigned grid = (unsigned)((P * NACHO_WAVE + 255) / 256);
+    const unsigned grid = (unsigned)((P + 255) / 256);
     if (dtype == NACHO_F64)
         hipLaunchKernelGGL((spmv_fixup_kernel<double>), dim3(grid), dim3(256), 0, stream,
                            (double *)y, (int)P, (const double *)carry_val, carry_row);
