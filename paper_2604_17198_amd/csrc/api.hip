@@ -285,7 +285,7 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
         return NACHO_ERR_HIP;
     profile_mark("partition");
     if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
-                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, grain, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmv_exec");
     if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, s) != hipSuccess)

@@ -13,10 +13,12 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
 
 // Items one wavefront can stage for SpMV (partition work must not exceed it).
 int spmv_capacity(int dtype);
+// `grain` > 0: the partitions come from the fixed-grain queries Q_p = min(p * grain, nnz)
+// (the kernel then deals the partitions of long rows out by XCD); 0: any partitions.
 hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, const void *val,
                             const void *x, void *y, int64_t n_rows, int64_t nnz,
                             const int32_t *coord, const int32_t *posn, int64_t P,
-                            void *carry_val, int32_t *carry_row, hipStream_t stream);
+                            void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream);
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
                              const int32_t *carry_row, hipStream_t stream);
 

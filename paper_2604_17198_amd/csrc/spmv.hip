@@ -4,8 +4,8 @@
 //
 // Partition p owns the stored non-zeros at positions [n_p, n_{p+1}) of A.  Its
 // wavefront
-//   1. streams crd/val of that range with 16-byte loads, gathers x and leaves
-//      the products in LDS;
+//   1. streams crd/val of that range (read once: non-temporal loads, so that
+//      the L2 is left to x), gathers x and leaves the products in LDS;
 //   2. walks the rows that overlap the range (their pos entries staged in LDS),
 //      one lane per row; rows with many products are summed by the whole
 //      wavefront instead;
@@ -23,35 +23,36 @@ namespace {
 
 constexpr int kLongRow = 192;  // products per row above which the wavefront sums it together
 
-template <typename T> struct Vec4;
-template <> struct Vec4<float> {
-    static __device__ inline void load(const float *p, float v[4])
-    {
-        const float4 q = *reinterpret_cast<const float4 *>(p);
-        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-    }
-};
-template <> struct Vec4<double> {
-    static __device__ inline void load(const double *p, double v[4])
-    {
-        const double2 a = *reinterpret_cast<const double2 *>(p);
-        const double2 b = *reinterpret_cast<const double2 *>(p + 2);
-        v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
-    }
-};
-
 template <typename T, int G, int RBLK>
 __global__ void __launch_bounds__(NACHO_WAVE)
 spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                  const T *__restrict__ val, const T *__restrict__ x, T *__restrict__ y,
                  int nnz, const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
-                 T *__restrict__ carry_val, int32_t *__restrict__ carry_row)
+                 T *__restrict__ carry_val, int32_t *__restrict__ carry_row, int n_rows, int grain)
 {
     __shared__ T prod[G + 8];
     __shared__ int32_t spos[RBLK + 1];
 
-    const int p = blockIdx.x;
     const int lane = threadIdx.x;
+    // Which partition this workgroup executes.  Workgroups are handed to the 8
+    // XCDs in turn (workgroup w runs on XCD w mod 8) and every XCD has its own
+    // L2, which x does not fit.  The partitions that lie inside one long row are
+    // therefore dealt out so that XCD j gets the j-th eighth of the row, in
+    // ascending order: its gathers then stay inside one eighth of x (columns
+    // are sorted inside a row), which its L2 holds.  With fixed-grain queries
+    // the partitions inside row r are ceil(pos[r] / grain) .. floor(pos[r+1] /
+    // grain) - 1; the deal is a permutation of the largest range of them that
+    // starts and ends on a multiple of 8, everything else keeps its index.
+    int p = blockIdx.x;
+    if (grain > 0) {
+        const int r = coord[2 * p];
+        if (r < n_rows) {
+            const int base = pos[0];
+            const int lo = (((pos[r] - base) + grain - 1) / grain + 7) & ~7;
+            const int hi = ((pos[r + 1] - base) / grain) & ~7;
+            if (hi - lo >= 16 && p >= lo && p < hi) p = lo + (p & 7) * ((hi - lo) >> 3) + ((p - lo) >> 3);
+        }
+    }
     // k = 1, d = 2: coord[b*2 + 0] = row, posn[b*2 + 1] = position in crd/val
     const int r0 = coord[2 * p], r1 = coord[2 * p + 2];
     const int n0 = posn[2 * p + 1], n1 = posn[2 * p + 3];
@@ -59,58 +60,40 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     const bool has_head = n0 > pr0;                    // row r0 started in an earlier partition
     const int next_first = (n1 > pr1) ? r1 + 1 : r1;   // first row that starts after this partition
     const int nrows = next_first - r0;                 // rows overlapping or starting here
-    const int a0 = n0 & ~3;                            // 16-byte aligned start of the window
-
+    const int a0 = n0;                                 // prod[i] belongs to position a0 + i
     // pos entries of the first row block, requested before the streamed data
     int nr = nrows < RBLK ? nrows : RBLK;
     if (nrows > 0)
         for (int i = lane; i <= nr; i += NACHO_WAVE) spos[i] = pos[r0 + i];
 
-    // All streamed loads are issued before the first gather, all gathers before
-    // the first LDS store, so one wavefront keeps its whole window in flight.
-    constexpr int kIter = G / (NACHO_WAVE * 4) + 1;    // +1: a misaligned start adds up to 3 items
-    int c[kIter][4];
-    T v[kIter][4];
+    // Lane l takes positions n0 + l, n0 + 64 + l, ...: consecutive lanes hold
+    // consecutive non-zeros, so inside a dense row the 64 gathers of one
+    // instruction fall into few cache lines of x (columns are sorted).  All
+    // streamed loads are issued before the first gather, all gathers before the
+    // first LDS store, so one wavefront keeps its whole window in flight.
+    constexpr int kIter = G / NACHO_WAVE;
+    int c[kIter];
+    T v[kIter];
 #pragma unroll
     for (int j = 0; j < kIter; ++j) {
-        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
-        if (base < n1) {
-            if (base + 4 <= nnz) {
-                const int4 q = *reinterpret_cast<const int4 *>(crd + base);
-                c[j][0] = q.x; c[j][1] = q.y; c[j][2] = q.z; c[j][3] = q.w;
-                Vec4<T>::load(val + base, v[j]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bool in = base + e < nnz;
-                    c[j][e] = in ? crd[base + e] : 0;
-                    v[j][e] = in ? val[base + e] : T(0);
-                }
-            }
+        const int idx = n0 + j * NACHO_WAVE + lane;
+        c[j] = 0;
+        v[j] = T(0);
+        if (idx < n1) {
+            c[j] = __builtin_nontemporal_load(crd + idx);
+            v[j] = __builtin_nontemporal_load(val + idx);
         }
     }
-    T xv[kIter][4];
+    T xv[kIter];
 #pragma unroll
     for (int j = 0; j < kIter; ++j) {
-        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int idx = base + e;
-            const bool in = idx >= n0 && idx < n1;
-            xv[j][e] = in ? x[c[j][e]] : T(0);
-        }
+        const int idx = n0 + j * NACHO_WAVE + lane;
+        xv[j] = idx < n1 ? x[c[j]] : T(0);
     }
 #pragma unroll
     for (int j = 0; j < kIter; ++j) {
-        const int base = a0 + (j * NACHO_WAVE + lane) * 4;
-        if (base < n1) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int idx = base + e;
-                const bool in = idx >= n0 && idx < n1;
-                prod[base - a0 + e] = in ? v[j][e] * xv[j][e] : T(0);
-            }
-        }
+        const int idx = n0 + j * NACHO_WAVE + lane;
+        if (idx < n1) prod[idx - a0] = v[j] * xv[j];
     }
     __syncthreads();
 
@@ -225,19 +208,18 @@ int spmv_capacity(int dtype) { return dtype == NACHO_F64 ? kGrainF64 : kGrainF32
 hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, const void *val,
                             const void *x, void *y, int64_t n_rows, int64_t nnz,
                             const int32_t *coord, const int32_t *posn, int64_t P,
-                            void *carry_val, int32_t *carry_row, hipStream_t stream)
+                            void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream)
 {
-    (void)n_rows;
     if (dtype == NACHO_F64)
         hipLaunchKernelGGL((spmv_exec_kernel<double, kGrainF64, kRowsF64>), dim3((unsigned)P),
                            dim3(NACHO_WAVE), 0, stream, pos, crd, (const double *)val,
                            (const double *)x, (double *)y, (int)nnz, coord, posn,
-                           (double *)carry_val, carry_row);
+                           (double *)carry_val, carry_row, (int)n_rows, (int)grain);
     else
         hipLaunchKernelGGL((spmv_exec_kernel<float, kGrainF32, kRowsF32>), dim3((unsigned)P),
                            dim3(NACHO_WAVE), 0, stream, pos, crd, (const float *)val,
                            (const float *)x, (float *)y, (int)nnz, coord, posn,
-                           (float *)carry_val, carry_row);
+                           (float *)carry_val, carry_row, (int)n_rows, (int)grain);
     return hipGetLastError();
 }
 
