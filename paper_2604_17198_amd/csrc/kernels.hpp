@@ -33,8 +33,7 @@ hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, 
 
 // ---- k-way union addition ---------------------------------------------------
 enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2 };
-constexpr int kSpaddCapVector = 1024;   // entries of all operands one wavefront stages (vectors)
-constexpr int kSpaddCapMatrix = 1024;   // ... (CSR / DCSR: 64-bit keys)
+constexpr int kSpaddCap = 4096;         // entries of all operands one partition (workgroup) stages
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
 struct SpaddOut {

@@ -399,7 +399,7 @@ __device__ inline int64_t level_total(const DevOperands &ops, int m, const int *
     return total;
 }
 
-constexpr int kGroup = 4;   // neighbouring boundaries one wavefront searches
+constexpr int kGroup = 1;   // neighbouring boundaries one wavefront searches
 
 }  // namespace
 

@@ -1,21 +1,24 @@
 // k-way sparse union addition: assembly (count), prefix sum and compute (fill)
-// of Section 4.3 / 4.4 (pipeline of Figure 7(a)) in ONE kernel, one wavefront
-// per partition.
+// of Section 4.3 / 4.4 (pipeline of Figure 7(a)) in ONE kernel, one workgroup
+// of eight wavefronts per partition.
 //
 // A partition owns, in every operand t, the stored entries at last-level
 // positions [q_t(p), q_t(p+1)) found by the partition search; because the
 // search runs in coordinate space, entries with equal coordinates in different
 // operands always fall in the same partition (Section 6, merge-path paragraph),
 // so a partition's output is independent of its neighbours: there is no carry.
+// Inside the workgroup the entries are dealt out thread by thread (entry c of
+// the partition belongs to thread c mod 512), so the eight wavefronts carry
+// exactly the same load whatever the operands look like.
 //
 // The union is formed by cross-ranking instead of a serial k-finger merge: the
 // work per entry is constant, every lane works on its own entries, and the only
 // data-dependent loops are binary searches of fixed depth done by the SMALLER
 // run of every pair of runs.
-// Per partition the wavefront
+// Per partition the workgroup
 //   1. stages the operands' coordinate segments in LDS as k sorted runs of keys
 //      (vectors: the index; matrices: row<<32 | column, the row of every entry
-//      recovered from the pos array with a marker + running-maximum scan);
+//      recovered from the pos array with a marker + latest-marker scan);
 //   2. ranks: for every pair of runs the entries of the smaller run search the
 //      larger one.  The position found is the number of entries of the larger
 //      run that precede the entry in the stable k-way merge (ties in operand
@@ -30,26 +33,27 @@
 //      HEAD of its coordinate.  The number of heads is the partition's output
 //      count (and a head whose predecessor lies in another row starts a row);
 //      every slot keeps the number of heads (and row heads) before it;
-//   4. prefix sum: publishes its counts and adds up the counts of all earlier
-//      partitions with a decoupled look-back over a state word per workgroup;
-//      the loads of the values are in flight meanwhile;
-//   5. compute: every lane goes back to its own entries (coordinates and values
-//      are in its registers).  A head writes coordinate and value at offset +
-//      heads before its slot; its value is its own plus the duplicates in the
-//      slots that follow it, i.e. in operand order (duplicates hand their
-//      values over through LDS).  The hierarchical arrays (crd0/pos1 of a DCSR
-//      result, pos of a CSR result) are written for the rows whose first
-//      output entry the partition owns -- exactly one writer per row.
-// Every loop over a partition's entries is unrolled over the 16 entries of a
-// lane, so that the LDS and global accesses of a stage are in flight together.
+//   4. prefix sum: publishes its counts and reads the counts of everything
+//      before it (two levels, see below); the loads of the values are in
+//      flight meanwhile;
+//   5. compute: every thread goes back to its own entries (coordinates and
+//      values are in its registers).  A head writes coordinate and value at
+//      offset + heads before its slot; its value is its own plus the
+//      duplicates in the slots that follow it, i.e. in operand order
+//      (duplicates hand their values over through LDS).  The hierarchical
+//      arrays (crd0/pos1 of a DCSR result, pos of a CSR result) are written for
+//      the rows whose first output entry the partition owns -- exactly one
+//      writer per row.
+// Every loop over a partition's entries is unrolled over the 8 entries of a
+// thread, so that the LDS and global accesses of a stage are in flight together.
 // What differs from the paper's three kernels: the inputs are read once instead
 // of twice and there is no separate scan launch; the arithmetic is the same.
 //
-// Workgroup g handles partitions g * W .. g * W + W - 1 and waits, in its
-// look-back, only for workgroups with a smaller index.  Workgroups are handed
-// to every XCD in index order, so the unfinished workgroup with the smallest
-// index is always running and waits for nobody: the waits end.  (Every wait is
-// bounded all the same; a wavefront that gives up reports NACHO_ERR_HIP.)
+// Workgroup p handles partition p and waits, when it looks up its offset, only
+// for workgroups with a smaller index.  Workgroups are handed to every XCD in
+// index order, so the unfinished workgroup with the smallest index is always
+// running and waits for nobody: the waits end.  (Every wait is bounded all the
+// same; a wavefront that gives up reports NACHO_ERR_HIP.)
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -60,11 +64,15 @@ namespace {
 template <int FMT> struct KeyOf { typedef uint64_t type; };
 template <> struct KeyOf<SPADD_VECTOR> { typedef uint32_t type; };
 
-template <int FMT> struct Cap { static constexpr int value = kSpaddCapMatrix; };
-template <> struct Cap<SPADD_VECTOR> { static constexpr int value = kSpaddCapVector; };
+constexpr int kWaves = 8;                          // wavefronts per workgroup
+constexpr int kThreads = kWaves * NACHO_WAVE;
+constexpr int kPerThread = 8;                      // entries of a thread: c = r * kThreads + tid, r < kPerThread
+constexpr int kTile = kThreads * kPerThread;       // entries a partition may hold
+static_assert(kTile == kSpaddCap, "capacity told to the host");
+static_assert(kTile <= 4096, "descriptors pack a 12-bit position");
 
 // Prefix sum over the workgroups' counts, two levels and no chains: a workgroup
-// publishes the counts of its partitions in a 32-bit word; the last workgroup
+// publishes the counts of its partition in a 32-bit word; the last workgroup
 // of every chunk of kChunk workgroups also publishes the chunk's total.  The
 // offset of a workgroup is the sum of the totals of the chunks before its own
 // plus the sum of the words of the workgroups before it in its chunk: all of
@@ -74,7 +82,6 @@ template <> struct Cap<SPADD_VECTOR> { static constexpr int value = kSpaddCapVec
 //   total: bit 63 published, bits 31..61 rows, bits 0..30 nnz
 constexpr int kChunk = 512;           // workgroups per chunk
 constexpr int kSpinLimit = 1 << 20;   // polls before a wavefront gives up
-constexpr int kWavesPerGroup = 2;     // partitions per workgroup (one prefix look-up for all of them)
 constexpr unsigned kWordValid = 0x80000000u;
 constexpr unsigned long long kTotalValid = 1ull << 63;
 
@@ -105,34 +112,37 @@ __device__ inline void run_lower_bound(const KeyT *seg, int n, const KeyT (&key)
     }
 }
 
-// Per-wavefront LDS state of one partition.
-constexpr int kPadShift = 4;    // one unused word after every 16: a lane's 16 consecutive words start on its own bank
-template <int CAP> struct Padded { static constexpr int value = CAP + (CAP >> kPadShift); };
+// LDS state of one partition.
+constexpr int kPadShift = 3;    // one unused word after every 8: a thread's 8 consecutive words start on its own bank
+static_assert((1 << kPadShift) == kPerThread, "the padding follows the words of a thread");
+constexpr int kPadded = kTile + (kTile >> kPadShift);
 __device__ inline int pad(int x) { return x + (x >> kPadShift); }
 
 // Word of an entry in `marks` while the ranks are formed:
-//   bits  0..15  marks left at this entry by smaller runs (then their prefix sum)
+//   bits  0..15  marks left at this entry by smaller runs (then their prefix sum over the tile)
 //   bits 16..19  number of equal keys met in operands with a smaller index (> 0: duplicate)
-//   bits 20..30  sum of the positions this entry found in larger runs
+//   bits 20..31  sum of the positions this entry found in larger runs (< kTile)
 constexpr int kDupShift = 16, kDirectShift = 20;
-// Word of a merged slot in `marks` after the assembly:
+// Word of a merged slot in `marks` after the assembly (counts inside the slot's wavefront share):
 //   bits 0..15 heads before the slot, 16..30 row heads before it, 31 the slot starts a row
-template <typename KeyT, typename T, int CAP>
-struct WaveTile {
+template <typename KeyT, typename T>
+struct Tile {
     union {
-        KeyT keys[CAP];                   // the k runs, one after the other
-        T dupval[sizeof(T) <= sizeof(KeyT) ? CAP : 1];   // later: values of duplicates by merged slot
+        KeyT keys[kTile];                 // the k runs, one after the other
+        T dupval[sizeof(T) <= sizeof(KeyT) ? kTile : 1];   // later: values of duplicates by merged slot
     };
-    T dupval_wide[sizeof(T) <= sizeof(KeyT) ? 1 : CAP];
-    int32_t marks[Padded<CAP>::value];    // staging: row markers; ranking words (padded); assembly words
-    uint16_t info[CAP];                   // merged order: position in keys (0..9) | duplicate (15)
+    T dupval_wide[sizeof(T) <= sizeof(KeyT) ? 1 : kTile];
+    uint32_t marks[kPadded];              // staging: row markers; ranking words (padded); assembly words
+    uint16_t info[kTile];                 // merged order: position in keys (0..11) | duplicate (15)
     unsigned long long scrd[NACHO_MAX_OPERANDS];   // address of crd of run t, biased so that [c] is entry c of keys
     unsigned long long sval[NACHO_MAX_OPERANDS];   // the same for the values
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
-    int32_t srun[NACHO_MAX_OPERANDS];              // start of run t | marks summed before it << 16
+    uint32_t srun[NACHO_MAX_OPERANDS];             // start of run t | marks summed before it << 16
+    uint32_t wave_x[kWaves];                       // per-wavefront partial of a scan across the workgroup
+    unsigned long long wave_cnt[kWaves];           // per-wavefront counts of the assembly (rows << 31 | nnz)
+    unsigned long long base;                       // the partition's offset (rows << 31 | nnz)
     __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
 };
-static_assert(kSpaddCapVector <= 1024 && kSpaddCapMatrix <= 1024, "info packs a 10-bit position");
 
 // Does boundary b fall strictly inside a row, i.e. does some operand hold an
 // entry of the boundary's row before the boundary?  (Then the row's first
@@ -186,425 +196,444 @@ __device__ inline void rank_blocks(Tile &w, int k, int t, int r0, int lane)
             if (u < t) {
                 // run u wins ties: its equal entry precedes this one, which is a duplicate
                 direct[i] += ((lb[i] + eq) << kDirectShift) + (eq << kDupShift);
-                if (valid[i] && lb[i] + eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + eq)], 1);
+                if (valid[i] && lb[i] + eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + eq)], 1u);
             } else {
                 // this entry precedes u's entries from position lb on; an equal one there is a duplicate
                 direct[i] += lb[i] << kDirectShift;
-                if (valid[i] && lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1 + (eq << kDupShift));
+                if (valid[i] && lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1u + ((unsigned)eq << kDupShift));
             }
         }
     }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int il = r0 + i * NACHO_WAVE + lane;
-        if (valid[i]) atomicAdd(&w.marks[pad(off_t + il)], direct[i]);
+        if (valid[i]) atomicAdd(&w.marks[pad(off_t + il)], (unsigned)direct[i]);
     }
 }
 
 template <int FMT, typename T, int K>
-__global__ void __launch_bounds__(kWavesPerGroup * NACHO_WAVE)
-spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_groups, int64_t n_chunks,
+__global__ void __launch_bounds__(kThreads)
+spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
              unsigned long long *__restrict__ tile_state, SpaddOut out)
 {
     typedef typename KeyOf<FMT>::type KeyT;
-    constexpr int CAP = Cap<FMT>::value;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
-    constexpr int R = CAP / NACHO_WAVE;        // entries of a lane: c = r * 64 + lane, r < R
-    typedef WaveTile<KeyT, T, CAP> Tile;
-    // every wavefront of the workgroup owns a private slice of LDS and works on
-    // its own partition; only the look-back is shared
-    __shared__ Tile s_tile[kWavesPerGroup];
-    __shared__ unsigned long long s_cnt[2][kWavesPerGroup];   // per-wavefront counts (rows<<31 | nnz)
-    __shared__ unsigned long long s_base[2];                  // the workgroup's exclusive prefix
+    constexpr int R = kPerThread;
+    constexpr int kShare = kTile / kWaves;     // merged slots a wavefront walks in the assembly
+    __shared__ Tile<KeyT, T> w;
 
+    const int tid = threadIdx.x;
     const int lane = lane_id();
-    const int wave = threadIdx.x / NACHO_WAVE;
+    const int wave = tid / NACHO_WAVE;
     const int k = ops.k;                       // <= K
     const unsigned long long below = (1ull << lane) - 1ull;
-    Tile &w = s_tile[wave];
     KeyT *keys = w.keys;
-    constexpr int parity = 0;
+    const int64_t p = blockIdx.x;              // the partition of this workgroup, p < P
 
-    {
-        const int64_t group = blockIdx.x;
-        const int64_t p = group * kWavesPerGroup + wave;
-        const bool active = p < P;             // idle wavefronts of the last workgroup only keep the barriers
-
-        // ---- 1. segments of this partition ----------------------------------
-        int q_lo[K], off[K + 1];
-        off[0] = 0;
+    // ---- 1. segments of this partition ----------------------------------
+    int q_lo[K], off[K + 1];
+    off[0] = 0;
 #pragma unroll
-        for (int t = 0; t < K; ++t) {
-            if (t >= k || !active) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
-            q_lo[t] = posn[(p * k + t) * D + (D - 1)];
-            const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
-            off[t + 1] = off[t] + (q_hi - q_lo[t]);
-        }
-        int n = off[K];                        // <= CAP by the host's choice of the partition count
-        // Only an operand that violates its preconditions (unsorted or repeated
-        // coordinates) can overflow the staging buffer: such a partition contributes
-        // nothing and the call reports INVALID_ARG, but the look-back chain goes on.
-        bool broken = n > CAP || n < 0;
+    for (int t = 0; t < K; ++t) {
+        if (t >= k) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
+        q_lo[t] = posn[(p * k + t) * D + (D - 1)];
+        const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
+        off[t + 1] = off[t] + (q_hi - q_lo[t]);
+    }
+    int n = off[K];                            // <= kTile by the host's choice of the partition count
+    // Only an operand that violates its preconditions (unsorted or repeated
+    // coordinates) can overflow the staging buffer: such a partition contributes
+    // nothing and the call reports INVALID_ARG, but the prefix sum goes on.
+    bool broken = n > kTile || n < 0;
 #pragma unroll
-        for (int t = 0; t < K; ++t) broken = broken || off[t + 1] < off[t];
-        if (broken) {
-            n = 0;
+    for (int t = 0; t < K; ++t) broken = broken || off[t + 1] < off[t];
+    if (broken) {
+        n = 0;
 #pragma unroll
-            for (int t = 0; t <= K; ++t) off[t] = 0;
-        }
-        wave_sync();                           // the previous partition's LDS reads are done
+        for (int t = 0; t <= K; ++t) off[t] = 0;
+    }
+    if (tid == 0) {
 #pragma unroll
         for (int t = 0; t <= K; ++t) {
-            if (lane == 0) {
-                w.soff[t] = off[t];
-                if (t < K) {
-                    const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
-                    w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
-                    w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
-                }
+            w.soff[t] = off[t];
+            if (t < K) {
+                const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
+                w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
+                w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
             }
         }
-        wave_sync();
+    }
+    __syncthreads();
 
-        // run and column of every entry of this lane
-        int tr[R], col[R];
+    // run and column of every entry of this thread
+    int tr[R], col[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            int t = 0;
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        int t = 0;
 #pragma unroll
-            for (int u = 1; u < K; ++u) t += c >= off[u] ? 1 : 0;
-            tr[r] = t;
-        }
+        for (int u = 1; u < K; ++u) t += c >= off[u] ? 1 : 0;
+        tr[r] = t;
+    }
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            col[r] = 0;
-            if (c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c];
-        }
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        col[r] = 0;
+        if (c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c];
+    }
 
-        uint32_t row[D == 2 ? R : 1];
-        if (D == 2) {
-            // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
-            // (word of the entry in marks), then hand every entry the latest marker
-            // at or before it.  The first entry of every run carries a marker, so no
-            // row leaks from one run into the next.
-            for (int i = lane; i < Padded<CAP>::value; i += NACHO_WAVE) w.marks[i] = 0;
-            wave_sync();
-#pragma unroll
-            for (int t = 0; t < K; ++t) {
-                if (t >= k) break;
-                const int nt = off[t + 1] - off[t];
-                if (nt == 0) continue;
-                const int32_t *pos1 = ops.lvl[t][1].pos;
-                const int32_t *crd0 = ops.lvl[t][0].crd;
-                const int ql = q_lo[t], qh = ql + nt;
-                const int i_lo = posn[(p * k + t) * 2 + 0];
-                int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
-                const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
-                if (i_hi > i_max) i_hi = i_max;
-                for (int i0 = i_lo + lane; i0 < i_hi; i0 += NACHO_WAVE * 4) {
-                    int a[4], b[4], rw[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * NACHO_WAVE;
-                        if (i < i_hi) {
-                            a[u] = pos1[i];
-                            b[u] = pos1[i + 1];
-                            rw[u] = FMT == SPADD_CSR ? i : crd0[i];
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * NACHO_WAVE;
-                        if (i < i_hi) {
-                            const int s = a[u] > ql ? a[u] : ql;
-                            if (b[u] > s && s < qh) w.marks[pad(off[t] + s - ql)] = rw[u] + 1;
-                        }
-                    }
-                }
-            }
-            wave_sync();
-            {
-                int v[R], cur = 0;
-                const int at = lane * (R + (R >> kPadShift));
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    v[j] = w.marks[at + j];
-                    cur = v[j] ? v[j] : cur;
-                }
-                int incl = cur;                           // latest marker up to the end of this lane's words
-#pragma unroll
-                for (int o = 1; o < NACHO_WAVE; o <<= 1) {
-                    const int left = __shfl_up(incl, o, NACHO_WAVE);
-                    if (lane >= o && incl == 0) incl = left;
-                }
-                cur = __shfl_up(incl, 1, NACHO_WAVE);
-                if (lane == 0) cur = 0;
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    cur = v[j] ? v[j] : cur;
-                    w.marks[at + j] = cur;
-                }
-            }
-            wave_sync();
-#pragma unroll
-            for (int r = 0; r < R; ++r) row[r] = (uint32_t)(w.marks[pad(r * NACHO_WAVE + lane)] - 1);
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            if (c < n) {
-                if (D == 1) keys[c] = (KeyT)(uint32_t)col[r];
-                else keys[c] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
-            }
-        }
-        wave_sync();
-
-        // ---- 2. ranks: slot of every entry in the merged order -----------------------
-        for (int i = lane; i < Padded<CAP>::value; i += NACHO_WAVE) w.marks[i] = 0;
-        wave_sync();
-        int n_max = 0, t_max = 0;              // the largest run searches nothing
+    uint32_t row[D == 2 ? R : 1];
+    if (D == 2) {
+        // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
+        // (word of the entry in marks), then hand every entry the latest marker
+        // at or before it.  The first entry of every run carries a marker, so no
+        // row leaks from one run into the next.
+        for (int i = tid; i < kPadded; i += kThreads) w.marks[i] = 0;
+        __syncthreads();
 #pragma unroll
         for (int t = 0; t < K; ++t) {
+            if (t >= k) break;
             const int nt = off[t + 1] - off[t];
-            if (t == 0 || (t < k && larger_run(nt, t, n_max, t_max))) { n_max = nt; t_max = t; }
+            if (nt == 0) continue;
+            const int32_t *pos1 = ops.lvl[t][1].pos;
+            const int32_t *crd0 = ops.lvl[t][0].crd;
+            const int ql = q_lo[t], qh = ql + nt;
+            const int i_lo = posn[(p * k + t) * 2 + 0];
+            int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
+            const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
+            if (i_hi > i_max) i_hi = i_max;
+            for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
+                int a[4], b[4], rw[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * kThreads;
+                    if (i < i_hi) {
+                        a[u] = pos1[i];
+                        b[u] = pos1[i + 1];
+                        rw[u] = FMT == SPADD_CSR ? i : crd0[i];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * kThreads;
+                    if (i < i_hi) {
+                        const int s = a[u] > ql ? a[u] : ql;
+                        if (b[u] > s && s < qh) w.marks[pad(off[t] + s - ql)] = (uint32_t)(rw[u] + 1);
+                    }
+                }
+            }
         }
+        __syncthreads();
+        {
+            uint32_t v[R], cur = 0;
+            const int at = tid * (R + 1);
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                v[j] = w.marks[at + j];
+                cur = v[j] ? v[j] : cur;
+            }
+            uint32_t incl = cur;                      // latest marker up to the end of this thread's words
+#pragma unroll
+            for (int o = 1; o < NACHO_WAVE; o <<= 1) {
+                const uint32_t left = __shfl_up(incl, o, NACHO_WAVE);
+                if (lane >= o && incl == 0) incl = left;
+            }
+            if (lane == NACHO_WAVE - 1) w.wave_x[wave] = incl;
+            __syncthreads();
+            uint32_t carry = 0;                       // latest marker of the earlier wavefronts
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww)
+                if (ww < wave && w.wave_x[ww]) carry = w.wave_x[ww];
+            cur = __shfl_up(incl, 1, NACHO_WAVE);
+            if (lane == 0) cur = 0;
+            if (cur == 0) cur = carry;
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                cur = v[j] ? v[j] : cur;
+                w.marks[at + j] = cur;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < R; ++r) row[r] = w.marks[pad(r * kThreads + tid)] - 1u;
+        __syncthreads();                           // markers are read: the ranking may clear them
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        if (c < n) {
+            if (D == 1) keys[c] = (KeyT)(uint32_t)col[r];
+            else keys[c] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
+        }
+    }
+
+    // ---- 2. ranks: slot of every entry in the merged order -----------------------
+    for (int i = tid; i < kPadded; i += kThreads) w.marks[i] = 0;
+    __syncthreads();
+    int n_max = 0, t_max = 0;                  // the largest run searches nothing
+#pragma unroll
+    for (int t = 0; t < K; ++t) {
+        const int nt = off[t + 1] - off[t];
+        if (t == 0 || (t < k && larger_run(nt, t, n_max, t_max))) { n_max = nt; t_max = t; }
+    }
+    {
+        int unit = 0;                          // units of work are dealt out to the wavefronts in turn
         for (int t = 0; t < k; ++t) {
             if (t == t_max) continue;
             const int nt = uni(w.soff[t + 1]) - uni(w.soff[t]);
             int r0 = 0;
-            for (; r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE) rank_blocks<KeyT, 4>(w, k, t, r0, lane);
-            for (; r0 < nt; r0 += NACHO_WAVE) rank_blocks<KeyT, 1>(w, k, t, r0, lane);
+            for (; r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE, ++unit)
+                if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4>(w, k, t, r0, lane);
+            for (; r0 < nt; r0 += NACHO_WAVE, ++unit)
+                if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1>(w, k, t, r0, lane);
         }
-        wave_sync();
+    }
+    __syncthreads();
+    {
+        // inclusive prefix sum of the marks (bits 0..15) over all runs at once; a
+        // thread owns R consecutive words, the other bits stay
+        uint32_t v[R];
+        int sum = 0;
+        const int at = tid * (R + 1);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            v[j] = w.marks[at + j];
+            sum += (int)(v[j] & 0xffffu);
+        }
+        const int incl = wave_inclusive_scan(sum);
+        if (lane == NACHO_WAVE - 1) w.wave_x[wave] = (uint32_t)incl;
+        __syncthreads();
+        int run = incl - sum;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww)
+            if (ww < wave) run += (int)w.wave_x[ww];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            run += (int)(v[j] & 0xffffu);
+            w.marks[at + j] = (v[j] & 0xffff0000u) | (uint32_t)run;
+        }
+    }
+    __syncthreads();
+    if (tid < K) {
+        const int o = w.soff[tid];
+        w.srun[tid] = (uint32_t)o | ((o > 0 ? (w.marks[pad(o - 1)] & 0xffffu) : 0u) << 16);
+    }
+    __syncthreads();
+    int slot[R];                               // merged slot | duplicate << 15
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        const uint32_t mk = w.marks[pad(c)];
+        const uint32_t sr = w.srun[tr[r]];
+        const int m = (c - (int)(sr & 0xffffu)) + (int)(mk >> kDirectShift) + ((int)(mk & 0xffffu) - (int)(sr >> 16));
+        const int dup = ((mk >> kDupShift) & 0xfu) ? 0x8000 : 0;
+        slot[r] = m | dup;
+    }
+    __syncthreads();                           // all ranking words are read: the assembly may overwrite them
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        if (c < n) w.info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
+    }
+    __syncthreads();
+
+    // ---- 3. assembly: heads and row heads before every merged slot ------------------
+    // wavefront v walks the slots v * kShare .. (v + 1) * kShare - 1; the counts in
+    // the words are relative to the start of that share
+    bool cont = false;                     // the partition starts inside a row whose head is elsewhere
+    if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
+    int heads = 0, rheads = 0;
+#pragma unroll
+    for (int b = 0; b < kShare / NACHO_WAVE; ++b) {
+        const int i = wave * kShare + b * NACHO_WAVE + lane;
+        if (i - lane >= n) break;
+        const bool valid = i < n;
+        const int inf = valid ? (int)w.info[i] : 0x8000;
+        const bool head = !(inf >> 15);
+        const unsigned long long hm = __ballot(head);
+        uint32_t word = (uint32_t)(heads + __popcll(hm & below));
+        heads += __popcll(hm);
+        if (FMT == SPADD_DCSR) {
+            const uint32_t rw = row_of(keys[inf & 0xfff]);
+            const uint32_t prow = (valid && i > 0) ? row_of(keys[w.info[i - 1] & 0xfff]) : 0u;
+            const bool rhead = head && (i == 0 ? !cont : rw != prow);
+            const unsigned long long rm = __ballot(rhead);
+            word |= (uint32_t)(rheads + __popcll(rm & below)) << 16;
+            word |= rhead ? 0x80000000u : 0u;
+            rheads += __popcll(rm);
+        }
+        if (valid) w.marks[i] = word;
+    }
+    if (lane == 0) w.wave_cnt[wave] = pack_counts(rheads, heads);
+
+    // the values of this thread's entries: in flight during the prefix look-up
+    T val[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        val[r] = T(0);
+        if (c < n) val[r] = reinterpret_cast<const T *>((uintptr_t)w.sval[tr[r]])[c];
+    }
+    __syncthreads();
+
+    // ---- 4. prefix sum over the workgroups ------------------------------------
+    // Wavefront 0 publishes the partition's counts and reads the counts of
+    // everything before the partition.
+    if (wave == 0) {
+        unsigned long long tot = 0;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) tot += w.wave_cnt[ww];
+        long long b_rows = 0, b_nnz = 0;
+        bool gave_up = false;
+        const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
+        unsigned long long *totals = tile_state;                                        // one per chunk
+        unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
+        if (lane == 0)
+            __hip_atomic_store(&words[p], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int64_t chunk = p / kChunk, c0 = chunk * kChunk;
         {
-            // inclusive prefix sum of the marks (bits 0..15) over all runs at once; a
-            // lane owns R consecutive words, the other bits stay
-            int v[R], sum = 0;
-            const int at = lane * (R + (R >> kPadShift));
+            // words of the workgroups before this one in its chunk, all loads in flight together
+            const int m = (int)(p - c0);
+            int spins = 0;
+            for (;;) {
+                unsigned v[kChunk / NACHO_WAVE];
+                bool missing = false;
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                v[j] = w.marks[at + j];
-                sum += v[j] & 0xffff;
+                for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+                    const int j = i * NACHO_WAVE + lane;
+                    v[i] = kWordValid;
+                    if (i * NACHO_WAVE < m && j < m)
+                        v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                int l_nnz = 0, l_rows = 0;
+#pragma unroll
+                for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+                    missing = missing || !(v[i] & kWordValid);
+                    l_nnz += (int)(v[i] & 0x3fffu);
+                    l_rows += (int)((v[i] >> 14) & 0x3fffu);
+                }
+                if (__ballot(missing)) {                   // a predecessor has not published yet
+                    if (++spins > kSpinLimit) { gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(16);
+                    continue;
+                }
+                b_nnz = wave_sum<int>(l_nnz);
+                b_rows = wave_sum<int>(l_rows);
+                break;
             }
-            int run = wave_inclusive_scan(sum) - sum;
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                run += v[j] & 0xffff;
-                w.marks[at + j] = (v[j] & 0xffff0000) | run;
+        }
+        if (!gave_up && (p == c0 + kChunk - 1 || p == P - 1) && lane == 0)
+            __hip_atomic_store(&totals[chunk], kTotalValid | pack_counts(b_rows + t_rows, b_nnz + t_nnz),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!gave_up && chunk > 0) {
+            // totals of the chunks before this one
+            int spins = 0;
+            long long c_nnz = 0, c_rows = 0;
+            for (int64_t first = 0; first < chunk && !gave_up; ) {
+                const int64_t j = first + lane;
+                unsigned long long s = kTotalValid;
+                if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__ballot(!(s & kTotalValid))) {
+                    if (++spins > kSpinLimit) { gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(16);
+                    continue;
+                }
+                c_nnz += wave_sum<long long>((long long)(s & 0x7fffffffull));
+                c_rows += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
+                first += NACHO_WAVE;
+            }
+            b_nnz += c_nnz;
+            b_rows += c_rows;
+        }
+        if (lane == 0) {
+            w.base = pack_counts(b_rows, b_nnz);
+            if (gave_up) *out.status = NACHO_ERR_HIP;
+            if (broken) *out.status = NACHO_ERR_INVALID_ARG;
+            if (p == P - 1) {
+                // totals, tails and the capacity verdict (the only writer of these words)
+                const long long total_nnz = b_nnz + t_nnz;
+                const long long total_rows = FMT == SPADD_DCSR ? b_rows + t_rows
+                                                               : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
+                out.counts[0] = total_rows;
+                out.counts[1] = total_nnz;
+                const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
+                if (!fits) *out.status = NACHO_ERR_CAPACITY;
+                if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
+                if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
+                if (FMT == SPADD_DCSR) {
+                    out.pos0[0] = 0;
+                    out.pos0[1] = (int32_t)total_rows;
+                    if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
+                }
             }
         }
-        wave_sync();
-        if (lane < K) {
-            const int o = w.soff[lane];
-            w.srun[lane] = o | ((o > 0 ? (w.marks[pad(o - 1)] & 0xffff) : 0) << 16);
-        }
-        wave_sync();
-        int slot[R];                           // merged slot | duplicate << 15
+    }
+    __syncthreads();
+    // offsets of the wavefronts' shares of the merged order
+    long long share_nnz[kWaves + 1], share_rows[kWaves + 1];
+    share_nnz[0] = (long long)(w.base & 0x7fffffffull);
+    share_rows[0] = (long long)((w.base >> 31) & 0x7fffffffull);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            const int mk = w.marks[pad(c)];
-            const int sr = w.srun[tr[r]];
-            const int m = (c - (sr & 0xffff)) + ((mk >> kDirectShift) & 0x7ff) + ((mk & 0xffff) - (sr >> 16));
-            const int dup = ((mk >> kDupShift) & 0xf) ? 0x8000 : 0;
-            slot[r] = m | dup;
-        }
-        wave_sync();                           // all ranking words are read: the assembly may overwrite them
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            if (c < n) w.info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
-        }
-        wave_sync();
+    for (int ww = 0; ww < kWaves; ++ww) {
+        share_nnz[ww + 1] = share_nnz[ww] + (long long)(w.wave_cnt[ww] & 0x7fffffffull);
+        share_rows[ww + 1] = share_rows[ww] + (long long)((w.wave_cnt[ww] >> 31) & 0x7fffffffull);
+    }
 
-        // ---- 3. assembly: heads and row heads before every merged slot ------------------
-        bool cont = false;                 // the partition starts inside a row whose head is elsewhere
-        if (D == 2 && active) cont = row_continues<FMT>(ops, coord, posn, p);
-        int heads = 0, rheads = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = r * NACHO_WAVE + lane;
-            if (r * NACHO_WAVE >= n) break;
-            const bool valid = i < n;
-            const int inf = valid ? (int)w.info[i] : 0x8000;
-            const bool head = !(inf >> 15);
-            const unsigned long long hm = __ballot(head);
-            int word = heads + __popcll(hm & below);
-            heads += __popcll(hm);
-            if (FMT == SPADD_DCSR) {
-                const uint32_t rw = row_of(keys[inf & 1023]);
-                const uint32_t prow = (valid && i > 0) ? row_of(keys[w.info[i - 1] & 1023]) : 0u;
-                const bool rhead = head && (i == 0 ? !cont : rw != prow);
-                const unsigned long long rm = __ballot(rhead);
-                word |= (rheads + __popcll(rm & below)) << 16;
-                word |= rhead ? (int)0x80000000 : 0;
-                rheads += __popcll(rm);
+    // ---- 5. compute: write the partition's output ------------------------------
+    if (FMT == SPADD_CSR) {
+        // pos of every row that starts inside this partition: offset of the first
+        // output entry whose row is not smaller
+        const int first = coord[p * 2] + (cont ? 1 : 0);
+        const int next_first = coord[(p + 1) * 2] + (row_continues<FMT>(ops, coord, posn, p + 1) ? 1 : 0);
+        for (int rr = first + tid; rr < next_first; rr += kThreads) {
+            int l = 0, h = n;
+            while (l < h) {
+                const int m = (l + h) >> 1;
+                if (row_of(keys[w.info[m] & 0xfff]) < (uint32_t)rr) l = m + 1; else h = m;
             }
-            if (valid) w.marks[i] = word;
+            long long at = share_nnz[kWaves];              // past the last entry of the partition
+            if (l < n) {
+                at = (long long)(w.marks[l] & 0xffffu);
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww)
+                    if (l / kShare == ww) at += share_nnz[ww];
+            }
+            out.pos1[rr] = (int32_t)at;
         }
-
-        // the values of this lane's entries: in flight during the look-back
-        T val[R];
+        __syncthreads();                       // keys are read: the duplicates' values may overwrite them
+    }
+    T *dv = w.dups();
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            val[r] = T(0);
-            if (c < n) val[r] = reinterpret_cast<const T *>((uintptr_t)w.sval[tr[r]])[c];
+    for (int r = 0; r < R; ++r)
+        if (slot[r] & 0x8000) dv[slot[r] & 0x7fff] = val[r];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        if (c >= n || (slot[r] & 0x8000)) continue;
+        const int m = slot[r];
+        const uint32_t word = w.marks[m];
+        T sum = val[r];                    // then the duplicates, which follow in operand order
+        bool more = true;
+#pragma unroll
+        for (int g = 1; g < K; ++g) {
+            more = more && m + g < n && (w.info[m + g < kTile ? m + g : kTile - 1] >> 15);
+            if (more) sum += dv[m + g];
         }
-
-        // ---- 4. prefix sum over the workgroups ------------------------------------
-        // The wavefronts pool their counts; wavefront 0 publishes them and reads the
-        // counts of everything before the workgroup.
-        if (lane == 0) s_cnt[parity][wave] = pack_counts(rheads, heads);
-        __syncthreads();
-        if (wave == 0) {
-            unsigned long long tot = 0;
+        long long wpos = (long long)(word & 0xffffu), wr = (long long)((word >> 16) & 0x7fffu);
 #pragma unroll
-            for (int ww = 0; ww < kWavesPerGroup; ++ww) tot += s_cnt[parity][ww];
-            long long b_rows = 0, b_nnz = 0;
-            bool gave_up = false;
-            const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
-            unsigned long long *totals = tile_state;                                        // one per chunk
-            unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
-            if (lane == 0)
-                __hip_atomic_store(&words[group], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int64_t chunk = group / kChunk, c0 = chunk * kChunk;
-            {
-                // words of the workgroups before this one in its chunk, all loads in flight together
-                const int m = (int)(group - c0);
-                int spins = 0;
-                for (;;) {
-                    unsigned v[kChunk / NACHO_WAVE];
-                    bool missing = false;
-#pragma unroll
-                    for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
-                        const int j = i * NACHO_WAVE + lane;
-                        v[i] = kWordValid;
-                        if (i * NACHO_WAVE < m && j < m)
-                            v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                    int l_nnz = 0, l_rows = 0;
-#pragma unroll
-                    for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
-                        missing = missing || !(v[i] & kWordValid);
-                        l_nnz += (int)(v[i] & 0x3fffu);
-                        l_rows += (int)((v[i] >> 14) & 0x3fffu);
-                    }
-                    if (__ballot(missing)) {                   // a predecessor has not published yet
-                        if (++spins > kSpinLimit) { gave_up = true; break; }
-                        __builtin_amdgcn_s_sleep(16);
-                        continue;
-                    }
-                    b_nnz = wave_sum<int>(l_nnz);
-                    b_rows = wave_sum<int>(l_rows);
-                    break;
-                }
-            }
-            if (!gave_up && (group == c0 + kChunk - 1 || group == n_groups - 1) && lane == 0)
-                __hip_atomic_store(&totals[chunk], kTotalValid | pack_counts(b_rows + t_rows, b_nnz + t_nnz),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (!gave_up && chunk > 0) {
-                // totals of the chunks before this one
-                int spins = 0;
-                long long c_nnz = 0, c_rows = 0;
-                for (int64_t first = 0; first < chunk && !gave_up; ) {
-                    const int64_t j = first + lane;
-                    unsigned long long s = kTotalValid;
-                    if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (__ballot(!(s & kTotalValid))) {
-                        if (++spins > kSpinLimit) { gave_up = true; break; }
-                        __builtin_amdgcn_s_sleep(16);
-                        continue;
-                    }
-                    c_nnz += wave_sum<long long>((long long)(s & 0x7fffffffull));
-                    c_rows += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
-                    first += NACHO_WAVE;
-                }
-                b_nnz += c_nnz;
-                b_rows += c_rows;
-            }
-            if (lane == 0) {
-                s_base[parity] = pack_counts(b_rows, b_nnz);
-                if (gave_up) *out.status = NACHO_ERR_HIP;
-                if (group == n_groups - 1) {
-                    // totals, tails and the capacity verdict (the only writer of these words)
-                    const long long total_nnz = b_nnz + t_nnz;
-                    const long long total_rows = FMT == SPADD_DCSR ? b_rows + t_rows
-                                                                   : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
-                    out.counts[0] = total_rows;
-                    out.counts[1] = total_nnz;
-                    const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
-                    if (!fits) *out.status = NACHO_ERR_CAPACITY;
-                    if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
-                    if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
-                    if (FMT == SPADD_DCSR) {
-                        out.pos0[0] = 0;
-                        out.pos0[1] = (int32_t)total_rows;
-                        if (total_rows <= out.cap_rows) out.pos1[total_rows] = (int32_t)total_nnz;
-                    }
-                }
-            }
+        for (int ww = 0; ww < kWaves; ++ww)
+            if (m / kShare == ww) { wpos += share_nnz[ww]; wr += share_rows[ww]; }
+        if (wpos < out.cap_nnz) {
+            out.crd1[wpos] = col[r];
+            static_cast<T *>(out.val)[wpos] = sum;
         }
-        __syncthreads();
-        unsigned long long mine = s_base[parity];
-#pragma unroll
-        for (int ww = 0; ww < kWavesPerGroup; ++ww)
-            if (ww < wave) mine += s_cnt[parity][ww];
-        const long long base_nnz = (long long)(mine & 0x7fffffffull);
-        const long long base_rows = (long long)((mine >> 31) & 0x7fffffffull);
-        if (broken && lane == 0) *out.status = NACHO_ERR_INVALID_ARG;
-        if (!active) return;
-
-        // ---- 5. compute: write the partition's output ------------------------------
-        wave_sync();                           // assembly words are visible
-        if (FMT == SPADD_CSR) {
-            // pos of every row that starts inside this partition: offset of the first
-            // output entry whose row is not smaller
-            const int first = coord[p * 2] + (cont ? 1 : 0);
-            const int next_first = coord[(p + 1) * 2] + (row_continues<FMT>(ops, coord, posn, p + 1) ? 1 : 0);
-            for (int rr = first + lane; rr < next_first; rr += NACHO_WAVE) {
-                int l = 0, h = n;
-                while (l < h) {
-                    const int m = (l + h) >> 1;
-                    if (row_of(keys[w.info[m] & 1023]) < (uint32_t)rr) l = m + 1; else h = m;
-                }
-                out.pos1[rr] = (int32_t)(base_nnz + (l < n ? (w.marks[l] & 0xffff) : heads));
-            }
-            wave_sync();                       // keys are read: the duplicates' values may overwrite them
-        }
-        T *dv = w.dups();
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (slot[r] & 0x8000) dv[slot[r] & 0x7fff] = val[r];
-        wave_sync();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * NACHO_WAVE + lane;
-            if (c >= n || (slot[r] & 0x8000)) continue;
-            const int m = slot[r];
-            const int word = w.marks[m];
-            T sum = val[r];                    // then the duplicates, which follow in operand order
-            bool more = true;
-#pragma unroll
-            for (int g = 1; g < K; ++g) {
-                more = more && m + g < n && (w.info[m + g < CAP ? m + g : CAP - 1] >> 15);
-                if (more) sum += dv[m + g];
-            }
-            const long long wpos = base_nnz + (word & 0xffff);
-            if (wpos < out.cap_nnz) {
-                out.crd1[wpos] = col[r];
-                static_cast<T *>(out.val)[wpos] = sum;
-            }
-            if (FMT == SPADD_DCSR && word < 0) {
-                const long long wr = base_rows + ((word >> 16) & 0x7fff);
-                if (wr < out.cap_rows) {
-                    out.crd0[wr] = (int32_t)row[r];
-                    out.pos1[wr] = (int32_t)wpos;
-                }
+        if (FMT == SPADD_DCSR && (word >> 31)) {
+            if (wr < out.cap_rows) {
+                out.crd0[wr] = (int32_t)row[r];
+                out.pos1[wr] = (int32_t)wpos;
             }
         }
     }
@@ -620,17 +649,14 @@ spadd_reset_kernel(int64_t n_words, unsigned long long *__restrict__ tile_state,
     if (i == 0) *status = NACHO_OK;
 }
 
-int64_t groups_of(int64_t P) { return (P + kWavesPerGroup - 1) / kWavesPerGroup; }
-int64_t chunks_of(int64_t P) { return (groups_of(P) + kChunk - 1) / kChunk; }
+int64_t chunks_of(int64_t P) { return (P + kChunk - 1) / kChunk; }
 
 template <int FMT, typename T, int K>
 hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                       const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    const int64_t n_groups = groups_of(P);
-    const unsigned grid = (unsigned)n_groups;
-    hipLaunchKernelGGL((spadd_kernel<FMT, T, K>), dim3(grid), dim3(kWavesPerGroup * NACHO_WAVE), 0, s, ops, vals,
-                       P, n_groups, chunks_of(P), coord, posn, tile_state, out);
+    hipLaunchKernelGGL((spadd_kernel<FMT, T, K>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
+                       P, chunks_of(P), coord, posn, tile_state, out);
     return hipGetLastError();
 }
 
@@ -647,10 +673,10 @@ hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P
 
 }  // namespace
 
-int spadd_capacity(int fmt) { return fmt == SPADD_VECTOR ? kSpaddCapVector : kSpaddCapMatrix; }
+int spadd_capacity(int fmt) { (void)fmt; return kSpaddCap; }
 
 // 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup
-int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (groups_of(P) + 1) / 2; }
+int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (P + 1) / 2; }
 
 hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s)
 {
