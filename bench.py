@@ -163,11 +163,64 @@ def bench_spmv(args):
     }
 
 
+def bench_others(steps, warmup):
+    """Configurations 3, 4 and 5 of the benchmark spec, one fused call per step, same timing
+    protocol; algorithmic bytes = every input array once + every output array once."""
+    import torch
+    from paper_2604_17198_amd import binding as nb
+    from paper_2604_17198_amd import workloads
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+    res = {}
+
+    def record(tag, what, fn, nnz, nbytes):
+        ms, _ = _time_steps(fn, steps, warmup)
+        res[tag] = {"workload": what, "ms_per_step": ms, "nnz_per_s": nnz / (ms * 1e-3),
+                    "GBps_algorithmic": nbytes / ms / 1e6,
+                    "frac_of_hbm_peak": nbytes / ms / 1e6 / PEAK_HBM_GBS,
+                    "kernel_ms": _kernel_ms(fn, 5)}
+
+    for c, fmt in ((3, "vector"), (4, "dcsr")):
+        cfg = workloads.config(c)
+        if fmt == "vector":
+            ops = [nb.vector(dev(v["i"]), v["extent"], dev(v["v"])) for v in cfg["ops"]]
+            rows = 0
+        else:
+            ops = [nb.dcsr(dev(m["pos0"]), dev(m["crd0"]), dev(m["pos1"]), dev(m["crd1"]),
+                           m["n_rows"], m["n_cols"], dev(m["val"])) for m in cfg["ops"]]
+            rows = sum(int(m["crd0"].shape[0]) for m in cfg["ops"])
+        tot = sum(o.nnz for o in ops)
+        out = nb.SparseOut(fmt, rows, tot, torch.float32, "cuda")
+        ws = torch.empty(nb.workspace_bytes(nb.OP_SPADD, ops, nb.F32), dtype=torch.uint8, device="cuda")
+        fn = lambda: nb.nacho_spadd_k(ops, out, ws=ws)
+        fn()
+        torch.cuda.synchronize()
+        n_rows_out, n_out = (int(v) for v in out.counts.cpu().numpy())
+        nbytes = tot * 8 + n_out * 8 + (rows * 8 + n_rows_out * 8 if fmt == "dcsr" else 0)
+        what = ("C3: 3 sparse vectors (10M + 1M + 100k nnz, index space 2^30), fp32 union add" if c == 3 else
+                "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
+        record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        del ops, out, ws, cfg
+    cfg = workloads.config(5)
+    A = cfg["A"]
+    op = nb.csr(dev(A["pos"]), dev(A["crd"]), A["n_rows"], A["n_cols"], dev(A["val"]))
+    B = dev(cfg["B"])
+    C = torch.empty((A["n_rows"], 64), dtype=torch.float32, device="cuda")
+    ws = torch.empty(nb.workspace_bytes(nb.OP_SPMM, [op], nb.F32, 64), dtype=torch.uint8, device="cuda")
+    nnz = int(A["pos"][-1])
+    nbytes = nnz * 8 + (A["n_rows"] + 1) * 4 + A["n_cols"] * 64 * 4 + A["n_rows"] * 64 * 4
+    record("C5", f"C5: CSR (1,000,000 x 1,000,000, {nnz} nnz) x dense 1,000,000 x 64, fp32 SpMM",
+           lambda: nb.nacho_spmm(op, B, C, ws=ws), nnz, nbytes)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time configuration 2 only (skip the other configurations)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run two device-to-device copies of 256 MiB (a kernel of known "
                          "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -179,6 +232,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     out = bench_spmv(args)
+    if not args.headline_only:
+        out["workloads"] = bench_others(max(5, args.steps // 5), 2)
     if args.calibrate_copy:
         a = torch.zeros(32 * 1024 * 1024, dtype=torch.float64, device="cuda")
         b = torch.empty_like(a)

@@ -358,9 +358,9 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     const int f = spadd_fmt(fmt);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     profile_begin(s);
-    if (launch_spadd_reset(Pe, w.tile_state, o.status, s) != hipSuccess) return NACHO_ERR_HIP;
-    profile_mark("spadd_reset");
-    if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+    // the partition kernel also clears the prefix-sum state and the status word of the call
+    if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s,
+                         w.tile_state, spadd_state_words(Pe), o.status) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
     if (launch_spadd(f, dtype, dev, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, o, s) != hipSuccess)

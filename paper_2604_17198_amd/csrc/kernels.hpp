@@ -7,9 +7,14 @@ namespace nacho {
 // Algorithm 1 for boundaries 0..P.  `queries` (device, may be NULL) overrides
 // the built-in queries; otherwise Q_p = min(p*grain, total) when grain > 0 and
 // floor(p*total/P) when grain == 0 (total = total_unscaled * cost_scale).
+// `clear_words` (may be NULL): n_clear 64-bit words the kernel sets to zero on the side, and
+// `clear_status` (may be NULL) a status word it sets to NACHO_OK: the state of the kernels that
+// follow it in a fused call.
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
-                            int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream);
+                            int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
+                            unsigned long long *clear_words = nullptr, int64_t n_clear = 0,
+                            int32_t *clear_status = nullptr);
 
 // Items one wavefront can stage for SpMV (partition work must not exceed it).
 int spmv_capacity(int dtype);
@@ -46,8 +51,6 @@ struct SpaddOut {
 int spadd_capacity(int fmt);
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
-// Clears the per-call prefix-sum state and the status word.
-hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s);
 // Count, prefix sum and fill in one kernel, one wavefront per partition.
 hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
                         const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,

@@ -30,6 +30,19 @@ namespace nacho {
 
 namespace {
 
+// Words of the call's later kernels that the partition kernel clears on the side
+// (it is the first kernel of every fused call): thread i clears word i.
+struct ClearWords {
+    unsigned long long *words;
+    int64_t n;
+    int32_t *status;
+    __device__ void run(int64_t i) const
+    {
+        if (i < n) words[i] = 0ull;
+        if (i == 0 && status) *status = NACHO_OK;
+    }
+};
+
 struct LevelResult {
     int64_t x;  // chosen coordinate
     int64_t c;  // C_m(x | prefix), unscaled
@@ -410,8 +423,10 @@ template <int K>
 __global__ void __launch_bounds__(256)
 partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                  const int64_t *__restrict__ queries, int64_t total_unscaled,
-                 int32_t *__restrict__ coord, int32_t *__restrict__ posn, int64_t *__restrict__ cost)
+                 int32_t *__restrict__ coord, int32_t *__restrict__ posn, int64_t *__restrict__ cost,
+                 ClearWords clear)
 {
+    clear.run((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
     const int64_t b0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE) * kGroup;
     if (b0 > P) return;                      // whole wavefront leaves together
     const int lane = lane_id();
@@ -570,9 +585,10 @@ struct QueryRule {
 __global__ void __launch_bounds__(256)
 partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
                       int64_t count, QueryRule rule, int64_t cost_scale, int32_t *__restrict__ coord,
-                      int32_t *__restrict__ posn, int64_t *__restrict__ cost)
+                      int32_t *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    clear.run(i);
     const int lane = lane_id();
     const int64_t P = rule.P;
     const int32_t p0 = pos[0];
@@ -623,8 +639,13 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
 
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
-                            int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream)
+                            int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
+                            unsigned long long *clear_words, int64_t n_clear, int32_t *clear_status)
 {
+    ClearWords clear;
+    clear.words = clear_words;
+    clear.n = clear_words ? n_clear : 0;
+    clear.status = clear_status;
     if (ops.k == 1 && ops.d == 2 && ops.lvl[0][0].kind == NACHO_DENSE && !queries &&
         (grain == 0 || grain % cost_scale == 0)) {
         QueryRule rule;
@@ -632,31 +653,33 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
         rule.total = total_unscaled;
         rule.grain_u = grain / cost_scale;
         const int64_t n_rows = ops.lvl[0][0].extent;
-        const int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
+        int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
+        if (clear.n > threads) threads = clear.n;
         hipLaunchKernelGGL(partition_csr1_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            ops.lvl[0][1].pos, ops.lvl[0][1].crd, n_rows, ops.lvl[0][1].count, rule, cost_scale,
-                           coord, posn, cost);
+                           coord, posn, cost, clear);
         return hipGetLastError();
     }
-    const int64_t waves = (P + 1 + kGroup - 1) / kGroup;
+    int64_t waves = (P + 1 + kGroup - 1) / kGroup;
+    if (clear.n > waves * NACHO_WAVE) waves = (clear.n + NACHO_WAVE - 1) / NACHO_WAVE;
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);
     // instantiated for 1, 2, 3, 4 and 8 operands so that small calls keep their state in registers
     if (ops.k <= 1)
         hipLaunchKernelGGL(partition_kernel<1>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
-                           queries, total_unscaled, coord, posn, cost);
+                           queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 2)
         hipLaunchKernelGGL(partition_kernel<2>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
-                           queries, total_unscaled, coord, posn, cost);
+                           queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 3)
         hipLaunchKernelGGL(partition_kernel<3>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
-                           queries, total_unscaled, coord, posn, cost);
+                           queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 4)
         hipLaunchKernelGGL(partition_kernel<4>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
-                           queries, total_unscaled, coord, posn, cost);
+                           queries, total_unscaled, coord, posn, cost, clear);
     else
         hipLaunchKernelGGL(partition_kernel<8>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
-                           queries, total_unscaled, coord, posn, cost);
+                           queries, total_unscaled, coord, posn, cost, clear);
     return hipGetLastError();
 }
 

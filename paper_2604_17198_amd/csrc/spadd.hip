@@ -639,16 +639,6 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     }
 }
 
-// Clears the published counts of a call (n_words 64-bit words) and the status.
-__global__ void __launch_bounds__(256)
-spadd_reset_kernel(int64_t n_words, unsigned long long *__restrict__ tile_state,
-                   int32_t *__restrict__ status)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_words) tile_state[i] = 0ull;
-    if (i == 0) *status = NACHO_OK;
-}
-
 int64_t chunks_of(int64_t P) { return (P + kChunk - 1) / kChunk; }
 
 template <int FMT, typename T, int K>
@@ -677,14 +667,6 @@ int spadd_capacity(int fmt) { (void)fmt; return kSpaddCap; }
 
 // 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup
 int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (P + 1) / 2; }
-
-hipError_t launch_spadd_reset(int64_t P, unsigned long long *tile_state, int32_t *status, hipStream_t s)
-{
-    const int64_t n_words = spadd_state_words(P);
-    const unsigned grid = (unsigned)((n_words + 255) / 256);
-    hipLaunchKernelGGL(spadd_reset_kernel, dim3(grid ? grid : 1), dim3(256), 0, s, n_words, tile_state, status);
-    return hipGetLastError();
-}
 
 hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
                         const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
