@@ -125,7 +125,10 @@ __device__ inline int pad(int x) { return x + (x >> kPadShift); }
 constexpr int kDupShift = 16, kDirectShift = 20;
 // Word of a merged slot in `marks` after the assembly (counts inside the slot's wavefront share):
 //   bits 0..15 heads before the slot, 16..30 row heads before it, 31 the slot starts a row
-template <typename KeyT, typename T>
+// kPacked (vectors): the descriptors and the assembly words (16 bits are enough
+// without row counts) share the memory of the ranking words, which are dead by
+// then; the workgroup then needs little enough LDS for four of them per CU.
+template <typename KeyT, typename T, bool kPacked>
 struct Tile {
     union {
         KeyT keys[kTile];                 // the k runs, one after the other
@@ -133,7 +136,7 @@ struct Tile {
     };
     T dupval_wide[sizeof(T) <= sizeof(KeyT) ? 1 : kTile];
     uint32_t marks[kPadded];              // staging: row markers; ranking words (padded); assembly words
-    uint16_t info[kTile];                 // merged order: position in keys (0..11) | duplicate (15)
+    uint16_t info_own[kPacked ? 1 : kTile];   // merged order: position in keys (0..11) | duplicate (15)
     unsigned long long scrd[NACHO_MAX_OPERANDS];   // address of crd of run t, biased so that [c] is entry c of keys
     unsigned long long sval[NACHO_MAX_OPERANDS];   // the same for the values
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
@@ -142,6 +145,16 @@ struct Tile {
     unsigned long long wave_cnt[kWaves];           // per-wavefront counts of the assembly (rows << 31 | nnz)
     unsigned long long base;                       // the partition's offset (rows << 31 | nnz)
     __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
+    __device__ uint16_t *info() { return kPacked ? reinterpret_cast<uint16_t *>(marks) : info_own; }
+    __device__ void set_word(int slot, uint32_t word)
+    {
+        if (kPacked) reinterpret_cast<uint16_t *>(marks)[kTile + slot] = (uint16_t)word;
+        else marks[slot] = word;
+    }
+    __device__ uint32_t word(int slot) const
+    {
+        return kPacked ? (uint32_t)reinterpret_cast<const uint16_t *>(marks)[kTile + slot] : marks[slot];
+    }
 };
 
 // Does boundary b fall strictly inside a row, i.e. does some operand hold an
@@ -168,46 +181,38 @@ __device__ inline bool row_continues(const DevOperands &ops, const int32_t *coor
 // Is run u the larger one of the pair (t, u)?  (Ties: the higher index.)
 __device__ inline bool larger_run(int nu, int u, int nt, int t) { return nu > nt || (nu == nt && u > t); }
 
-// Ranking of NI consecutive 64-entry blocks of run t, starting at entry r0:
-// searches in every larger run.
-template <typename KeyT, int NI, typename Tile>
-__device__ inline void rank_blocks(Tile &w, int k, int t, int r0, int lane)
+// Ranking of NI consecutive 64-entry blocks of run t, starting at entry r0,
+// against the larger run u: one search per entry.
+template <typename KeyT, int NI, typename TileT>
+__device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
 {
     const int off_t = uni(w.soff[t]), nt = uni(w.soff[t + 1]) - off_t;
+    const int off_u = uni(w.soff[u]), nu = uni(w.soff[u + 1]) - off_u;
     KeyT key[NI];
     bool valid[NI];
-    int direct[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int il = r0 + i * NACHO_WAVE + lane;
         valid[i] = il < nt;
         key[i] = valid[i] ? w.keys[off_t + il] : KeyT(0);
-        direct[i] = 0;
     }
-    for (int u = 0; u < k; ++u) {
-        const int off_u = uni(w.soff[u]), nu = uni(w.soff[u + 1]) - off_u;
-        if (u == t || !larger_run(nu, u, nt, t)) continue;
-        int lb[NI];
-        run_lower_bound<KeyT, NI>(w.keys + off_u, nu, key, lb);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const KeyT at = w.keys[off_u + (lb[i] < nu ? lb[i] : nu - 1)];
-            const int eq = (lb[i] < nu && at == key[i]) ? 1 : 0;
-            if (u < t) {
-                // run u wins ties: its equal entry precedes this one, which is a duplicate
-                direct[i] += ((lb[i] + eq) << kDirectShift) + (eq << kDupShift);
-                if (valid[i] && lb[i] + eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + eq)], 1u);
-            } else {
-                // this entry precedes u's entries from position lb on; an equal one there is a duplicate
-                direct[i] += lb[i] << kDirectShift;
-                if (valid[i] && lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1u + ((unsigned)eq << kDupShift));
-            }
-        }
-    }
+    int lb[NI];
+    run_lower_bound<KeyT, NI>(w.keys + off_u, nu, key, lb);
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
+        if (!valid[i]) continue;
         const int il = r0 + i * NACHO_WAVE + lane;
-        if (valid[i]) atomicAdd(&w.marks[pad(off_t + il)], (unsigned)direct[i]);
+        const KeyT at = w.keys[off_u + (lb[i] < nu ? lb[i] : nu - 1)];
+        const unsigned eq = (lb[i] < nu && at == key[i]) ? 1u : 0u;
+        if (u < t) {
+            // run u wins ties: its equal entry precedes this one, which is a duplicate
+            if (lb[i] + (int)eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + (int)eq)], 1u);
+            atomicAdd(&w.marks[pad(off_t + il)], (((unsigned)lb[i] + eq) << kDirectShift) + (eq << kDupShift));
+        } else {
+            // this entry precedes u's entries from position lb on; an equal one there is a duplicate
+            if (lb[i] < nu) atomicAdd(&w.marks[pad(off_u + lb[i])], 1u + (eq << kDupShift));
+            if (lb[i] > 0) atomicAdd(&w.marks[pad(off_t + il)], (unsigned)lb[i] << kDirectShift);
+        }
     }
 }
 
@@ -221,7 +226,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
     constexpr int R = kPerThread;
     constexpr int kShare = kTile / kWaves;     // merged slots a wavefront walks in the assembly
-    __shared__ Tile<KeyT, T> w;
+    __shared__ Tile<KeyT, T, FMT == SPADD_VECTOR> w;
+    uint16_t *info = w.info();
 
     const int tid = threadIdx.x;
     const int lane = lane_id();
@@ -378,15 +384,22 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         if (t == 0 || (t < k && larger_run(nt, t, n_max, t_max))) { n_max = nt; t_max = t; }
     }
     {
-        int unit = 0;                          // units of work are dealt out to the wavefronts in turn
+        // every pair (smaller run t, larger run u) and every block of t is a unit of
+        // work; the units are dealt out to the wavefronts in turn
+        int unit = 0;
         for (int t = 0; t < k; ++t) {
             if (t == t_max) continue;
             const int nt = uni(w.soff[t + 1]) - uni(w.soff[t]);
-            int r0 = 0;
-            for (; r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE, ++unit)
-                if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4>(w, k, t, r0, lane);
-            for (; r0 < nt; r0 += NACHO_WAVE, ++unit)
-                if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1>(w, k, t, r0, lane);
+            for (int u = 0; u < k; ++u) {
+                if (u == t || !larger_run(uni(w.soff[u + 1]) - uni(w.soff[u]), u, nt, t)) continue;
+                int r0 = 0;
+                // a long run is searched four blocks at a time (the chains of LDS reads
+                // overlap), a short one block by block (more wavefronts share it)
+                for (; nt > 8 * NACHO_WAVE && r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE, ++unit)
+                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4>(w, t, u, r0, lane);
+                for (; r0 < nt; r0 += NACHO_WAVE, ++unit)
+                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1>(w, t, u, r0, lane);
+            }
         }
     }
     __syncthreads();
@@ -434,7 +447,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int c = r * kThreads + tid;
-        if (c < n) w.info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
+        if (c < n) info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
     }
     __syncthreads();
 
@@ -449,21 +462,21 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const int i = wave * kShare + b * NACHO_WAVE + lane;
         if (i - lane >= n) break;
         const bool valid = i < n;
-        const int inf = valid ? (int)w.info[i] : 0x8000;
+        const int inf = valid ? (int)info[i] : 0x8000;
         const bool head = !(inf >> 15);
         const unsigned long long hm = __ballot(head);
         uint32_t word = (uint32_t)(heads + __popcll(hm & below));
         heads += __popcll(hm);
         if (FMT == SPADD_DCSR) {
             const uint32_t rw = row_of(keys[inf & 0xfff]);
-            const uint32_t prow = (valid && i > 0) ? row_of(keys[w.info[i - 1] & 0xfff]) : 0u;
+            const uint32_t prow = (valid && i > 0) ? row_of(keys[info[i - 1] & 0xfff]) : 0u;
             const bool rhead = head && (i == 0 ? !cont : rw != prow);
             const unsigned long long rm = __ballot(rhead);
             word |= (uint32_t)(rheads + __popcll(rm & below)) << 16;
             word |= rhead ? 0x80000000u : 0u;
             rheads += __popcll(rm);
         }
-        if (valid) w.marks[i] = word;
+        if (valid) w.set_word(i, word);
     }
     if (lane == 0) w.wave_cnt[wave] = pack_counts(rheads, heads);
 
@@ -591,11 +604,11 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             int l = 0, h = n;
             while (l < h) {
                 const int m = (l + h) >> 1;
-                if (row_of(keys[w.info[m] & 0xfff]) < (uint32_t)rr) l = m + 1; else h = m;
+                if (row_of(keys[info[m] & 0xfff]) < (uint32_t)rr) l = m + 1; else h = m;
             }
             long long at = share_nnz[kWaves];              // past the last entry of the partition
             if (l < n) {
-                at = (long long)(w.marks[l] & 0xffffu);
+                at = (long long)(w.word(l) & 0xffffu);
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww)
                     if (l / kShare == ww) at += share_nnz[ww];
@@ -614,12 +627,12 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const int c = r * kThreads + tid;
         if (c >= n || (slot[r] & 0x8000)) continue;
         const int m = slot[r];
-        const uint32_t word = w.marks[m];
+        const uint32_t word = w.word(m);
         T sum = val[r];                    // then the duplicates, which follow in operand order
         bool more = true;
 #pragma unroll
         for (int g = 1; g < K; ++g) {
-            more = more && m + g < n && (w.info[m + g < kTile ? m + g : kTile - 1] >> 15);
+            more = more && m + g < n && (info[m + g < kTile ? m + g : kTile - 1] >> 15);
             if (more) sum += dv[m + g];
         }
         long long wpos = (long long)(word & 0xffffu), wr = (long long)((word >> 16) & 0x7fffu);
