@@ -48,25 +48,6 @@ struct LevelResult {
     int64_t c;  // C_m(x | prefix), unscaled
 };
 
-__device__ inline int64_t wave_max64(int64_t v)
-{
-#pragma unroll
-    for (int off = NACHO_WAVE / 2; off > 0; off >>= 1) {
-        const int64_t o = __shfl_xor((long long)v, off, NACHO_WAVE);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-__device__ inline int64_t wave_min64(int64_t v)
-{
-#pragma unroll
-    for (int off = NACHO_WAVE / 2; off > 0; off >>= 1) {
-        const int64_t o = __shfl_xor((long long)v, off, NACHO_WAVE);
-        v = o < v ? o : v;
-    }
-    return v;
-}
-
 // Dense level (level 0 of CSR operands): position == coordinate, cost through
 // the next level's pos array.  64-ary search over [0, N].
 template <int K>
@@ -202,9 +183,12 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 //                return; the result is in W.
 //   otherwise:   R_lo == R_hi; runs until the boundary is found.
 template <bool kLast, int K>
-__device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo, int64_t R_hi,
+__device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
                                       Windows<K> &W, bool narrow_only, int *p)
 {
+    // costs, positions and coordinates all fit 32 bits (the operands hold fewer than
+    // 2^31 entries together; INT32_MAX is no coordinate)
+    const int R_lo = (int)R_lo64, R_hi = (int)R_hi64;
     const int lane = lane_id();
     const int k = ops.k;
     int base[K], l[K], h[K], cl[K], ch[K];
@@ -219,11 +203,11 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
     auto sample_pos = [](int lo, int w, int j) -> int {
         return lo + (w <= NACHO_WAVE ? j : (int)(((int64_t)j * w) >> 6));
     };
-    int64_t prev_total = INT64_MAX;
+    int prev_total = INT32_MAX;
     for (;;) {
         int v[K], ca[K], cb[K], w[K], mt[K];
         bool all_small = true;
-        int64_t total = 0;
+        int total = 0;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             w[t] = h[t] - l[t];
@@ -231,12 +215,12 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
             total += w[t];
             if (w[t] > NACHO_WAVE) all_small = false;
         }
-        if (narrow_only && (all_small || total * 4 > prev_total)) break;   // no longer pays
+        if (narrow_only && (all_small || total > prev_total / 4)) break;   // no longer pays
         if (!all_small && total >= prev_total) {
             int64_t c0 = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K>(ops, m, R_lo, base, l, h, c0, p);
+            return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p);
         }
         prev_total = total;
 #pragma unroll
@@ -279,10 +263,10 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                 }
         }
         // bounds of the cost of every sampled coordinate
-        int64_t best_le = -1, best_gt = INT64_MAX;
+        int best_le = -1, best_gt = INT32_MAX;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
-            int64_t glo = cb[t], ghi = cb[t];       // own operand: the sample's position is exact
+            int glo = cb[t], ghi = cb[t];           // own operand: the sample's position is exact
 #pragma unroll
             for (int u = 0; u < K; ++u) {
                 if (u == t) continue;
@@ -303,20 +287,20 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                 ghi += costB;
             }
             const bool valid = lane < mt[t];
-            const int64_t vv = v[t];
+            const int vv = v[t];
             if (valid && ghi <= R_lo && vv > best_le) best_le = vv;
             if (valid && glo > R_hi && vv < best_gt) best_gt = vv;
         }
-        const int64_t vminus = wave_max64(best_le);     // largest sample not after the first boundary
-        const int64_t vplus = wave_min64(best_gt);      // smallest sample after the last boundary
+        const int vminus = wave_max(best_le);           // largest sample not after the first boundary
+        const int vplus = -wave_max(-best_gt);          // smallest sample after the last boundary
 
 #pragma unroll
         for (int u = 0; u < K; ++u) {
             const bool in = lane < mt[u];
             int nl = l[u], ncl = cl[u], nh = h[u], nch = ch[u];
             if (vminus >= 0) {
-                const int c = __popcll(__ballot(in && (int64_t)v[u] < vminus));
-                const bool eq = __ballot(in && (int64_t)v[u] == vminus) != 0ull;
+                const int c = __popcll(__ballot(in && v[u] < vminus));
+                const bool eq = __ballot(in && v[u] == vminus) != 0ull;
                 const int sc = c < mt[u] ? sample_pos(l[u], w[u], c) : h[u];
                 const int sp = c > 0 ? sample_pos(l[u], w[u], c - 1) + 1 : l[u];
                 nl = eq ? sc : sp;
@@ -327,8 +311,8 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     ncl = eq ? e : (c == 0 ? cl[u] : a);
                 }
             }
-            if (vplus != INT64_MAX) {
-                const int c = __popcll(__ballot(in && (int64_t)v[u] < vplus));
+            if (vplus != INT32_MAX) {
+                const int c = __popcll(__ballot(in && v[u] < vplus));
                 nh = c == mt[u] ? h[u] : sample_pos(l[u], w[u], c);
                 if (kLast) nch = nh - base[u];
                 else {
@@ -346,7 +330,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     l[t] = W.l[t]; h[t] = W.h[t];
                     c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K>(ops, m, R_lo, base, l, h, c0, p);
+                return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p);
             }
             r.x = vminus;
 #pragma unroll
