@@ -128,7 +128,7 @@ const char *nacho_status_string(int32_t status);
 /* Number of partitions a fused call uses for these operands (host descriptors;
  * only counts/extents are read) when the caller asks for `P` (0 = automatic).
  * Fused calls never use fewer partitions than needed for one partition's work
- * to fit a wavefront's staging buffer, so the result is >= P.  `n_dense`:
+ * to fit the staging buffer of its wavefront (SpMV, SpMM) or workgroup (SpAdd), so the result is >= P.  `n_dense`:
  * SpMM's dense extent (0 otherwise).  Returns 0 on bad input. */
 int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                              int64_t n_dense, int64_t P);
@@ -158,6 +158,21 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
 int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, int64_t P,
                         const int64_t *queries, const nacho_parts *out,
                         void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Where a fused call keeps its stored partitions (Section 4.2.3: the positions
+ * found by the search are kept for the assembly and compute stages).  Fills
+ * `parts` (host struct) with the number of partitions the fused call `op` uses
+ * for these operands and with DEVICE pointers into the workspace `ws` the call
+ * was (or will be) given; the table is valid once that call has run.  Nothing
+ * is launched.  `grain` (host, may be NULL) receives G when the call uses the
+ * fixed-grain queries Q_p = min(p*G, Q_total) (SpMV and SpMM with P = 0; G is
+ * in scaled units, a multiple of n_dense for SpMM), 0 when it uses
+ * Q_p = floor(p*Q_total/P).  Arguments as for nacho_workspace_bytes.
+ */
+int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
+                              int64_t n_dense, int64_t P, void *ws, size_t ws_bytes,
+                              nacho_parts *parts /* host */, int64_t *grain /* host */);
 
 /*
  * y = A x with A in CSR (Section 4.2.2 uses this expression for the broadcast

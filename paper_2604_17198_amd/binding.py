@@ -24,7 +24,7 @@ MAX_OPERANDS, MAX_LEVELS = 8, 2
 
 EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
-    "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k",
+    "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_workspace_parts",
     "nacho_profile_enable", "nacho_profile_read",
 ]
 
@@ -80,6 +80,8 @@ def lib():
                                  C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spadd_k.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_workspace_parts.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                            C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         _lib = L
     return _lib
@@ -205,6 +207,27 @@ def nacho_partition(ops, P, queries=None, cost_scale=1):
     _check(lib().nacho_partition(C.cast(arr, C.c_void_p), k, cost_scale, P, _ptr(queries),
                                  C.byref(parts), None, 0, _stream()), "nacho_partition")
     return {"coord": coord, "posn": posn, "cost": cost}
+
+
+def workspace_parts(op, ops, dtype, ws, n_dense=0, P=0):
+    """The partition table a fused call keeps in its workspace `ws` (valid after the call ran):
+    dict(coord[P+1, d], posn[P+1, k, d] int32, cost[P+1] int64) as copies, plus 'P' and 'grain'."""
+    parts = _Parts()
+    grain = C.c_int64(0)
+    arr = _pack(ops)
+    _check(lib().nacho_workspace_parts(op, C.cast(arr, C.c_void_p), len(ops), dtype, n_dense, P, _ptr(ws),
+                                       ws.numel(), C.byref(parts), C.byref(grain)), "nacho_workspace_parts")
+    base = ws.data_ptr()
+    k, d, Pe = parts.k, parts.d, int(parts.P)
+
+    def view(ptr, count, dt, shape):
+        off = ptr - base
+        nbytes = count * (8 if dt == torch.int64 else 4)
+        return ws[off:off + nbytes].view(dt).reshape(shape).clone()
+
+    return {"coord": view(parts.coord, (Pe + 1) * d, torch.int32, (Pe + 1, d)),
+            "posn": view(parts.posn, (Pe + 1) * k * d, torch.int32, (Pe + 1, k, d)),
+            "cost": view(parts.cost, Pe + 1, torch.int64, (Pe + 1,)), "P": Pe, "grain": int(grain.value)}
 
 
 def nacho_spmv(A: Operand, x, y=None, P=0, ws=None):

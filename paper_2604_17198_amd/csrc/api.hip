@@ -241,6 +241,52 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
     }
 }
 
+int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
+                              int64_t n_dense, int64_t P, void *ws, size_t ws_bytes,
+                              nacho_parts *parts, int64_t *grain)
+{
+    if (!parts || !ws || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    int32_t rc = check_operands(ops, k, false, &dev, &total, &fmt);
+    if (rc != NACHO_OK) return rc;
+    PartsWs w;
+    int64_t Pe = 0, g = 0;
+    size_t need = 0;
+    switch (op) {
+    case NACHO_OP_SPMV:
+    case NACHO_OP_SPMM: {
+        if (k != 1 || fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+        if (op == NACHO_OP_SPMM && (n_dense < 1 || n_dense > NACHO_WAVE)) return NACHO_ERR_INVALID_ARG;
+        Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        CarryWs c = carve_carry(ws, Pe, dtype, op == NACHO_OP_SPMM ? NACHO_WAVE : 1);
+        w = c.parts;
+        need = c.bytes;
+        if (P == 0) g = op == NACHO_OP_SPMV ? (int64_t)spmv_capacity(dtype) : (int64_t)spmm_capacity(dtype) * n_dense;
+        break;
+    }
+    case NACHO_OP_SPADD: {
+        Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        SpaddWs c = carve_spadd(ws, Pe, k, dev.d);
+        w = c.parts;
+        need = c.bytes;
+        break;
+    }
+    default: return NACHO_ERR_UNSUPPORTED;
+    }
+    if (ws_bytes < need) return NACHO_ERR_WORKSPACE;
+    parts->k = k;
+    parts->d = dev.d;
+    parts->P = Pe;
+    parts->coord = w.coord;
+    parts->posn = w.posn;
+    parts->cost = w.cost;
+    if (grain) *grain = g;
+    return NACHO_OK;
+}
+
 int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, int64_t P,
                         const int64_t *queries, const nacho_parts *out,
                         void *ws, size_t ws_bytes, void *hip_stream)

@@ -110,3 +110,60 @@ def test_config1_and_scaled_configs():
     work = np.diff(got["cost"])
     ideal = np.diff([(p * int(got["cost"][-1])) // 777 for p in range(778)])
     assert np.all(np.abs(work - ideal) <= 1)
+
+
+def _fused_queries(P, total, grain, scale):
+    if grain > 0:
+        return np.minimum(np.arange(P + 1, dtype=np.int64) * grain, total * scale) // scale
+    return (np.arange(P + 1, dtype=np.int64) * total) // P
+
+
+@pytest.mark.parametrize("op", ["spmv", "spmm", "spadd_vec", "spadd_dcsr"])
+def test_fused_call_partition_table(op):
+    """The table a fused call stores in its workspace is the oracle's Algorithm 1 on the call's queries."""
+    import torch
+    if op in ("spmv", "spmm"):
+        A = workloads.config(2, scale=0.01)["A"] if op == "spmv" else workloads.config(5, scale=0.01)["A"]
+        dt = np.float64 if op == "spmv" else np.float32
+        g = csr_operand({**A, "val": A["val"].astype(dt)})
+        o = [oracle.csr(A["pos"], A["crd"], A["n_rows"], A["n_cols"])]
+        n = 1 if op == "spmv" else 64
+        code = nb.OP_SPMV if op == "spmv" else nb.OP_SPMM
+        dtc = nb.F64 if op == "spmv" else nb.F32
+        for P in (0, 37):
+            ws = torch.empty(nb.workspace_bytes(code, [g], dtc, 0 if op == "spmv" else n, P), dtype=torch.uint8, device="cuda")
+            if op == "spmv":
+                nb.nacho_spmv(g, dev(np.ones(A["n_cols"], dtype=dt)), P=P, ws=ws)
+            else:
+                nb.nacho_spmm(g, dev(np.ones((A["n_cols"], n), dtype=dt)), P=P, ws=ws)
+            torch.cuda.synchronize()
+            t = nb.workspace_parts(code, [g], dtc, ws, 0 if op == "spmv" else n, P)
+            total = int(A["pos"][-1])
+            qs = _fused_queries(t["P"], total, t["grain"], n)
+            print(f"fused table {op} P={P} -> {t['P']} grain={t['grain']}", flush=True)
+            ref = oracle.partition(o, t["P"], queries=qs)
+            got = {k: v.cpu().numpy() for k, v in t.items() if k in ("coord", "posn", "cost")}
+            assert np.array_equal(got["posn"].astype(np.int64), ref["posn"]), (op, P)
+            assert np.array_equal(got["coord"].astype(np.int64), ref["coord"]), (op, P)
+            assert np.array_equal(got["cost"], ref["cost"] * n), (op, P)
+    else:
+        if op == "spadd_vec":
+            cfg = workloads.config(3, scale=0.02)
+            g = [vector_operand(v) for v in cfg["ops"]]
+            o = [oracle.vector(v["i"], v["extent"]) for v in cfg["ops"]]
+            fmt, rows = "vector", 0
+        else:
+            cfg = workloads.config(4, scale=0.02)
+            g = [dcsr_operand(m) for m in cfg["ops"]]
+            o = [oracle.dcsr(m["pos0"], m["crd0"], m["pos1"], m["crd1"], m["n_rows"], m["n_cols"]) for m in cfg["ops"]]
+            fmt, rows = "dcsr", sum(int(m["crd0"].shape[0]) for m in cfg["ops"])
+        total = sum(x.nnz for x in g)
+        for P in (0, 501):
+            ws = torch.empty(nb.workspace_bytes(nb.OP_SPADD, g, nb.F32, 0, P), dtype=torch.uint8, device="cuda")
+            out = nb.SparseOut(fmt, rows, total, torch.float32, "cuda")
+            nb.nacho_spadd_k(g, out, P=P, ws=ws)
+            torch.cuda.synchronize()
+            t = nb.workspace_parts(nb.OP_SPADD, g, nb.F32, ws, 0, P)
+            print(f"fused table {op} P={P} -> {t['P']}", flush=True)
+            _compare({k: v.cpu().numpy() for k, v in t.items() if k in ("coord", "posn", "cost")},
+                     oracle.partition(o, t["P"]), (op, P))
