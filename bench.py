@@ -201,6 +201,20 @@ def bench_others(steps, warmup):
                 "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
         record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
         del ops, out, ws, cfg
+    for kk in (2, 3):
+        cfg = workloads.csr_add_config(kk)
+        ops = [nb.csr(dev(m["pos"]), dev(m["crd"]), m["n_rows"], m["n_cols"], dev(m["val"])) for m in cfg["ops"]]
+        tot = sum(o.nnz for o in ops)
+        out = nb.SparseOut("csr", 0, tot, torch.float32, "cuda", n_rows=cfg["n_rows"])
+        ws = torch.empty(nb.workspace_bytes(nb.OP_SPADD, ops, nb.F32), dtype=torch.uint8, device="cuda")
+        fn = lambda: nb.nacho_spadd_k(ops, out, ws=ws)
+        fn()
+        torch.cuda.synchronize()
+        n_out = int(out.counts.cpu().numpy()[1])
+        nbytes = tot * 8 + n_out * 8 + (kk + 1) * (cfg["n_rows"] + 1) * 4
+        record(f"F1_k{kk}", f"fused {kk}-way CSR add, power-law 100,000 x 100,000, 5M nnz each (shape of the paper's "
+               f"skew experiment), fp32, {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        del ops, out, ws, cfg
     cfg = workloads.config(5)
     A = cfg["A"]
     op = nb.csr(dev(A["pos"]), dev(A["crd"]), A["n_rows"], A["n_cols"], dev(A["val"]))

@@ -24,7 +24,7 @@ import numpy as np
 
 __all__ = [
     "zipf_row_lengths", "csr_powerlaw", "dcsr_powerlaw", "sparse_vector",
-    "spmv_config", "spadd_vec3_config", "spadd_dcsr_config", "spmm_config",
+    "spmv_config", "spadd_vec3_config", "spadd_dcsr_config", "spmm_config", "csr_add_config",
     "config", "CONFIG_NAMES",
 ]
 
@@ -220,6 +220,13 @@ def spmm_config(n, nnz, alpha, cap, n_dense, seed, dtype=np.float32):
     rng = np.random.default_rng(seed + 1000003)
     B = rng.uniform(-1.0, 1.0, size=(n, n_dense)).astype(dtype)
     return {"kind": "spmm", "A": A, "B": B, "n_dense": int(n_dense)}
+
+
+def csr_add_config(k, n=100_000, nnz_each=5_000_000, alpha=1.3, seed=61, dtype=np.float32):
+    """k power-law CSR matrices of one shape for the fused k-way CSR addition: the shape of the paper's skew
+    experiment (synthetic power-law matrices of 100000 x 100000, Evaluation) with independent operands."""
+    ops = [csr_powerlaw(n, n, nnz_each, alpha, max(8, n // 4), 0.0, seed + t, dtype) for t in range(k)]
+    return {"kind": "spadd_csr", "ops": ops, "n_rows": int(n), "n_cols": int(n)}
 
 
 def config(which: int, scale: float = 1.0, seed: int | None = None):

@@ -198,3 +198,22 @@ def test_config4_full_size():
     assert np.array_equal(out.pos1.cpu().numpy()[:rows + 1], ref["pos1"])
     assert np.array_equal(out.crd1.cpu().numpy()[:nnz], ref["crd1"])
     _vals_ok(out.val.cpu().numpy()[:nnz], ref["val"], ref["abs"], np.float32, "config4 full")
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_csr_add_powerlaw_full_size(k):
+    """Fused k-way CSR addition on power-law matrices of the paper's skew-experiment shape
+    (100000 x 100000, 5M non-zeros each), against the oracle's k-finger union."""
+    cfg = workloads.csr_add_config(k)
+    mats = cfg["ops"]
+    print(f"spadd csr powerlaw k={k} nnz={[int(m['pos'][-1]) for m in mats]}", flush=True)
+    gops = [nb.csr(dev(m["pos"]), dev(m["crd"]), m["n_rows"], m["n_cols"], dev(m["val"])) for m in mats]
+    total = sum(int(m["pos"][-1]) for m in mats)
+    out = nb.SparseOut("csr", 0, total, torch.float32, "cuda", n_rows=cfg["n_rows"])
+    nb.nacho_spadd_k(gops, out)
+    rows, nnz, status = _finish(out)
+    ref = oracle.spadd_csr([{"pos": m["pos"], "crd": m["crd"], "val": m["val"]} for m in mats])
+    assert status == 0 and rows == cfg["n_rows"] and nnz == ref["crd"].shape[0]
+    assert np.array_equal(out.pos1.cpu().numpy(), ref["pos"])
+    assert np.array_equal(out.crd1.cpu().numpy()[:nnz], ref["crd"])
+    _vals_ok(out.val.cpu().numpy()[:nnz], ref["val"], ref["abs"], np.float32, f"csr add k={k}")
