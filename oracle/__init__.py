@@ -52,6 +52,8 @@ def lib():
         _lib.ora_total_cost.restype = C.c_int64
         _lib.ora_spadd_vec.restype = C.c_int64
         _lib.ora_spadd_csr.restype = C.c_int64
+        _lib.ora_spmul_vec.restype = C.c_int64
+        _lib.ora_spmul_csr.restype = C.c_int64
     return _lib
 
 
@@ -260,4 +262,43 @@ def spadd_csr(mats):
                              o_v.ctypes.data_as(C.c_void_p), o_a.ctypes.data_as(C.c_void_p))
     if nz < 0:
         raise ValueError("ora_spadd_csr rejected its arguments")
+    return {"pos": o_pos, "crd": o_crd[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}
+
+
+def spmul_vec(idxs, vals):
+    """Intersection multiply of k sparse vectors.  Returns (idx int32, val f64, abs f64)."""
+    k = len(idxs)
+    idxs = [_i32(i) for i in idxs]
+    vals, is64 = _vals(vals)
+    nnz = np.array([i.shape[0] for i in idxs], dtype=np.int64)
+    cap = int(nnz.min()) if k else 0
+    oi = np.empty(cap, dtype=np.int32)
+    ov = np.empty(cap, dtype=np.float64)
+    oa = np.empty(cap, dtype=np.float64)
+    n = lib().ora_spmul_vec(k, _ptr_array(idxs), _ptr_array(vals), nnz.ctypes.data_as(C.c_void_p),
+                            is64, oi.ctypes.data_as(C.c_void_p), ov.ctypes.data_as(C.c_void_p),
+                            oa.ctypes.data_as(C.c_void_p))
+    if n < 0:
+        raise ValueError("ora_spmul_vec rejected its arguments")
+    return oi[:n].copy(), ov[:n].copy(), oa[:n].copy()
+
+
+def spmul_csr(mats):
+    """Hadamard product of k CSR matrices given as dicts(pos, crd, val).
+    Returns dict(pos, crd int32; val, abs float64)."""
+    k = len(mats)
+    pos = [_i32(m["pos"]) for m in mats]
+    crd = [_i32(m["crd"]) for m in mats]
+    vals, is64 = _vals([m["val"] for m in mats])
+    n_rows = pos[0].shape[0] - 1
+    cap = min(c.shape[0] for c in crd)
+    o_pos = np.empty(n_rows + 1, dtype=np.int32)
+    o_crd = np.empty(cap, dtype=np.int32)
+    o_v = np.empty(cap, dtype=np.float64)
+    o_a = np.empty(cap, dtype=np.float64)
+    nz = lib().ora_spmul_csr(k, C.c_int64(n_rows), _ptr_array(pos), _ptr_array(crd), _ptr_array(vals),
+                             is64, o_pos.ctypes.data_as(C.c_void_p), o_crd.ctypes.data_as(C.c_void_p),
+                             o_v.ctypes.data_as(C.c_void_p), o_a.ctypes.data_as(C.c_void_p))
+    if nz < 0:
+        raise ValueError("ora_spmul_csr rejected its arguments")
     return {"pos": o_pos, "crd": o_crd[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}

@@ -25,6 +25,10 @@
  *        is the k-finger coiteration of Section 2.1 with "any operand matches"
  *        in place of "all operands match" (Section 2.2 gives the two-level
  *        loop nest for DCSR).
+ *        intersection multiply: the sorted intersection of the operands'
+ *        stored coordinates, each with the product (in operand order) of the
+ *        k values; the k-finger loop of Section 2.1 as printed ("all operands
+ *        match"), for sparse vectors and for the columns of every CSR row.
  *
  * Precision: products and sums are accumulated wider than the GPU's working
  * type (long double for the fp64 kernels, double for the fp32 kernels) and the
@@ -438,6 +442,70 @@ int64_t ora_spadd_csr(int k, int64_t n_rows, const int32_t *const *pos, const in
     for (int64_t i = 0; i < n_rows; ++i) {
         for (int t = 0; t < k; ++t) { p[t] = pos[t][i]; e[t] = pos[t][i + 1]; }
         union_merge(k, crd, val, is_f64, p, e, out_crd, out_val, out_abs, &nz);
+        out_pos[i + 1] = (int32_t)nz;
+    }
+    return nz;
+}
+
+/*
+ * k-finger intersection of the segments [p[t], e[t]) of k sorted coordinate
+ * lists: the sequential loop of Section 2.1 (z_i = a_i b_i c_i): while every
+ * finger is inside its segment, take the smallest coordinate under the
+ * fingers; if all fingers show it, emit the product; advance every finger that
+ * shows it.  Appends to out_crd/out_val/out_abs at *n_out.
+ */
+static void intersect_merge(int k, const int32_t *const *crd, const void *const *val, int is_f64,
+                            int64_t *p, const int64_t *e,
+                            int32_t *out_crd, double *out_val, double *out_abs, int64_t *n_out)
+{
+    for (;;) {
+        int inside = 1;
+        for (int t = 0; t < k; ++t)
+            if (p[t] >= e[t]) inside = 0;
+        if (!inside) break;
+        int64_t i = crd[0][p[0]];
+        for (int t = 1; t < k; ++t)
+            if ((int64_t)crd[t][p[t]] < i) i = crd[t][p[t]];
+        int all = 1;
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd[t][p[t]] != i) all = 0;
+        if (all) {
+            double prod = 1.0;
+            for (int t = 0; t < k; ++t) prod *= load_value(val[t], is_f64, p[t]);
+            out_crd[*n_out] = (int32_t)i;
+            out_val[*n_out] = prod;
+            if (out_abs) out_abs[*n_out] = fabs(prod);
+            ++*n_out;
+        }
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd[t][p[t]] == i) ++p[t];
+    }
+}
+
+/* z_i = prod_t v_t,i over the coordinates all k sparse vectors store.  Outputs
+ * must hold min_t nnz_t entries; returns the number written. */
+int64_t ora_spmul_vec(int k, const int32_t *const *idx, const void *const *val, const int64_t *nnz,
+                      int is_f64, int32_t *out_idx, double *out_val, double *out_abs)
+{
+    int64_t p[ORA_MAXK], n_out = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) p[t] = 0;
+    intersect_merge(k, idx, val, is_f64, p, nnz, out_idx, out_val, out_abs, &n_out);
+    return n_out;
+}
+
+/* Z_ij = prod_t A_t,ij (Hadamard product) of k CSR matrices of one shape: dense
+ * rows, intersection of the columns per row.  Returns nnz of Z. */
+int64_t ora_spmul_csr(int k, int64_t n_rows, const int32_t *const *pos, const int32_t *const *crd,
+                      const void *const *val, int is_f64,
+                      int32_t *out_pos, int32_t *out_crd, double *out_val, double *out_abs)
+{
+    int64_t p[ORA_MAXK], e[ORA_MAXK], nz = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    out_pos[0] = 0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        for (int t = 0; t < k; ++t) { p[t] = pos[t][i]; e[t] = pos[t][i + 1]; }
+        intersect_merge(k, crd, val, is_f64, p, e, out_crd, out_val, out_abs, &nz);
         out_pos[i + 1] = (int32_t)nz;
     }
     return nz;

@@ -160,3 +160,68 @@ def test_workload_recipe_matches_its_specification():
     a, b, c = (o["i"] for o in c3["ops"])
     assert np.all(np.diff(a) > 0) and np.all(np.diff(b) > 0) and np.all(np.diff(c) > 0)
     assert 0.18 < np.isin(b, a).mean() < 0.25
+
+
+def test_intersection_of_fig1_vectors(golden_dir):
+    """The three-finger listing of Section 2.1 on the vectors of Figure 1: only
+    coordinates 1 and 9 are stored by all of a, b and c."""
+    with open(os.path.join(golden_dir, "fig1_three_vectors.json")) as f:
+        g = json.load(f)
+    idx = [np.array(g[n], np.int32) for n in "abc"]
+    vals = [np.arange(2, len(i) + 2, dtype=np.float64) * (t + 1) for t, i in enumerate(idx)]
+    oi, ov, oa = oracle.spmul_vec(idx, vals)
+    assert oi.tolist() == [1, 9]
+    # 1: a0*b0*c0 ; 9: a2*b3*c2
+    assert ov.tolist() == [2 * 4 * 6, 4 * 10 * 12] and oa.tolist() == ov.tolist()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5])
+def test_spmul_vec_and_csr_vs_dense(k):
+    rng = np.random.default_rng(71 + k)
+    for trial in range(40):
+        shape = (int(rng.integers(1, 12)), int(rng.integers(1, 30)))
+        mats, vec_i, vec_v = [], [], []
+        dense = np.ones(shape)
+        mask = np.ones(shape, bool)
+        for t in range(k):
+            nmax = shape[0] * shape[1]
+            c = random_coords(rng, shape, int(rng.integers(nmax // 2, nmax + 1)))
+            if trial % 7 == 0 and t > 0:
+                c = random_coords(rng, shape, 0)                      # an empty operand: empty result
+            v = rng.uniform(-1, 1, c.shape[0]).astype(np.float64)
+            pos, crd = to_csr(c, shape[0])
+            mats.append({"pos": pos, "crd": crd, "val": v})
+            m = np.zeros(shape, bool)
+            m[tuple(c.T)] = True
+            d = np.zeros(shape)
+            d[tuple(c.T)] = v
+            mask &= m
+            dense *= d
+            # the same data as one long sparse vector (row-major linear index)
+            vec_i.append((c[:, 0] * shape[1] + c[:, 1]).astype(np.int32))
+            vec_v.append(v)
+        out = oracle.spmul_csr(mats)
+        rr, cc = np.nonzero(mask)
+        assert out["pos"].tolist() == [0] + np.cumsum(mask.sum(axis=1)).tolist()
+        assert out["crd"].tolist() == cc.tolist()
+        assert np.allclose(out["val"], dense[rr, cc], rtol=1e-14, atol=0)
+        oi, ov, _ = oracle.spmul_vec(vec_i, vec_v)
+        ref = vec_i[0]
+        for t in range(1, k):
+            ref = np.intersect1d(ref, vec_i[t])
+        assert oi.tolist() == ref.tolist() == (rr * shape[1] + cc).tolist()
+        assert np.allclose(ov, dense[rr, cc], rtol=1e-14, atol=0)
+
+
+def test_spmul_csr_vs_scipy_medium():
+    cfg = workloads.csr_add_config(2, n=3000, nnz_each=200_000)
+    A, B = cfg["ops"]
+    out = oracle.spmul_csr([A, B])
+
+    def to_sp(M):
+        return sp.csr_matrix((M["val"].astype(np.float64), M["crd"], M["pos"]), shape=(cfg["n_rows"], cfg["n_cols"]))
+
+    ref = to_sp(A).multiply(to_sp(B)).tocsr()
+    ref.sort_indices()
+    assert out["pos"].tolist() == ref.indptr.tolist() and out["crd"].tolist() == ref.indices.tolist()
+    assert np.allclose(out["val"], ref.data, rtol=1e-14, atol=0) and out["crd"].shape[0] > 1000
