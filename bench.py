@@ -200,6 +200,13 @@ def bench_others(steps, warmup):
         what = ("C3: 3 sparse vectors (10M + 1M + 100k nnz, index space 2^30), fp32 union add" if c == 3 else
                 "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
         record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        if c == 3:
+            fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
+            fm()
+            torch.cuda.synchronize()
+            n_mul = int(out.counts.cpu().numpy()[1])
+            record("F2_vec3", f"3-way sparse-vector multiply (intersection) on the C3 vectors, {tot} input nnz, "
+                   f"{n_mul} output nnz", fm, tot, tot * 8 + n_mul * 8)
         del ops, out, ws, cfg
     for kk in (2, 3):
         cfg = workloads.csr_add_config(kk)
@@ -214,6 +221,13 @@ def bench_others(steps, warmup):
         nbytes = tot * 8 + n_out * 8 + (kk + 1) * (cfg["n_rows"] + 1) * 4
         record(f"F1_k{kk}", f"fused {kk}-way CSR add, power-law 100,000 x 100,000, 5M nnz each (shape of the paper's "
                f"skew experiment), fp32, {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        if kk == 2:
+            fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
+            fm()
+            torch.cuda.synchronize()
+            n_mul = int(out.counts.cpu().numpy()[1])
+            record("F2_csr2", f"CSR Hadamard product of the same two matrices, {tot} input nnz, {n_mul} output nnz",
+                   fm, tot, tot * 8 + n_mul * 8 + 3 * (cfg["n_rows"] + 1) * 4)
         del ops, out, ws, cfg
     cfg = workloads.config(5)
     A = cfg["A"]

@@ -205,6 +205,21 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Z = prod_t ops[t] over the INTERSECTION of the operands' stored coordinates:
+ * the k-way product of sparse vectors (the three-finger loop of Section 2.1,
+ * z_i = a_i b_i c_i) or the Hadamard product of k CSR matrices.  The
+ * intersection is on the innermost level, so the partitions are those of
+ * Algorithm 1 on the operands' non-zero counts, exactly as for nacho_spadd_k
+ * (Section 3.3: only an outer intersection needs the recursive partitioning);
+ * an entry is emitted when all k operands store its coordinate, its value is
+ * the product in operand order.  Same arguments, output layout, status and
+ * capacity rules as nacho_spadd_k (min_t nnz_t is always a sufficient cap_nnz).
+ * DCSR operands: NACHO_ERR_UNSUPPORTED (outer-level intersection).
+ */
+int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the hot path).  While enabled,
  * every fused call brackets each of its kernels with HIP events on the call's
  * stream.  nacho_profile_read synchronises on those events and returns the

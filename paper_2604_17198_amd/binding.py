@@ -24,7 +24,7 @@ MAX_OPERANDS, MAX_LEVELS = 8, 2
 
 EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
-    "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_workspace_parts",
+    "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
     "nacho_profile_enable", "nacho_profile_read",
 ]
 
@@ -80,6 +80,7 @@ def lib():
                                  C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spadd_k.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_spmul_k.argtypes = L.nacho_spadd_k.argtypes
         L.nacho_workspace_parts.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
@@ -285,6 +286,18 @@ def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):
     arr = _pack(ops)
     _check(lib().nacho_spadd_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
                                ws.numel(), _stream()), "nacho_spadd_k")
+    return out
+
+
+def nacho_spmul_k(ops, out: SparseOut, P=0, ws=None):
+    """Z = product of the operands over the intersection of their coordinates (vectors, CSR)."""
+    dt = dtype_code(ops[0].val.dtype)
+    dev = ops[0].val.device
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPADD, ops, dt, 0, P), dev)
+    arr = _pack(ops)
+    _check(lib().nacho_spmul_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
+                               ws.numel(), _stream()), "nacho_spmul_k")
     return out
 
 

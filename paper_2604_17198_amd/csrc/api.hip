@@ -374,8 +374,9 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
     return NACHO_OK;
 }
 
-int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
-                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
+// nacho_spadd_k and nacho_spmul_k: the same pipeline, sums over the union or products over the intersection
+static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (!out || P < 0) return NACHO_ERR_INVALID_ARG;
     if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
@@ -384,6 +385,9 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     Format fmt;
     int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
     if (rc != NACHO_OK) return rc;
+    // a product of DCSR operands intersects the OUTER level: that takes the recursive
+    // partitioning of Section 3.3, which is not built
+    if (multiply && fmt == FMT_DCSR) return NACHO_ERR_UNSUPPORTED;
     SpaddValues vals;
     std::memset(&vals, 0, sizeof(vals));
     for (int t = 0; t < k; ++t) {
@@ -409,10 +413,22 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
                          w.tile_state, spadd_state_words(Pe), o.status) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
-    if (launch_spadd(f, dtype, dev, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, o, s) != hipSuccess)
+    if (launch_spadd(f, dtype, multiply, dev, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, o, s) != hipSuccess)
         return NACHO_ERR_HIP;
-    profile_mark("spadd_merge");
+    profile_mark(multiply ? "spmul_merge" : "spadd_merge");
     return NACHO_OK;
+}
+
+int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return sparse_combine(false, ops, k, dtype, P, out, ws, ws_bytes, hip_stream);
+}
+
+int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
+                      const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return sparse_combine(true, ops, k, dtype, P, out, ws, ws_bytes, hip_stream);
 }
 
 int32_t nacho_profile_enable(int32_t on)

@@ -51,9 +51,10 @@ struct SpaddOut {
 int spadd_capacity(int fmt);
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
-// Count, prefix sum and fill in one kernel, one wavefront per partition.
-hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
-                        const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
+// Count, prefix sum and fill in one kernel, one workgroup per partition.  `multiply`: the k-way
+// intersection with products instead of the union with sums (vectors and CSR only).
+hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,
+                        int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
                         const SpaddOut &out, hipStream_t s);
 
 }  // namespace nacho

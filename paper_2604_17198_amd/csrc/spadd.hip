@@ -216,7 +216,10 @@ __device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
     }
 }
 
-template <int FMT, typename T, int K>
+// kMul: the k-way intersection with products (an entry is emitted when all k
+// operands store its coordinate, Section 2.1) instead of the union with sums;
+// the partitions, the ranks and the prefix sum are the same.
+template <int FMT, typename T, int K, bool kMul>
 __global__ void __launch_bounds__(kThreads)
 spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
@@ -463,9 +466,15 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         if (i - lane >= n) break;
         const bool valid = i < n;
         const int inf = valid ? (int)info[i] : 0x8000;
-        const bool head = !(inf >> 15);
+        bool head = !(inf >> 15);              // emitted entries: heads; kMul: heads followed by k - 1 duplicates
+        if (kMul) {
+            head = head && i + k - 1 < n;
+#pragma unroll
+            for (int g = 1; g < K; ++g)
+                if (g < k && head) head = (info[i + g < kTile ? i + g : kTile - 1] >> 15) != 0;
+        }
         const unsigned long long hm = __ballot(head);
-        uint32_t word = (uint32_t)(heads + __popcll(hm & below));
+        uint32_t word = (uint32_t)(heads + __popcll(hm & below)) | (head ? 0x8000u : 0u);
         heads += __popcll(hm);
         if (FMT == SPADD_DCSR) {
             const uint32_t rw = row_of(keys[inf & 0xfff]);
@@ -608,7 +617,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             }
             long long at = share_nnz[kWaves];              // past the last entry of the partition
             if (l < n) {
-                at = (long long)(w.word(l) & 0xffffu);
+                at = (long long)(w.word(l) & 0x7fffu);
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww)
                     if (l / kShare == ww) at += share_nnz[ww];
@@ -628,14 +637,21 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         if (c >= n || (slot[r] & 0x8000)) continue;
         const int m = slot[r];
         const uint32_t word = w.word(m);
+        if (!(word & 0x8000u)) continue;   // (kMul: a head that not every operand matches)
         T sum = val[r];                    // then the duplicates, which follow in operand order
-        bool more = true;
+        if (kMul) {
 #pragma unroll
-        for (int g = 1; g < K; ++g) {
-            more = more && m + g < n && (info[m + g < kTile ? m + g : kTile - 1] >> 15);
-            if (more) sum += dv[m + g];
+            for (int g = 1; g < K; ++g)
+                if (g < k) sum *= dv[m + g];
+        } else {
+            bool more = true;
+#pragma unroll
+            for (int g = 1; g < K; ++g) {
+                more = more && m + g < n && (info[m + g < kTile ? m + g : kTile - 1] >> 15);
+                if (more) sum += dv[m + g];
+            }
         }
-        long long wpos = (long long)(word & 0xffffu), wr = (long long)((word >> 16) & 0x7fffu);
+        long long wpos = (long long)(word & 0x7fffu), wr = (long long)((word >> 16) & 0x7fffu);
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww)
             if (m / kShare == ww) { wpos += share_nnz[ww]; wr += share_rows[ww]; }
@@ -654,24 +670,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 
 int64_t chunks_of(int64_t P) { return (P + kChunk - 1) / kChunk; }
 
-template <int FMT, typename T, int K>
+template <int FMT, typename T, int K, bool kMul>
 hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
-                      const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
+                    const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    hipLaunchKernelGGL((spadd_kernel<FMT, T, K>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
+    hipLaunchKernelGGL((spadd_kernel<FMT, T, K, kMul>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
                        P, chunks_of(P), coord, posn, tile_state, out);
     return hipGetLastError();
 }
 
 // instantiated for up to 2, 3, 4 and 8 operands: the per-entry loops over the runs are unrolled
-template <int FMT, typename T>
+template <int FMT, typename T, bool kMul>
 hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                       const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    if (ops.k <= 2) return launch_k<FMT, T, 2>(ops, vals, P, coord, posn, tile_state, out, s);
-    if (ops.k <= 3) return launch_k<FMT, T, 3>(ops, vals, P, coord, posn, tile_state, out, s);
-    if (ops.k <= 4) return launch_k<FMT, T, 4>(ops, vals, P, coord, posn, tile_state, out, s);
-    return launch_k<FMT, T, 8>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 2) return launch_k<FMT, T, 2, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 3) return launch_k<FMT, T, 3, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 4) return launch_k<FMT, T, 4, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
+    return launch_k<FMT, T, 8, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
 }
 
 }  // namespace
@@ -681,20 +697,22 @@ int spadd_capacity(int fmt) { (void)fmt; return kSpaddCap; }
 // 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup
 int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (P + 1) / 2; }
 
-hipError_t launch_spadd(int fmt, int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
-                        const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
+hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,
+                        int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
                         const SpaddOut &out, hipStream_t s)
 {
-#define NACHO_SPADD_CASE(F)                                                                          \
-    if (fmt == F) {                                                                                  \
-        if (dtype == NACHO_F64) return launch_one<F, double>(ops, vals, P, coord, posn, tile_state, out, s); \
-        return launch_one<F, float>(ops, vals, P, coord, posn, tile_state, out, s);                  \
+#define NACHO_SPADD_CASE(F, M)                                                                       \
+    if (fmt == F && multiply == M) {                                                                 \
+        if (dtype == NACHO_F64) return launch_one<F, double, M>(ops, vals, P, coord, posn, tile_state, out, s); \
+        return launch_one<F, float, M>(ops, vals, P, coord, posn, tile_state, out, s);               \
     }
-    NACHO_SPADD_CASE(SPADD_VECTOR)
-    NACHO_SPADD_CASE(SPADD_CSR)
-    NACHO_SPADD_CASE(SPADD_DCSR)
+    NACHO_SPADD_CASE(SPADD_VECTOR, false)
+    NACHO_SPADD_CASE(SPADD_CSR, false)
+    NACHO_SPADD_CASE(SPADD_DCSR, false)
+    NACHO_SPADD_CASE(SPADD_VECTOR, true)
+    NACHO_SPADD_CASE(SPADD_CSR, true)
 #undef NACHO_SPADD_CASE
-    return hipErrorInvalidValue;
+    return hipErrorInvalidValue;    // (DCSR products intersect the outer level: not built)
 }
 
 }  // namespace nacho
