@@ -334,7 +334,7 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
                          w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, grain, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmv_exec");
-    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmv_fixup");
     return NACHO_OK;

@@ -25,7 +25,7 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
                             const int32_t *coord, const int32_t *posn, int64_t P,
                             void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream);
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
-                             const int32_t *carry_row, hipStream_t stream);
+                             const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream);
 
 // ---- SpMM (lane per column of B, n <= 64) -----------------------------------
 int spmm_capacity(int dtype);

@@ -14,6 +14,8 @@
 //      row that started earlier to the fix-up pass as a carry.
 // The fix-up pass adds the carries of a row, in a fixed order, to y[r].  There
 // are no floating-point atomics anywhere: results repeat bit for bit.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -40,17 +42,30 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     // therefore dealt out so that XCD j gets the j-th eighth of the row, in
     // ascending order: its gathers then stay inside one eighth of x (columns
     // are sorted inside a row), which its L2 holds.  With fixed-grain queries
-    // the partitions inside row r are ceil(pos[r] / grain) .. floor(pos[r+1] /
-    // grain) - 1; the deal is a permutation of the largest range of them that
-    // starts and ends on a multiple of 8, everything else keeps its index.
+    // the partitions inside row r are first = ceil(pos[r] / grain) .. end - 1 =
+    // floor(pos[r+1] / grain) - 1.  Among the workgroups first .. end - 1 those
+    // with index = j (mod 8) take, in order, the j-th stretch of these
+    // partitions (stretches as long as there are such workgroups): a
+    // permutation of first .. end - 1; everything else keeps its index.
     int p = blockIdx.x;
     if (grain > 0) {
         const int r = coord[2 * p];
         if (r < n_rows) {
             const int base = pos[0];
-            const int lo = (((pos[r] - base) + grain - 1) / grain + 7) & ~7;
-            const int hi = ((pos[r + 1] - base) / grain) & ~7;
-            if (hi - lo >= 16 && p >= lo && p < hi) p = lo + (p & 7) * ((hi - lo) >> 3) + ((p - lo) >> 3);
+            const int first = ((pos[r] - base) + grain - 1) / grain;
+            const int end = (pos[r + 1] - base) / grain;
+            if (end - first >= 4 && p >= first && p < end) {
+                const int j = p & 7;
+                int before = 0, mine = 0;              // partitions of the stretches before stretch j; first workgroup of j
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int f = first + ((jj - first) & 7);      // first workgroup >= first with index = jj (mod 8)
+                    const int cnt = f < end ? (end - f + 7) >> 3 : 0;
+                    if (jj < j) before += cnt;
+                    if (jj == j) mine = f;
+                }
+                p = first + before + ((p - mine) >> 3);
+            }
         }
     }
     // k = 1, d = 2: coord[b*2 + 0] = row, posn[b*2 + 1] = position in crd/val
@@ -143,7 +158,7 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
 template <typename T>
 __global__ void __launch_bounds__(256)
 spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
-                  const int32_t *__restrict__ carry_row)
+                  const int32_t *__restrict__ carry_row, const int32_t *__restrict__ pos, int grain)
 {
     const int p = (int)((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
     const int lane = lane_id();
@@ -171,11 +186,33 @@ spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
     const int r_last = __shfl(r, NACHO_WAVE - 1, NACHO_WAVE);
     const bool last_owned = __shfl((int)owned, NACHO_WAVE - 1, NACHO_WAVE) != 0;
     T tail = T(0);
-    if (r_last >= 0 && last_owned) {
-        constexpr int kBatch = 4;                      // chunks of 64 partitions loaded together
+    if (r_last >= 0 && last_owned && grain > 0) {
+        // fixed-grain partitions: the carries of row r come from the partitions that
+        // start strictly inside it, floor(pos[r] / grain) + 1 .. ceil(pos[r+1] / grain) - 1,
+        // so the rest of the run is known without looking: independent loads, eight
+        // chunks of 64 in flight, added in a fixed order
+        const int base = pos[0];
+        int last = ((pos[r_last + 1] - base) + grain - 1) / grain - 1;
+        if (last > P - 1) last = P - 1;
+        T acc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] = T(0);
+        for (int q0 = p_first + NACHO_WAVE; q0 <= last; q0 += 8 * NACHO_WAVE) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * NACHO_WAVE + lane;
+                if (q <= last) acc[u] += carry_val[q];
+            }
+        }
+        tail = wave_sum(((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
+    } else if (r_last >= 0 && last_owned) {
+        // chunks of 64 partitions, loaded in batches: two chunks first (most runs end
+        // there), then sixteen at a time (a row of a million non-zeros has thousands of
+        // carries; every batch is one round trip)
         int e = p_first + NACHO_WAVE;
         bool more = true;
-        while (more) {
+        auto walk = [&](auto batch_tag) {
+            constexpr int kBatch = decltype(batch_tag)::value;
             int rr[kBatch];
             T vv[kBatch];
 #pragma unroll
@@ -193,12 +230,14 @@ spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
                 more = cnt == NACHO_WAVE;
             }
             e += kBatch * NACHO_WAVE;
-        }
+        };
+        walk(std::integral_constant<int, 2>());
+        while (more) walk(std::integral_constant<int, 16>());
     }
     if (r >= 0 && owned && lane == end) y[r] += v + (end == NACHO_WAVE - 1 ? tail : T(0));
 }
 
-constexpr int kGrainF64 = 1024, kRowsF64 = 1024;
+constexpr int kGrainF64 = 512, kRowsF64 = 512;
 constexpr int kGrainF32 = 2048, kRowsF32 = 1024;
 
 }  // namespace
@@ -224,15 +263,15 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
 }
 
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
-                             const int32_t *carry_row, hipStream_t stream)
+                             const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream)
 {
     const unsigned grid = (unsigned)((P + 255) / 256);
     if (dtype == NACHO_F64)
         hipLaunchKernelGGL((spmv_fixup_kernel<double>), dim3(grid), dim3(256), 0, stream,
-                           (double *)y, (int)P, (const double *)carry_val, carry_row);
+                           (double *)y, (int)P, (const double *)carry_val, carry_row, pos, (int)grain);
     else
         hipLaunchKernelGGL((spmv_fixup_kernel<float>), dim3(grid), dim3(256), 0, stream,
-                           (float *)y, (int)P, (const float *)carry_val, carry_row);
+                           (float *)y, (int)P, (const float *)carry_val, carry_row, pos, (int)grain);
     return hipGetLastError();
 }
 
