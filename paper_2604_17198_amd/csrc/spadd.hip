@@ -123,20 +123,23 @@ __device__ inline int pad(int x) { return x + (x >> kPadShift); }
 //   bits 16..19  number of equal keys met in operands with a smaller index (> 0: duplicate)
 //   bits 20..31  sum of the positions this entry found in larger runs (< kTile)
 constexpr int kDupShift = 16, kDirectShift = 20;
-// Word of a merged slot in `marks` after the assembly (counts inside the slot's wavefront share):
-//   bits 0..15 heads before the slot, 16..30 row heads before it, 31 the slot starts a row
-// kPacked (vectors): the descriptors and the assembly words (16 bits are enough
-// without row counts) share the memory of the ranking words, which are dead by
-// then; the workgroup then needs little enough LDS for four of them per CU.
-template <typename KeyT, typename T, bool kPacked>
+// Word of a merged slot (in the memory of the ranking words, which are dead by then):
+//   bits  0..11  position of the slot's entry in keys      } written when the ranks are known
+//   bit   12     the entry is a duplicate                  }
+//   bits 13..21  emitted entries before the slot           } added by the assembly
+//   bits 22..30  row heads before the slot (DCSR)          } (counts inside the slot's wavefront share)
+//   bit   31     the slot's entry is emitted
+constexpr uint32_t kSlotPos = 0xfffu, kSlotDup = 1u << 12, kSlotEmit = 1u << 31;
+constexpr int kSlotHeads = 13, kSlotRows = 22;
+static_assert(kTile / kWaves <= 512, "the counts inside a share take 9 bits");
+template <typename KeyT, typename T>
 struct Tile {
     union {
         KeyT keys[kTile];                 // the k runs, one after the other
         T dupval[sizeof(T) <= sizeof(KeyT) ? kTile : 1];   // later: values of duplicates by merged slot
     };
     T dupval_wide[sizeof(T) <= sizeof(KeyT) ? 1 : kTile];
-    uint32_t marks[kPadded];              // staging: row markers; ranking words (padded); assembly words
-    uint16_t info_own[kPacked ? 1 : kTile];   // merged order: position in keys (0..11) | duplicate (15)
+    uint32_t marks[kPadded];              // staging: row markers; ranking words (padded); slot words
     unsigned long long scrd[NACHO_MAX_OPERANDS];   // address of crd of run t, biased so that [c] is entry c of keys
     unsigned long long sval[NACHO_MAX_OPERANDS];   // the same for the values
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
@@ -145,16 +148,6 @@ struct Tile {
     unsigned long long wave_cnt[kWaves];           // per-wavefront counts of the assembly (rows << 31 | nnz)
     unsigned long long base;                       // the partition's offset (rows << 31 | nnz)
     __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
-    __device__ uint16_t *info() { return kPacked ? reinterpret_cast<uint16_t *>(marks) : info_own; }
-    __device__ void set_word(int slot, uint32_t word)
-    {
-        if (kPacked) reinterpret_cast<uint16_t *>(marks)[kTile + slot] = (uint16_t)word;
-        else marks[slot] = word;
-    }
-    __device__ uint32_t word(int slot) const
-    {
-        return kPacked ? (uint32_t)reinterpret_cast<const uint16_t *>(marks)[kTile + slot] : marks[slot];
-    }
 };
 
 // Does boundary b fall strictly inside a row, i.e. does some operand hold an
@@ -229,8 +222,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
     constexpr int R = kPerThread;
     constexpr int kShare = kTile / kWaves;     // merged slots a wavefront walks in the assembly
-    __shared__ Tile<KeyT, T, FMT == SPADD_VECTOR> w;
-    uint16_t *info = w.info();
+    __shared__ Tile<KeyT, T> w;
+    uint32_t *slotw = w.marks;              // slot words (once the ranking words are dead)
 
     const int tid = threadIdx.x;
     const int lane = lane_id();
@@ -450,7 +443,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int c = r * kThreads + tid;
-        if (c < n) info[slot[r] & 0x7fff] = (uint16_t)(c | (slot[r] & 0x8000));
+        if (c < n) slotw[slot[r] & 0x7fff] = (uint32_t)c | ((slot[r] & 0x8000) ? kSlotDup : 0u);
     }
     __syncthreads();
 
@@ -465,27 +458,29 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const int i = wave * kShare + b * NACHO_WAVE + lane;
         if (i - lane >= n) break;
         const bool valid = i < n;
-        const int inf = valid ? (int)info[i] : 0x8000;
-        bool head = !(inf >> 15);              // emitted entries: heads; kMul: heads followed by k - 1 duplicates
+        const uint32_t inf = valid ? slotw[i] : kSlotDup;
+        bool head = !(inf & kSlotDup);         // emitted entries: heads; kMul: heads followed by k - 1 duplicates
         if (kMul) {
             head = head && i + k - 1 < n;
 #pragma unroll
             for (int g = 1; g < K; ++g)
-                if (g < k && head) head = (info[i + g < kTile ? i + g : kTile - 1] >> 15) != 0;
+                if (g < k && head) head = (slotw[i + g < kTile ? i + g : kTile - 1] & kSlotDup) != 0;
         }
         const unsigned long long hm = __ballot(head);
-        uint32_t word = (uint32_t)(heads + __popcll(hm & below)) | (head ? 0x8000u : 0u);
+        uint32_t word = inf | ((uint32_t)(heads + __popcll(hm & below)) << kSlotHeads) | (head ? kSlotEmit : 0u);
         heads += __popcll(hm);
+        bool rhead = false;
         if (FMT == SPADD_DCSR) {
-            const uint32_t rw = row_of(keys[inf & 0xfff]);
-            const uint32_t prow = (valid && i > 0) ? row_of(keys[info[i - 1] & 0xfff]) : 0u;
-            const bool rhead = head && (i == 0 ? !cont : rw != prow);
+            const uint32_t rw = row_of(keys[inf & kSlotPos]);
+            const uint32_t prow = (valid && i > 0) ? row_of(keys[slotw[i - 1] & kSlotPos]) : 0u;
+            rhead = head && (i == 0 ? !cont : rw != prow);
             const unsigned long long rm = __ballot(rhead);
-            word |= (uint32_t)(rheads + __popcll(rm & below)) << 16;
-            word |= rhead ? 0x80000000u : 0u;
+            word |= (uint32_t)(rheads + __popcll(rm & below)) << kSlotRows;
             rheads += __popcll(rm);
         }
-        if (valid) w.set_word(i, word);
+        // (a DCSR union emits every head: the top bit says instead that the head starts a row)
+        if (FMT == SPADD_DCSR) word = (word & ~kSlotEmit) | (rhead ? kSlotEmit : 0u);
+        if (valid) slotw[i] = word;
     }
     if (lane == 0) w.wave_cnt[wave] = pack_counts(rheads, heads);
 
@@ -613,11 +608,11 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             int l = 0, h = n;
             while (l < h) {
                 const int m = (l + h) >> 1;
-                if (row_of(keys[info[m] & 0xfff]) < (uint32_t)rr) l = m + 1; else h = m;
+                if (row_of(keys[slotw[m] & kSlotPos]) < (uint32_t)rr) l = m + 1; else h = m;
             }
             long long at = share_nnz[kWaves];              // past the last entry of the partition
             if (l < n) {
-                at = (long long)(w.word(l) & 0x7fffu);
+                at = (long long)((slotw[l] >> kSlotHeads) & 0x1ffu);
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww)
                     if (l / kShare == ww) at += share_nnz[ww];
@@ -636,8 +631,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const int c = r * kThreads + tid;
         if (c >= n || (slot[r] & 0x8000)) continue;
         const int m = slot[r];
-        const uint32_t word = w.word(m);
-        if (!(word & 0x8000u)) continue;   // (kMul: a head that not every operand matches)
+        const uint32_t word = slotw[m];
+        if (FMT != SPADD_DCSR && !(word & kSlotEmit)) continue;   // (kMul: a head that not every operand matches)
         T sum = val[r];                    // then the duplicates, which follow in operand order
         if (kMul) {
 #pragma unroll
@@ -647,11 +642,11 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             bool more = true;
 #pragma unroll
             for (int g = 1; g < K; ++g) {
-                more = more && m + g < n && (info[m + g < kTile ? m + g : kTile - 1] >> 15);
+                more = more && m + g < n && (slotw[m + g < kTile ? m + g : kTile - 1] & kSlotDup);
                 if (more) sum += dv[m + g];
             }
         }
-        long long wpos = (long long)(word & 0x7fffu), wr = (long long)((word >> 16) & 0x7fffu);
+        long long wpos = (long long)((word >> kSlotHeads) & 0x1ffu), wr = (long long)((word >> kSlotRows) & 0x1ffu);
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww)
             if (m / kShare == ww) { wpos += share_nnz[ww]; wr += share_rows[ww]; }
@@ -659,7 +654,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             out.crd1[wpos] = col[r];
             static_cast<T *>(out.val)[wpos] = sum;
         }
-        if (FMT == SPADD_DCSR && (word >> 31)) {
+        if (FMT == SPADD_DCSR && (word & kSlotEmit)) {
             if (wr < out.cap_rows) {
                 out.crd0[wr] = (int32_t)row[r];
                 out.pos1[wr] = (int32_t)wpos;
