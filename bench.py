@@ -118,9 +118,9 @@ def bench_spmv(args):
     exec_ms = kms["spmv_exec"]
     achieved = exec_bytes / exec_ms / 1e6
 
-    # balance from the partition table the library builds for the same P
-    parts = nb.nacho_partition([op], P)
+    # balance from the partition table the fused call stored in its workspace
     torch.cuda.synchronize()
+    parts = nb.workspace_parts(nb.OP_SPMV, [op], nb.F64, ws)
     work = np.diff(parts["cost"].cpu().numpy())
     balance = {"partitions": int(P), "max_over_mean_nnz": float(work.max() / work.mean()),
                "max": int(work.max()), "mean": float(work.mean())}
@@ -173,12 +173,19 @@ def bench_others(steps, warmup):
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
     res = {}
 
-    def record(tag, what, fn, nnz, nbytes):
+    def record(tag, what, fn, nnz, nbytes, table=None):
         ms, _ = _time_steps(fn, steps, warmup)
         res[tag] = {"workload": what, "ms_per_step": ms, "nnz_per_s": nnz / (ms * 1e-3),
                     "GBps_algorithmic": nbytes / ms / 1e6,
                     "frac_of_hbm_peak": nbytes / ms / 1e6 / PEAK_HBM_GBS,
                     "kernel_ms": _kernel_ms(fn, 5)}
+        if table is not None:
+            # work per partition from the table the fused call stored in its workspace (a partition is
+            # executed by one wavefront (SpMM) or dealt out evenly over the 8 wavefronts of a workgroup (SpAdd))
+            torch.cuda.synchronize()
+            work = np.diff(table()["cost"].cpu().numpy())
+            res[tag]["balance"] = {"partitions": int(work.shape[0]), "max": int(work.max()),
+                                   "mean": float(work.mean()), "max_over_mean": float(work.max() / work.mean())}
 
     for c, fmt in ((3, "vector"), (4, "dcsr")):
         cfg = workloads.config(c)
@@ -199,7 +206,8 @@ def bench_others(steps, warmup):
         nbytes = tot * 8 + n_out * 8 + (rows * 8 + n_rows_out * 8 if fmt == "dcsr" else 0)
         what = ("C3: 3 sparse vectors (10M + 1M + 100k nnz, index space 2^30), fp32 union add" if c == 3 else
                 "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
-        record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes,
+               table=lambda: nb.workspace_parts(nb.OP_SPADD, ops, nb.F32, ws))
         if c == 3:
             fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
             fm()
@@ -238,7 +246,8 @@ def bench_others(steps, warmup):
     nnz = int(A["pos"][-1])
     nbytes = nnz * 8 + (A["n_rows"] + 1) * 4 + A["n_cols"] * 64 * 4 + A["n_rows"] * 64 * 4
     record("C5", f"C5: CSR (1,000,000 x 1,000,000, {nnz} nnz) x dense 1,000,000 x 64, fp32 SpMM",
-           lambda: nb.nacho_spmm(op, B, C, ws=ws), nnz, nbytes)
+           lambda: nb.nacho_spmm(op, B, C, ws=ws), nnz, nbytes,
+           table=lambda: nb.workspace_parts(nb.OP_SPMM, [op], nb.F32, ws, 64))
     return res
 
 
