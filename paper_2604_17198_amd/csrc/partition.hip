@@ -262,8 +262,12 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     hi[t][u] = (go && !right) ? mid : hi[t][u];
                 }
         }
-        // bounds of the cost of every sampled coordinate
-        int best_le = -1, best_gt = INT32_MAX;
+        // Bounds of the cost of every sampled coordinate.  Inside one operand the
+        // samples ascend with the lane and so do both bounds, so the samples whose
+        // upper bound is within the query are a prefix of the lanes and those whose
+        // lower bound exceeds it a suffix: one ballot each finds the largest / smallest
+        // such sample, no reduction over the wavefront.
+        int vminus = -1, vplus = INT32_MAX;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             int glo = cb[t], ghi = cb[t];           // own operand: the sample's position is exact
@@ -287,12 +291,17 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                 ghi += costB;
             }
             const bool valid = lane < mt[t];
-            const int vv = v[t];
-            if (valid && ghi <= R_lo && vv > best_le) best_le = vv;
-            if (valid && glo > R_hi && vv < best_gt) best_gt = vv;
+            const int n_le = __popcll(__ballot(valid && ghi <= R_lo));   // lanes 0 .. n_le - 1
+            const int n_in = __popcll(__ballot(valid && glo <= R_hi));   // lanes n_in .. mt - 1 are after
+            if (n_le > 0) {
+                const int cand = __shfl(v[t], n_le - 1, NACHO_WAVE);
+                vminus = cand > vminus ? cand : vminus;  // largest sample not after the first boundary
+            }
+            if (n_in < mt[t]) {
+                const int cand = __shfl(v[t], n_in, NACHO_WAVE);
+                vplus = cand < vplus ? cand : vplus;     // smallest sample after the last boundary
+            }
         }
-        const int vminus = wave_max(best_le);           // largest sample not after the first boundary
-        const int vplus = -wave_max(-best_gt);          // smallest sample after the last boundary
 
 #pragma unroll
         for (int u = 0; u < K; ++u) {
