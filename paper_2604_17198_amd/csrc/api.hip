@@ -368,7 +368,7 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
                          w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmm_exec");
-    if (launch_spmm_fixup(dtype, C, ldc, (int)n, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+    if (launch_spmm_fixup(dtype, C, ldc, (int)n, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain / n, s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmm_fixup");
     return NACHO_OK;

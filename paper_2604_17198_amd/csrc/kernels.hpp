@@ -33,8 +33,9 @@ hipError_t launch_spmm_exec(int dtype, const int32_t *pos, const int32_t *crd, c
                             const void *B, int n, int64_t ldb, void *C, int64_t ldc,
                             const int32_t *coord, const int32_t *posn, int64_t P, void *carry_val,
                             int32_t *carry_row, hipStream_t stream);
+// `grain` > 0: fixed-grain partitions of `grain` non-zeros (run lengths then come from `pos`).
 hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, const void *carry_val,
-                             const int32_t *carry_row, hipStream_t stream);
+                             const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream);
 
 // ---- k-way union addition ---------------------------------------------------
 enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2 };

@@ -4,7 +4,7 @@
 // every stored non-zero by n, so the partitions are those of SpMV).
 //
 // The wavefront stages its partition's crd/val and the pos entries of its rows
-// in LDS, then streams over the non-zeros eight at a time: eight rows of B are
+// in LDS, then streams over the non-zeros sixteen at a time: sixteen rows of B are
 // requested (one 4n-byte coalesced load each) before the first is consumed.  A
 // row of C is stored by the partition in which the row starts; the partial row
 // of a partition that starts inside a row goes to the carry buffer and is added
@@ -16,7 +16,7 @@ namespace nacho {
 
 namespace {
 
-constexpr int kUnroll = 8;
+constexpr int kUnroll = 16;
 
 template <typename T, int G, int RBLK>
 __global__ void __launch_bounds__(NACHO_WAVE)
@@ -103,7 +103,7 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
 template <typename T>
 __global__ void __launch_bounds__(256)
 spmm_fixup_kernel(T *__restrict__ C, int64_t ldc, int n, int P, const T *__restrict__ carry_val,
-                  const int32_t *__restrict__ carry_row)
+                  const int32_t *__restrict__ carry_row, const int32_t *__restrict__ pos, int grain)
 {
     const int p = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE);
     if (p >= P) return;
@@ -112,7 +112,12 @@ spmm_fixup_kernel(T *__restrict__ C, int64_t ldc, int n, int P, const T *__restr
     if (r < 0) return;
     if (p > 0 && carry_row[p - 1] == r) return;
     int e = p + 1;
-    for (;;) {
+    if (grain > 0) {
+        // fixed-grain partitions: the carries of row r come from the partitions that start
+        // strictly inside it, the last one being ceil(pos[r+1] / grain) - 1
+        e = ((pos[r + 1] - pos[0]) + grain - 1) / grain;
+        if (e > P) e = P;
+    } else for (;;) {
         const int q = e + lane;
         const bool same = q < P && carry_row[q] == r;
         const unsigned long long m = __ballot(same);
@@ -121,18 +126,24 @@ spmm_fixup_kernel(T *__restrict__ C, int64_t ldc, int n, int P, const T *__restr
         break;
     }
     if (lane >= n) return;
-    // eight independent partial sums keep eight carry rows in flight; the order
-    // of the additions is fixed, so the result repeats bit for bit
-    T s[8];
+    // 32 independent partial sums keep 32 carry rows in flight (a row of hundreds of
+    // thousands of non-zeros has hundreds of carries); the order of the additions is
+    // fixed, so the result repeats bit for bit
+    constexpr int kAcc = 32;
+    T s[kAcc];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s[u] = T(0);
+    for (int u = 0; u < kAcc; ++u) s[u] = T(0);
     int q = p;
-    for (; q + 8 <= e; q += 8) {
+    for (; q + kAcc <= e; q += kAcc) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s[u] += carry_val[(int64_t)(q + u) * NACHO_WAVE + lane];
+        for (int u = 0; u < kAcc; ++u) s[u] += carry_val[(int64_t)(q + u) * NACHO_WAVE + lane];
     }
-    for (; q < e; ++q) s[0] += carry_val[(int64_t)q * NACHO_WAVE + lane];
-    C[(int64_t)r * ldc + lane] += ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+    for (; q < e; ++q) s[(q - p) & (kAcc - 1)] += carry_val[(int64_t)q * NACHO_WAVE + lane];
+#pragma unroll
+    for (int w = kAcc / 2; w > 0; w >>= 1)
+#pragma unroll
+        for (int u = 0; u < w; ++u) s[u] += s[u + w];
+    C[(int64_t)r * ldc + lane] += s[0];
 }
 
 constexpr int kGrain = 512, kRows = 512;
@@ -158,15 +169,15 @@ hipError_t launch_spmm_exec(int dtype, const int32_t *pos, const int32_t *crd, c
 }
 
 hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, const void *carry_val,
-                             const int32_t *carry_row, hipStream_t stream)
+                             const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream)
 {
     const unsigned grid = (unsigned)((P * NACHO_WAVE + 255) / 256);
     if (dtype == NACHO_F64)
         hipLaunchKernelGGL((spmm_fixup_kernel<double>), dim3(grid), dim3(256), 0, stream, (double *)C, ldc,
-                           n, (int)P, (const double *)carry_val, carry_row);
+                           n, (int)P, (const double *)carry_val, carry_row, pos, (int)grain);
     else
         hipLaunchKernelGGL((spmm_fixup_kernel<float>), dim3(grid), dim3(256), 0, stream, (float *)C, ldc,
-                           n, (int)P, (const float *)carry_val, carry_row);
+                           n, (int)P, (const float *)carry_val, carry_row, pos, (int)grain);
     return hipGetLastError();
 }
 
