@@ -238,7 +238,7 @@ spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
 }
 
 constexpr int kGrainF64 = 512, kRowsF64 = 512;
-constexpr int kGrainF32 = 2048, kRowsF32 = 1024;
+constexpr int kGrainF32 = 1024, kRowsF32 = 1024;
 
 }  // namespace
 
