@@ -302,3 +302,75 @@ def spmul_csr(mats):
     if nz < 0:
         raise ValueError("ora_spmul_csr rejected its arguments")
     return {"pos": o_pos, "crd": o_crd[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}
+
+
+def spmul_dcsr(mats):
+    """Hadamard product of k DCSR matrices given as dicts(pos0, crd0, pos1, crd1, val).
+    Returns dict(pos0, crd0, pos1, crd1 int32; val, abs float64)."""
+    k = len(mats)
+    p0 = [_i32(m["pos0"]) for m in mats]
+    c0 = [_i32(m["crd0"]) for m in mats]
+    p1 = [_i32(m["pos1"]) for m in mats]
+    c1 = [_i32(m["crd1"]) for m in mats]
+    vals, is64 = _vals([m["val"] for m in mats])
+    cap_r = min(c.shape[0] for c in c0)
+    cap_n = min(c.shape[0] for c in c1)
+    o_p0 = np.zeros(2, dtype=np.int32)
+    o_c0 = np.empty(cap_r, dtype=np.int32)
+    o_p1 = np.empty(cap_r + 1, dtype=np.int32)
+    o_c1 = np.empty(cap_n, dtype=np.int32)
+    o_v = np.empty(cap_n, dtype=np.float64)
+    o_a = np.empty(cap_n, dtype=np.float64)
+    counts = np.zeros(2, dtype=np.int64)
+    rc = lib().ora_spmul_dcsr(k, _ptr_array(p0), _ptr_array(c0), _ptr_array(p1), _ptr_array(c1),
+                              _ptr_array(vals), is64,
+                              o_p0.ctypes.data_as(C.c_void_p), o_c0.ctypes.data_as(C.c_void_p),
+                              o_p1.ctypes.data_as(C.c_void_p), o_c1.ctypes.data_as(C.c_void_p),
+                              o_v.ctypes.data_as(C.c_void_p), o_a.ctypes.data_as(C.c_void_p),
+                              counts.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("ora_spmul_dcsr rejected its arguments")
+    nr, nz = int(counts[0]), int(counts[1])
+    return {"pos0": o_p0, "crd0": o_c0[:nr].copy(), "pos1": o_p1[:nr + 1].copy(),
+            "crd1": o_c1[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}
+
+
+def recursive_partition_dcsr(mats, n_cols, P, queries=None):
+    """Algorithm 2 for the Hadamard product of k DCSR matrices (dicts as above; val unused).
+    Returns dict(rows[M], rpos[k, M], T[M], Tprime[M+1], coord[P+1, 2] = (i', j),
+    lpos[P+1, k], before[P+1, k], cost[P+1])."""
+    k = len(mats)
+    p0 = [_i32(m["pos0"]) for m in mats]
+    c0 = [_i32(m["crd0"]) for m in mats]
+    p1 = [_i32(m["pos1"]) for m in mats]
+    c1 = [_i32(m["crd1"]) for m in mats]
+    cap = max(1, min(c.shape[0] for c in c0))
+    rows = np.zeros(cap, dtype=np.int64)
+    rpos = np.zeros((k, cap), dtype=np.int64)
+    T = np.zeros(cap, dtype=np.int64)
+    lib().ora_remap_rows.restype = C.c_int64
+    M = int(lib().ora_remap_rows(k, _ptr_array(p0), _ptr_array(c0), _ptr_array(p1), C.c_int64(cap),
+                                 rows.ctypes.data_as(C.c_void_p), rpos.ctypes.data_as(C.c_void_p),
+                                 T.ctypes.data_as(C.c_void_p)))
+    if M < 0:
+        raise ValueError("ora_remap_rows rejected its arguments")
+    Tprime = np.zeros(M + 1, dtype=np.int64)
+    coord = np.zeros((P + 1, 2), dtype=np.int64)
+    lpos = np.zeros((P + 1, k), dtype=np.int64)
+    before = np.zeros((P + 1, k), dtype=np.int64)
+    cost = np.zeros(P + 1, dtype=np.int64)
+    qp = None
+    if queries is not None:
+        queries = np.ascontiguousarray(queries, dtype=np.int64)
+        assert queries.shape[0] == P + 1
+        qp = queries.ctypes.data_as(C.c_void_p)
+    rc = lib().ora_recursive_partition_dcsr(k, _ptr_array(p1), _ptr_array(c1), C.c_int64(n_cols),
+                                            C.c_int64(M), C.c_int64(cap),
+                                            rpos.ctypes.data_as(C.c_void_p), T.ctypes.data_as(C.c_void_p),
+                                            C.c_int64(P), qp, Tprime.ctypes.data_as(C.c_void_p),
+                                            coord.ctypes.data_as(C.c_void_p), lpos.ctypes.data_as(C.c_void_p),
+                                            before.ctypes.data_as(C.c_void_p), cost.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("ora_recursive_partition_dcsr rejected its arguments")
+    return {"rows": rows[:M].copy(), "rpos": rpos[:, :M].copy(), "T": T[:M].copy(), "Tprime": Tprime,
+            "coord": coord, "lpos": lpos, "before": before, "cost": cost}

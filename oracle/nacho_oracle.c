@@ -510,3 +510,195 @@ int64_t ora_spmul_csr(int k, int64_t n_rows, const int32_t *const *pos, const in
     }
     return nz;
 }
+
+/* ---- nested intersections: Section 3.3 ---------------------------------- */
+
+/*
+ * Z_ij = prod_t A_t,ij for k DCSR matrices: the loop nest of Section 3.3
+ * (rows coiterated as an INTERSECTION, then the columns of the row as an
+ * intersection), serially.  As in the union, a row is stored only when it
+ * holds at least one entry.  out_crd0/out_pos1 must hold min_t rows_t (+1)
+ * entries, out_crd1/out_val min_t nnz_t.  counts = {stored rows, nnz}.
+ */
+int ora_spmul_dcsr(int k, const int32_t *const *pos0, const int32_t *const *crd0,
+                   const int32_t *const *pos1, const int32_t *const *crd1,
+                   const void *const *val, int is_f64,
+                   int32_t *out_pos0, int32_t *out_crd0, int32_t *out_pos1, int32_t *out_crd1,
+                   double *out_val, double *out_abs, int64_t *counts)
+{
+    int64_t r[ORA_MAXK], re[ORA_MAXK], p[ORA_MAXK], e[ORA_MAXK];
+    int64_t nr = 0, nz = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) { r[t] = pos0[t][0]; re[t] = pos0[t][1]; }
+    out_pos1[0] = 0;
+    for (;;) {
+        int inside = 1;
+        for (int t = 0; t < k; ++t)
+            if (r[t] >= re[t]) inside = 0;
+        if (!inside) break;
+        int64_t i = crd0[0][r[0]];
+        for (int t = 1; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] < i) i = crd0[t][r[t]];
+        int all = 1;
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] != i) all = 0;
+        if (all) {
+            for (int t = 0; t < k; ++t) { p[t] = pos1[t][r[t]]; e[t] = pos1[t][r[t] + 1]; }
+            int64_t before = nz;
+            intersect_merge(k, crd1, val, is_f64, p, e, out_crd1, out_val, out_abs, &nz);
+            if (nz > before) {
+                out_crd0[nr] = (int32_t)i;
+                out_pos1[nr + 1] = (int32_t)nz;
+                ++nr;
+            }
+        }
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] == i) ++r[t];
+    }
+    out_pos0[0] = 0;
+    out_pos0[1] = (int32_t)nr;
+    counts[0] = nr;
+    counts[1] = nz;
+    return 0;
+}
+
+/*
+ * First loop of the rewritten nest of Section 3.3 ("Efficiently computing
+ * remapped cost functions"): coiterate the rows all k operands store and, for
+ * every such row i (the i'-th one), memoise
+ *     T[i'] = C_j(N_j | i) = sum_t (number of entries operand t stores in row i).
+ * Also returns the row coordinate rows[i'] and, per operand, the position
+ * rpos[t * cap + i'] of the row in the operand's level 0.  Arrays hold cap >=
+ * min_t rows_t entries.  Returns the number M of intersected rows.
+ */
+int64_t ora_remap_rows(int k, const int32_t *const *pos0, const int32_t *const *crd0,
+                       const int32_t *const *pos1, int64_t cap,
+                       int64_t *rows, int64_t *rpos, int64_t *T)
+{
+    int64_t r[ORA_MAXK], re[ORA_MAXK], M = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) { r[t] = pos0[t][0]; re[t] = pos0[t][1]; }
+    for (;;) {
+        int inside = 1;
+        for (int t = 0; t < k; ++t)
+            if (r[t] >= re[t]) inside = 0;
+        if (!inside) break;
+        int64_t i = crd0[0][r[0]];
+        for (int t = 1; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] < i) i = crd0[t][r[t]];
+        int all = 1;
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] != i) all = 0;
+        if (all) {
+            if (M >= cap) return -1;
+            int64_t c = 0;
+            for (int t = 0; t < k; ++t) {
+                c += pos1[t][r[t] + 1] - pos1[t][r[t]];
+                rpos[(size_t)t * cap + M] = r[t];
+            }
+            rows[M] = i;
+            T[M] = c;
+            ++M;
+        }
+        for (int t = 0; t < k; ++t)
+            if ((int64_t)crd0[t][r[t]] == i) ++r[t];
+    }
+    return M;
+}
+
+/*
+ * FindRecursivePartition (Algorithm 2) for the Hadamard product of k DCSR
+ * matrices.  The outermost sparse intersection (the row loop) is not the
+ * innermost loop, so its cost function is remapped: the row loop becomes a
+ * loop over i' in [0, M), the intersected rows, with
+ *     C'_i(x) = T'[x],   T' = exclusive prefix sum of T          (Section 3.3)
+ * and the remapped nest (i' dense, then the column intersection, which is
+ * innermost and needs no remapping) is handed to FindPartition (Algorithm 1)
+ * with the cost of Section 4.2.2.
+ *
+ * Inputs: the operands, M, rpos and T from ora_remap_rows (cap = stride of
+ * rpos), n_cols, P, optional queries (P + 1, as in ora_partition).
+ * Outputs per boundary b (boundary 0 = origin, boundary P = end of the
+ * remapped space, by the same definition as ora_partition):
+ *   coord[b*2 + {0,1}]            (i', j)
+ *   lpos[(b*k + t)]               position in operand t's crd1/val of its first
+ *                                 entry of row i' that is not before j
+ *                                 (for i' == M: one past its last entry of row M-1,
+ *                                 or its pos1[0] when M == 0)
+ *   before[(b*k + t)]             number of entries operand t stores in the
+ *                                 intersected rows before the boundary
+ *   cost[b]                       C(boundary) = sum_t before
+ * Tprime must hold M + 1 entries and returns T'.
+ */
+int ora_recursive_partition_dcsr(int k, const int32_t *const *pos1, const int32_t *const *crd1,
+                                 int64_t n_cols, int64_t M, int64_t cap, const int64_t *rpos,
+                                 const int64_t *T, int64_t P, const int64_t *queries,
+                                 int64_t *Tprime, int64_t *coord, int64_t *lpos, int64_t *before,
+                                 int64_t *cost)
+{
+    if (k < 1 || k > ORA_MAXK || P < 1 || M < 0) return -1;
+    Tprime[0] = 0;
+    for (int64_t x = 0; x < M; ++x) Tprime[x + 1] = Tprime[x] + T[x];
+    const int64_t total = Tprime[M];
+    /* per operand: entries stored in the intersected rows before row y (for `before`) */
+    int64_t *rows_before = (int64_t *)malloc(sizeof(int64_t) * (size_t)k * (size_t)(M + 1));
+    if (!rows_before) return -1;
+    for (int t = 0; t < k; ++t) {
+        int64_t *s = rows_before + (size_t)t * (M + 1);
+        s[0] = 0;
+        for (int64_t y = 0; y < M; ++y) {
+            int64_t q = rpos[(size_t)t * cap + y];
+            s[y + 1] = s[y] + (pos1[t][q + 1] - pos1[t][q]);
+        }
+    }
+    for (int64_t b = 0; b <= P; ++b) {
+        int64_t Q = queries ? queries[b] : equal_query(b, total, P);
+        int64_t x, j = 0, R;
+        if (b == 0) { x = 0; R = 0; Q = 0; }
+        else if (b == P || Q >= total) { x = M; R = 0; Q = total; }
+        else {
+            /* level i': highest x in [0, M] with C'_i(x) = T'[x] <= Q */
+            int64_t low = 0, high = M;
+            while (low < high) {
+                int64_t mid = low + (high - low + 1) / 2;
+                if (Tprime[mid] <= Q) low = mid; else high = mid - 1;
+            }
+            x = low;
+            R = Q - Tprime[x];
+            /* level j inside row x: highest j in [0, N_j] with C_j(j | x) <= R */
+            int64_t lowj = 0, highj = n_cols;
+            while (lowj < highj) {
+                int64_t mid = lowj + (highj - lowj + 1) / 2;
+                int64_t c = 0;
+                for (int t = 0; t < k; ++t) {
+                    int64_t q = rpos[(size_t)t * cap + x];
+                    c += lower_bound(crd1[t], pos1[t][q], pos1[t][q + 1], mid) - pos1[t][q];
+                }
+                if (c <= R) lowj = mid; else highj = mid - 1;
+            }
+            j = lowj;
+        }
+        coord[b * 2 + 0] = x;
+        coord[b * 2 + 1] = j;
+        int64_t csum = 0;
+        for (int t = 0; t < k; ++t) {
+            int64_t at, bef = rows_before[(size_t)t * (M + 1) + x];
+            if (x < M) {
+                int64_t q = rpos[(size_t)t * cap + x];
+                at = lower_bound(crd1[t], pos1[t][q], pos1[t][q + 1], j);
+                bef += at - pos1[t][q];
+            } else if (M > 0) {
+                at = pos1[t][rpos[(size_t)t * cap + M - 1] + 1];
+            } else {
+                at = pos1[t][0];
+            }
+            lpos[b * k + t] = at;
+            before[b * k + t] = bef;
+            csum += bef;
+        }
+        cost[b] = csum;
+        (void)R;
+    }
+    free(rows_before);
+    return 0;
+}
