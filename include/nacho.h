@@ -55,7 +55,9 @@ typedef enum {
 
 typedef enum { NACHO_F32 = 0, NACHO_F64 = 1 } nacho_dtype;
 typedef enum { NACHO_DENSE = 0, NACHO_COMPRESSED = 1 } nacho_level_kind;
-typedef enum { NACHO_OP_PARTITION = 0, NACHO_OP_SPMV = 1, NACHO_OP_SPMM = 2, NACHO_OP_SPADD = 3 } nacho_op;
+typedef enum {
+    NACHO_OP_PARTITION = 0, NACHO_OP_SPMV = 1, NACHO_OP_SPMM = 2, NACHO_OP_SPADD = 3, NACHO_OP_SPMUL = 4
+} nacho_op;
 
 #define NACHO_MAX_OPERANDS 8
 #define NACHO_MAX_LEVELS 2
@@ -135,7 +137,8 @@ int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int
 
 /* Bytes of device workspace `op` needs for these operands (host descriptors;
  * only counts/extents are read).  `P` as passed to the call (0 = automatic),
- * `n_dense` = columns of B for SpMM (0 otherwise). */
+ * `n_dense` = columns of B for SpMM (0 otherwise).  NACHO_OP_SPADD sizes
+ * nacho_spadd_k, NACHO_OP_SPMUL nacho_spmul_k. */
 int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                               int64_t n_dense, int64_t P, size_t *bytes);
 
@@ -214,7 +217,24 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
  * an entry is emitted when all k operands store its coordinate, its value is
  * the product in operand order.  Same arguments, output layout, status and
  * capacity rules as nacho_spadd_k (min_t nnz_t is always a sufficient cap_nnz).
- * DCSR operands: NACHO_ERR_UNSUPPORTED (outer-level intersection).
+ *
+ * DCSR operands intersect on the OUTER level as well, and rows that not every
+ * operand stores are skipped with everything below them, so the plain non-zero
+ * count is the wrong cost.  The call then follows the recursive partitioning of
+ * Section 3.3 (Algorithm 2): a first, separately partitioned loop intersects
+ * the operands' row coordinates and memoises, for the i'-th row all operands
+ * store, T[i'] = the number of entries the operands store in it; the prefix sum
+ * T' is the remapped cost function C'_i(x) = T'[x]; Algorithm 1 on the
+ * remapped nest (i' over the intersected rows, then the columns) gives the
+ * partitions of the product.  A row of the result is stored only when it holds
+ * an entry (min_t rows_t is always a sufficient cap_rows).  The stored
+ * partitions (nacho_workspace_parts with NACHO_OP_SPMUL, after the call) are
+ * those of the remapped nest, a CSR-like space: coord = (i', j), posn[..][0] =
+ * i', posn[..][1] = the number of entries the operand stores in the
+ * intersected rows before the boundary.  Workspace: nacho_workspace_bytes with
+ * NACHO_OP_SPMUL.  Unlike the other calls this one waits for the stream once,
+ * after the row loop: the size of the remapped space decides what is launched
+ * next.
  */
 int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);

@@ -19,7 +19,7 @@ from . import build as _build
 
 F32, F64 = 0, 1
 DENSE, COMPRESSED = 0, 1
-OP_PARTITION, OP_SPMV, OP_SPMM, OP_SPADD = 0, 1, 2, 3
+OP_PARTITION, OP_SPMV, OP_SPMM, OP_SPADD, OP_SPMUL = 0, 1, 2, 3, 4
 MAX_OPERANDS, MAX_LEVELS = 8, 2
 
 EXPORTS = [
@@ -290,11 +290,13 @@ def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):
 
 
 def nacho_spmul_k(ops, out: SparseOut, P=0, ws=None):
-    """Z = product of the operands over the intersection of their coordinates (vectors, CSR)."""
+    """Z = product of the operands over the intersection of their coordinates (vectors, CSR, DCSR).
+    Enqueues only, except for DCSR operands, where the call waits once for the number of rows all
+    operands store."""
     dt = dtype_code(ops[0].val.dtype)
     dev = ops[0].val.device
     if ws is None:
-        ws = _workspace(workspace_bytes(OP_SPADD, ops, dt, 0, P), dev)
+        ws = _workspace(workspace_bytes(OP_SPMUL, ops, dt, 0, P), dev)
     arr = _pack(ops)
     _check(lib().nacho_spmul_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
                                ws.numel(), _stream()), "nacho_spmul_k")

@@ -160,6 +160,21 @@ SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Workspace of a DCSR product (recursive partitioning, Section 3.3)
+constexpr int64_t kRowGrain = 2048;     // level-0 coordinates of all operands per partition of the row loop
+struct RemapWs {
+    int64_t P0, Pmax, Mmax, count0;
+    PartsWs parts0;                  // partitions of the row loop
+    int32_t *flags, *qpos, *tsum;
+    RemapArrays remap;
+    int64_t *info;                   // {partitions, intersected rows, remapped total cost} of the last call
+    PartsWs parts;                   // partitions of the remapped nest
+    unsigned long long *tile_state;
+    int32_t *pos_full;
+    int64_t *counts;
+    size_t bytes;
+};
+
 int spadd_fmt(Format f) { return f == FMT_VECTOR ? SPADD_VECTOR : (f == FMT_CSR ? SPADD_CSR : SPADD_DCSR); }
 
 // Partitions a fused call uses: at least P, and enough that one partition's work
@@ -172,6 +187,40 @@ int64_t fused_partitions(int32_t op, Format fmt, int32_t dtype, int32_t k, int64
     else cap = spadd_capacity(spadd_fmt(fmt)) - k;
     const int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
     return P > need ? P : need;
+}
+
+RemapWs carve_remap(void *ws, const nacho_tensor *ops, int k, int32_t dtype, int64_t total_nnz, int64_t P)
+{
+    Carver c(ws);
+    RemapWs w;
+    int64_t rows_total = 0;
+    w.count0 = ops[0].lvl[0].count;
+    w.Mmax = w.count0;
+    for (int t = 0; t < k; ++t) {
+        rows_total += ops[t].lvl[0].count;
+        if (ops[t].lvl[0].count < w.Mmax) w.Mmax = ops[t].lvl[0].count;
+    }
+    w.P0 = rows_total > 0 ? ceil_div(rows_total, kRowGrain) : 1;
+    // the remapped cost never exceeds the stored non-zeros: enough partitions for any outcome
+    w.Pmax = fused_partitions(NACHO_OP_SPADD, FMT_CSR, dtype, k, total_nnz, P);
+    w.parts0 = carve_parts(c, w.P0, k, 1);
+    w.flags = c.take<int32_t>((size_t)w.count0);
+    w.qpos = c.take<int32_t>((size_t)w.count0 * (k - 1));
+    int64_t sw = remap_scan_words(w.count0, 1);
+    if (remap_scan_words(w.Mmax + 1, k) > sw) sw = remap_scan_words(w.Mmax + 1, k);
+    w.tsum = c.take<int32_t>((size_t)sw);
+    w.remap.stride = w.Mmax;
+    w.remap.rows = c.take<int32_t>((size_t)w.Mmax);
+    w.remap.start = c.take<int32_t>((size_t)w.Mmax * k);
+    w.remap.cost = c.take<int32_t>((size_t)(w.Mmax + 1) * k);
+    w.remap.head = c.take<int32_t>(1 + NACHO_MAX_OPERANDS);
+    w.info = c.take<int64_t>(4);
+    w.parts = carve_parts(c, w.Pmax, k, 2);
+    w.tile_state = c.take<unsigned long long>((size_t)spadd_state_words(w.Pmax));
+    w.pos_full = c.take<int32_t>((size_t)w.Mmax + 1);
+    w.counts = c.take<int64_t>(2);
+    w.bytes = align_up(c.off, 256);
+    return w;
 }
 
 }  // namespace
@@ -208,7 +257,9 @@ int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int
     case NACHO_OP_SPMM:
         if (k != 1 || fmt != FMT_CSR) return 0;
         return fused_partitions(op, fmt, dtype, k, total, P);
-    case NACHO_OP_SPADD: return fused_partitions(op, fmt, dtype, k, total, P);
+    case NACHO_OP_SPADD:
+    case NACHO_OP_SPMUL:      // (a DCSR product: an upper bound, the count depends on the intersected rows)
+        return fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     default: return 0;
     }
 }
@@ -232,8 +283,14 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
         *bytes = carve_carry(nullptr, Pe, dtype, op == NACHO_OP_SPMM ? NACHO_WAVE : 1).bytes;
         return NACHO_OK;
     }
+    case NACHO_OP_SPMUL:
+        if (fmt == FMT_DCSR && k > 1) {
+            *bytes = carve_remap(nullptr, ops, k, dtype, total, P).bytes;
+            return NACHO_OK;
+        }
+        /* fall through: the pipeline of the union */
     case NACHO_OP_SPADD: {
-        const int64_t Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
         *bytes = carve_spadd(nullptr, Pe, k, dev.d).bytes;
         return NACHO_OK;
     }
@@ -267,8 +324,21 @@ int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, in
         if (P == 0) g = op == NACHO_OP_SPMV ? (int64_t)spmv_capacity(dtype) : (int64_t)spmm_capacity(dtype) * n_dense;
         break;
     }
+    case NACHO_OP_SPMUL:
+        if (fmt == FMT_DCSR && k > 1) {
+            RemapWs c = carve_remap(ws, ops, k, dtype, total, P);
+            if (ws_bytes < c.bytes) return NACHO_ERR_WORKSPACE;
+            int64_t info[4];
+            if (hipMemcpy(info, c.info, sizeof(info), hipMemcpyDeviceToHost) != hipSuccess) return NACHO_ERR_HIP;
+            if (info[0] < 0 || info[0] > c.Pmax) return NACHO_ERR_INVALID_ARG;   // no call has run on ws
+            w = c.parts;
+            Pe = info[0];
+            need = c.bytes;
+            break;
+        }
+        /* fall through */
     case NACHO_OP_SPADD: {
-        Pe = fused_partitions(op, fmt, dtype, k, total, P);
+        Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
         SpaddWs c = carve_spadd(ws, Pe, k, dev.d);
         w = c.parts;
         need = c.bytes;
@@ -374,6 +444,96 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
     return NACHO_OK;
 }
 
+// Product of k >= 2 DCSR matrices: the rows are intersected first and the cost
+// function of the row loop is remapped (Section 3.3, Algorithm 2); the remapped
+// nest then runs through the partition and merge kernels of the CSR product.
+static int32_t dcsr_product(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P, const DevOperands &dev,
+                            int64_t total, const SpaddValues &vals, const SpaddOut &o, void *ws,
+                            size_t ws_bytes, hipStream_t s)
+{
+    RemapWs w = carve_remap(ws, ops, k, dtype, total, P);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    profile_begin(s);
+    bool empty = false;
+    for (int t = 0; t < k; ++t)
+        if (ops[t].lvl[0].count == 0 || ops[t].lvl[1].count == 0) empty = true;
+    int32_t head[1 + NACHO_MAX_OPERANDS] = {0};
+    int64_t remapped_total = 0;
+    if (!empty) {
+        // 1. the row loop on its own partitions (Algorithm 1 on the level-0 coordinate arrays)
+        DevOperands rows;
+        std::memset(&rows, 0, sizeof(rows));
+        rows.k = k;
+        rows.d = 1;
+        int64_t rows_total = 0;
+        for (int t = 0; t < k; ++t) {
+            rows.lvl[t][0] = dev.lvl[t][0];
+            rows_total += dev.lvl[t][0].count;
+        }
+        if (hipMemsetAsync(w.remap.cost, 0, sizeof(int32_t) * (size_t)(w.Mmax + 1) * k, s) != hipSuccess)
+            return NACHO_ERR_HIP;
+        if (launch_partition(rows, 1, w.P0, 0, nullptr, rows_total, w.parts0.coord, w.parts0.posn, w.parts0.cost,
+                             s) != hipSuccess)
+            return NACHO_ERR_HIP;
+        profile_mark("rows_partition");
+        if (launch_rows_match(dev, w.P0, w.parts0.posn, w.flags, w.qpos, s) != hipSuccess) return NACHO_ERR_HIP;
+        profile_mark("rows_match");
+        // 2. T (per operand) and the rows' places, 3. its prefix sums: the remapped cost function
+        if (launch_remap_rows(dev, w.flags, w.qpos, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
+        profile_mark("remap_rows");
+        if (launch_remap_costs(k, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
+        profile_mark("remap_costs");
+        // the size of the remapped space decides the launch of everything below
+        if (hipMemcpyAsync(head, w.remap.head, sizeof(int32_t) * (size_t)(1 + k), hipMemcpyDeviceToHost, s) !=
+                hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return NACHO_ERR_HIP;
+        for (int t = 0; t < k; ++t) remapped_total += head[1 + t];
+        empty = head[0] == 0 || remapped_total == 0;
+    }
+    if (empty) {
+        if (launch_empty_result(o, w.info, s) != hipSuccess) return NACHO_ERR_HIP;
+        profile_mark("empty_result");
+        return NACHO_OK;
+    }
+    const int64_t M = head[0];
+    DevOperands mapped;
+    std::memset(&mapped, 0, sizeof(mapped));
+    mapped.k = k;
+    mapped.d = 2;
+    for (int t = 0; t < k; ++t) {
+        mapped.lvl[t][0].kind = NACHO_DENSE;
+        mapped.lvl[t][0].extent = M;
+        mapped.lvl[t][1].kind = NACHO_COMPRESSED;
+        mapped.lvl[t][1].extent = dev.lvl[t][1].extent;
+        mapped.lvl[t][1].pos = w.remap.cost + (size_t)t * (w.Mmax + 1);
+        mapped.lvl[t][1].crd = dev.lvl[t][1].crd;
+        mapped.lvl[t][1].count = head[1 + t];
+        mapped.start[t] = w.remap.start + (size_t)t * w.Mmax;
+    }
+    int64_t Pe = fused_partitions(NACHO_OP_SPADD, FMT_CSR, dtype, k, remapped_total, P);
+    if (Pe > w.Pmax) Pe = w.Pmax;          // (cannot happen: remapped_total <= total)
+    SpaddOut mo = o;                        // the remapped result: CSR over the intersected rows
+    mo.pos0 = nullptr;
+    mo.crd0 = nullptr;
+    mo.pos1 = w.pos_full;
+    mo.cap_rows = M;
+    mo.counts = w.counts;
+    if (launch_partition(mapped, 1, Pe, 0, nullptr, remapped_total, w.parts.coord, w.parts.posn, w.parts.cost, s,
+                         w.tile_state, spadd_state_words(Pe), o.status) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    if (launch_spadd(SPADD_CSR, dtype, true, mapped, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, mo, s) !=
+        hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmul_merge");
+    const int64_t info_vals[3] = {Pe, M, remapped_total};
+    if (launch_compact_rows(M, w.remap, w.pos_full, w.counts, o, info_vals, w.info, w.tsum, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("rows_compact");
+    return NACHO_OK;
+}
+
 // nacho_spadd_k and nacho_spmul_k: the same pipeline, sums over the union or products over the intersection
 static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
                        const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
@@ -385,9 +545,8 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     Format fmt;
     int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
     if (rc != NACHO_OK) return rc;
-    // a product of DCSR operands intersects the OUTER level: that takes the recursive
-    // partitioning of Section 3.3, which is not built
-    if (multiply && fmt == FMT_DCSR) return NACHO_ERR_UNSUPPORTED;
+    // (the product of one operand is the operand: the union's pipeline copies it)
+    if (multiply && fmt == FMT_DCSR && k == 1) multiply = false;
     SpaddValues vals;
     std::memset(&vals, 0, sizeof(vals));
     for (int t = 0; t < k; ++t) {
@@ -401,12 +560,15 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     if (fmt == FMT_DCSR && (!out->pos0 || (out->cap_rows > 0 && !out->crd0))) return NACHO_ERR_INVALID_ARG;
     const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
-    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    const bool recursive = multiply && fmt == FMT_DCSR && k > 1;    // (its own workspace layout)
+    if (!recursive && (!ws || ws_bytes < w.bytes)) return NACHO_ERR_WORKSPACE;
     SpaddOut o;
     o.pos0 = out->pos0; o.crd0 = out->crd0; o.pos1 = out->pos1; o.crd1 = out->crd1; o.val = out->val;
     o.cap_rows = out->cap_rows; o.cap_nnz = out->cap_nnz; o.counts = out->counts; o.status = out->status;
     const int f = spadd_fmt(fmt);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // a product of DCSR operands intersects the OUTER level
+    if (multiply && fmt == FMT_DCSR) return dcsr_product(ops, k, dtype, P, dev, total, vals, o, ws, ws_bytes, s);
     profile_begin(s);
     // the partition kernel also clears the prefix-sum state and the status word of the call
     if (launch_partition(dev, 1, Pe, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s,

@@ -23,6 +23,10 @@ struct DevLevel {
 struct DevOperands {
     int32_t k, d;
     DevLevel lvl[NACHO_MAX_OPERANDS][NACHO_MAX_LEVELS];
+    // Remapped operands (Section 3.3; dense level 0 over the intersected rows): the entries of
+    // row i' of operand t are stored from position start[t][i'] of crd / val on, while the
+    // level-1 pos array counts only the entries of the intersected rows.  NULL otherwise.
+    const int32_t *start[NACHO_MAX_OPERANDS];
 };
 
 // floor(p * total / P) for 0 <= p <= P < 2^31 without leaving int64.

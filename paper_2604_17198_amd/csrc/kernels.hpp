@@ -58,4 +58,33 @@ hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &op
                         int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
                         const SpaddOut &out, hipStream_t s);
 
+// ---- recursive partitioning for an outer intersection (DCSR products) -----------
+// Memoised row loop of Section 3.3, all arrays on the device:
+//   rows[i']                    coordinate of the i'-th row all operands store
+//   start[t * stride + i']      position in operand t's crd / val of that row's first entry
+//   cost[t * (stride + 1) + x]  entries operand t stores in the intersected rows before row x
+//                               (x <= stride; rows past the last intersected one hold nothing)
+//   head[0] = number M of intersected rows, head[1 + t] = cost[t][stride]
+struct RemapArrays {
+    int32_t *rows, *start, *cost, *head;
+    int64_t stride;
+};
+// 32-bit words of scratch a prefix sum over `batch` arrays of n items uses.
+int64_t remap_scan_words(int64_t n, int batch);
+// flags[e] = all operands store row crd0_0[e]; qpos[(t-1) * count_0 + e] = its position in operand t.
+// posn0: boundaries of a P0-way partition of the operands' level-0 coordinate arrays.
+hipError_t launch_rows_match(const DevOperands &ops, int64_t P0, const int32_t *posn0, int32_t *flags,
+                             int32_t *qpos, hipStream_t s);
+// rows, start and the per-row entry counts (in r.cost, which must be zero beforehand), head[0]
+hipError_t launch_remap_rows(const DevOperands &ops, const int32_t *flags, const int32_t *qpos,
+                             const RemapArrays &r, int32_t *tsum, hipStream_t s);
+// r.cost: per-row counts -> exclusive prefix sums (in place), head[1 + t]
+hipError_t launch_remap_costs(int k, const RemapArrays &r, int32_t *tsum, hipStream_t s);
+// Result rows that hold an entry: pos_full[M + 1] over the intersected rows -> out.pos0 / crd0 /
+// pos1 / counts (counts_in = {M, nnz} of the remapped result); info[0..2] = info_vals.
+hipError_t launch_compact_rows(int64_t M, const RemapArrays &r, const int32_t *pos_full,
+                               const int64_t *counts_in, const SpaddOut &out, const int64_t *info_vals,
+                               int64_t *info, int32_t *tsum, hipStream_t s);
+hipError_t launch_empty_result(const SpaddOut &out, int64_t *info, hipStream_t s);
+
 }  // namespace nacho

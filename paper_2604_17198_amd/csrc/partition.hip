@@ -88,6 +88,10 @@ __device__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, in
     return r;
 }
 
+// (In all searches of a compressed level, sh[t] is added to operand t's positions
+// where its coordinates are read: the offset between the positions the cost is
+// counted in and the storage of a remapped operand's row, 0 otherwise.)
+//
 // 64-ary search over coordinates with one lower-bound search per operand and
 // probe inside tracked windows [wl, wh] (the specialised search of Section
 // 4.2.3, 64 probes per round).  Lower bounds are clamped to the windows, which
@@ -96,7 +100,7 @@ __device__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, in
 // below stops making progress.
 template <bool kLast, int K>
 __device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, const int *base,
-                                      int *wl, int *wh, int64_t c_low, int *p)
+                                      int *wl, int *wh, int64_t c_low, int *p, const int *sh)
 {
     const int lane = lane_id();
     const int k = ops.k;
@@ -111,7 +115,7 @@ __device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, 
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             if (t >= k) break;
-            const int q = lower_bound_global(ops.lvl[t][m].crd, wl[t], wh[t], x);
+            const int q = lower_bound_global(ops.lvl[t][m].crd + sh[t], wl[t], wh[t], x);
             ip[t] = q;
             c += kLast ? (int64_t)(q - base[t]) : (int64_t)(ops.lvl[t][m + 1].pos[q] - base[t]);
         }
@@ -184,7 +188,7 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 //   otherwise:   R_lo == R_hi; runs until the boundary is found.
 template <bool kLast, int K>
 __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
-                                      Windows<K> &W, bool narrow_only, int *p)
+                                      Windows<K> &W, bool narrow_only, int *p, const int *sh)
 {
     // costs, positions and coordinates all fit 32 bits (the operands hold fewer than
     // 2^31 entries together; INT32_MAX is no coordinate)
@@ -220,7 +224,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
             int64_t c0 = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p);
+            return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p, sh);
         }
         prev_total = total;
 #pragma unroll
@@ -231,7 +235,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
             cb[t] = s - base[t];
             ca[t] = s + 1 - base[t];
             if (t < k) {
-                if (valid) v[t] = ops.lvl[t][m].crd[s];
+                if (valid) v[t] = ops.lvl[t][m].crd[s + sh[t]];
                 if (!kLast) {
                     const int32_t *pos = ops.lvl[t][m + 1].pos;
                     cb[t] = valid ? pos[s] - base[t] : 0;
@@ -339,7 +343,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     l[t] = W.l[t]; h[t] = W.h[t];
                     c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p);
+                return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p, sh);
             }
             r.x = vminus;
 #pragma unroll
@@ -362,7 +366,8 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
 // position of operand t's first entry with coordinate >= x inside its segment.
 template <bool kLast, int K>
 __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
-                                        const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p)
+                                        const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p,
+                                        const int *sh)
 {
     const int k = ops.k;
     LevelResult r;
@@ -385,11 +390,15 @@ __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R
         for (int t = 0; t < K; ++t)
             if (t < k) p[t] = seg_lo[t];
         p[which] = seg_lo[which] + (int)R;
-        r.x = ops.lvl[which][m].crd[p[which]];
+        int at = p[which];
+#pragma unroll
+        for (int t = 0; t < K; ++t)
+            if (t == which) at += sh[t];
+        r.x = ops.lvl[which][m].crd[at];
         r.c = R;
         return r;
     }
-    return sampled_search<kLast, K>(ops, m, R, R, W, false, p);
+    return sampled_search<kLast, K>(ops, m, R, R, W, false, p, sh);
 }
 
 template <bool kLast, int K>
@@ -458,15 +467,18 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             seg0_hi[t] = (L.kind == NACHO_DENSE) ? (int)L.extent : (int)L.count;
         }
     }
+    int no_shift[K];
+#pragma unroll
+    for (int t = 0; t < K; ++t) no_shift[t] = 0;
     Windows<K> W0;
     if (!dense0 && q_first >= 0) {
         int dummy[K];
         if (d == 1) {
             windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
-            if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy);
+            if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
         } else {
             windows_init<false, K>(ops, 0, seg0_lo, seg0_hi, W0);
-            if (q_last > q_first) sampled_search<false, K>(ops, 0, q_first, q_last, W0, true, dummy);
+            if (q_last > q_first) sampled_search<false, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
         }
     }
 
@@ -495,7 +507,7 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
         int64_t R = Qu[g];
         if (d == 1) {
             Windows<K> W = W0;
-            LevelResult r = compressed_level<true, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p);
+            LevelResult r = compressed_level<true, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p, no_shift);
             R -= r.c;
             if (lane == 0) {
                 cb[0] = (int32_t)r.x;
@@ -506,13 +518,14 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             if (dense0) r0 = dense_search<K>(ops, 0, R, p);
             else {
                 Windows<K> W = W0;
-                r0 = compressed_level<false, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p);
+                r0 = compressed_level<false, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p, no_shift);
             }
             R -= r0.c;
-            int p0[K];
+            int p0[K], sh[K];
 #pragma unroll
             for (int t = 0; t < K; ++t) {
                 p0[t] = 0;
+                sh[t] = 0;
                 seg_lo[t] = seg_hi[t] = 0;
                 if (t < k) {
                     p0[t] = p[t];
@@ -524,12 +537,13 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                     const int lo1 = pos1[p[t]];
                     seg_lo[t] = lo1;
                     seg_hi[t] = present ? pos1[p[t] + 1] : lo1;
+                    if (present && ops.start[t]) sh[t] = ops.start[t][p[t]] - lo1;   // remapped row
                 }
             }
             Windows<K> W1;
             windows_init<true, K>(ops, 1, seg_lo, seg_hi, W1);
             const int64_t tot1 = level_total<true, K>(ops, 1, seg_lo, seg_hi);
-            LevelResult r1 = compressed_level<true, K>(ops, 1, R, tot1, seg_lo, seg_hi, W1, p);
+            LevelResult r1 = compressed_level<true, K>(ops, 1, R, tot1, seg_lo, seg_hi, W1, p, sh);
             R -= r1.c;
             if (lane == 0) {
                 cb[0] = (int32_t)r0.x;
@@ -639,7 +653,7 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
     clear.words = clear_words;
     clear.n = clear_words ? n_clear : 0;
     clear.status = clear_status;
-    if (ops.k == 1 && ops.d == 2 && ops.lvl[0][0].kind == NACHO_DENSE && !queries &&
+    if (ops.k == 1 && ops.d == 2 && ops.lvl[0][0].kind == NACHO_DENSE && !queries && !ops.start[0] &&
         (grain == 0 || grain % cost_scale == 0)) {
         QueryRule rule;
         rule.P = P;

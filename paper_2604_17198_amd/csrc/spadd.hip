@@ -142,6 +142,8 @@ struct Tile {
     uint32_t marks[kPadded];              // staging: row markers; ranking words (padded); slot words
     unsigned long long scrd[NACHO_MAX_OPERANDS];   // address of crd of run t, biased so that [c] is entry c of keys
     unsigned long long sval[NACHO_MAX_OPERANDS];   // the same for the values
+    unsigned long long sstart[NACHO_MAX_OPERANDS]; // remapped operands: address of start[t] and of pos of run t
+    unsigned long long spos[NACHO_MAX_OPERANDS];
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
     uint32_t srun[NACHO_MAX_OPERANDS];             // start of run t | marks summed before it << 16
     uint32_t wave_x[kWaves];                       // per-wavefront partial of a scan across the workgroup
@@ -212,7 +214,10 @@ __device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
 // kMul: the k-way intersection with products (an entry is emitted when all k
 // operands store its coordinate, Section 2.1) instead of the union with sums;
 // the partitions, the ranks and the prefix sum are the same.
-template <int FMT, typename T, int K, bool kMul>
+// kMapped: the operands are remapped ones (Section 3.3): CSR over the rows all
+// operands store, positions counted over those rows only; the entries of row
+// i' of operand t are read from start[t][i'] on.
+template <int FMT, typename T, int K, bool kMul, bool kMapped>
 __global__ void __launch_bounds__(kThreads)
 spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
@@ -263,6 +268,10 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
                 w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
                 w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
+                if (kMapped) {
+                    w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.start[t] : nullptr);
+                    w.spos[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].pos : nullptr);
+                }
             }
         }
     }
@@ -282,7 +291,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     for (int r = 0; r < R; ++r) {
         const int c = r * kThreads + tid;
         col[r] = 0;
-        if (c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c];
+        if (!kMapped && c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c];
     }
 
     uint32_t row[D == 2 ? R : 1];
@@ -360,6 +369,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 #pragma unroll
         for (int r = 0; r < R; ++r) row[r] = w.marks[pad(r * kThreads + tid)] - 1u;
         __syncthreads();                           // markers are read: the ranking may clear them
+    }
+    int sh[kMapped ? R : 1];                   // remapped: storage position - counted position of an entry
+    if (kMapped) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * kThreads + tid;
+            sh[r] = 0;
+            if (c < n) {
+                const int32_t *st = reinterpret_cast<const int32_t *>((uintptr_t)w.sstart[tr[r]]);
+                const int32_t *ps = reinterpret_cast<const int32_t *>((uintptr_t)w.spos[tr[r]]);
+                sh[r] = st[row[D == 2 ? r : 0]] - ps[row[D == 2 ? r : 0]];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * kThreads + tid;
+            if (c < n) col[r] = reinterpret_cast<const int32_t *>((uintptr_t)w.scrd[tr[r]])[c + sh[r]];
+        }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -490,7 +517,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     for (int r = 0; r < R; ++r) {
         const int c = r * kThreads + tid;
         val[r] = T(0);
-        if (c < n) val[r] = reinterpret_cast<const T *>((uintptr_t)w.sval[tr[r]])[c];
+        if (c < n) val[r] = reinterpret_cast<const T *>((uintptr_t)w.sval[tr[r]])[c + (kMapped ? sh[kMapped ? r : 0] : 0)];
     }
     __syncthreads();
 
@@ -665,24 +692,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 
 int64_t chunks_of(int64_t P) { return (P + kChunk - 1) / kChunk; }
 
-template <int FMT, typename T, int K, bool kMul>
+template <int FMT, typename T, int K, bool kMul, bool kMapped>
 hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                     const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    hipLaunchKernelGGL((spadd_kernel<FMT, T, K, kMul>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
+    hipLaunchKernelGGL((spadd_kernel<FMT, T, K, kMul, kMapped>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
                        P, chunks_of(P), coord, posn, tile_state, out);
     return hipGetLastError();
 }
 
 // instantiated for up to 2, 3, 4 and 8 operands: the per-entry loops over the runs are unrolled
-template <int FMT, typename T, bool kMul>
+template <int FMT, typename T, bool kMul, bool kMapped = false>
 hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                       const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
-    if (ops.k <= 2) return launch_k<FMT, T, 2, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
-    if (ops.k <= 3) return launch_k<FMT, T, 3, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
-    if (ops.k <= 4) return launch_k<FMT, T, 4, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
-    return launch_k<FMT, T, 8, kMul>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 2) return launch_k<FMT, T, 2, kMul, kMapped>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 3) return launch_k<FMT, T, 3, kMul, kMapped>(ops, vals, P, coord, posn, tile_state, out, s);
+    if (ops.k <= 4) return launch_k<FMT, T, 4, kMul, kMapped>(ops, vals, P, coord, posn, tile_state, out, s);
+    return launch_k<FMT, T, 8, kMul, kMapped>(ops, vals, P, coord, posn, tile_state, out, s);
 }
 
 }  // namespace
@@ -705,9 +732,14 @@ hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &op
     NACHO_SPADD_CASE(SPADD_CSR, false)
     NACHO_SPADD_CASE(SPADD_DCSR, false)
     NACHO_SPADD_CASE(SPADD_VECTOR, true)
+    if (fmt == SPADD_CSR && multiply && ops.start[0]) {       // remapped operands of a DCSR product
+        if (dtype == NACHO_F64)
+            return launch_one<SPADD_CSR, double, true, true>(ops, vals, P, coord, posn, tile_state, out, s);
+        return launch_one<SPADD_CSR, float, true, true>(ops, vals, P, coord, posn, tile_state, out, s);
+    }
     NACHO_SPADD_CASE(SPADD_CSR, true)
 #undef NACHO_SPADD_CASE
-    return hipErrorInvalidValue;    // (DCSR products intersect the outer level: not built)
+    return hipErrorInvalidValue;    // (a DCSR product reaches this kernel as remapped CSR operands)
 }
 
 }  // namespace nacho

@@ -105,17 +105,6 @@ def test_capacity_overflow_is_reported():
     assert np.array_equal(out.crd1.cpu().numpy()[:ri.shape[0] - 5], ri[:-5])
 
 
-def test_dcsr_is_unsupported():
-    p0 = dev(np.array([0, 1], np.int32)); c0 = dev(np.array([0], np.int32))
-    p1 = dev(np.array([0, 1], np.int32)); c1 = dev(np.array([0], np.int32))
-    v = dev(np.array([1.0], np.float32))
-    ops = [nb.dcsr(p0, c0, p1, c1, 4, 4, v), nb.dcsr(p0, c0, p1, c1, 4, 4, v)]
-    out = nb.SparseOut("dcsr", 2, 2, torch.float32, "cuda")
-    with pytest.raises(nb.NachoError) as e:
-        nb.nacho_spmul_k(ops, out)
-    assert e.value.status == -2
-
-
 def test_config3_vectors_full_size():
     """The three vectors of configuration 3 multiplied: coordinates stored by all of a, b and c."""
     cfg = workloads.config(3)
