@@ -215,6 +215,23 @@ def bench_others(steps, warmup):
             n_mul = int(out.counts.cpu().numpy()[1])
             record("F2_vec3", f"3-way sparse-vector multiply (intersection) on the C3 vectors, {tot} input nnz, "
                    f"{n_mul} output nnz", fm, tot, tot * 8 + n_mul * 8)
+        if c == 4:
+            # F3: the same two matrices multiplied: an OUTER intersection, recursive partitioning
+            outm = nb.SparseOut("dcsr", min(int(m["crd0"].shape[0]) for m in cfg["ops"]), min(o.nnz for o in ops),
+                                torch.float32, "cuda")
+            wsm = torch.empty(nb.workspace_bytes(nb.OP_SPMUL, ops, nb.F32), dtype=torch.uint8, device="cuda")
+            fm = lambda: nb.nacho_spmul_k(ops, outm, ws=wsm)
+            fm()
+            torch.cuda.synchronize()
+            r_mul, n_mul = (int(v) for v in outm.counts.cpu().numpy())
+            tab = nb.workspace_parts(nb.OP_SPMUL, ops, nb.F32, wsm)
+            work = int(tab["cost"][-1])                 # entries in the rows both operands store
+            m_rows = int(tab["coord"][-1, 0])
+            nbytes_m = work * 8 + rows * 4 + m_rows * 2 * 4 * len(ops) + n_mul * 8 + r_mul * 8
+            record("F3_dcsr2", f"DCSR Hadamard product of the C4 matrices (recursive partitioning): {rows} stored "
+                   f"rows, {m_rows} in both, {work} of {tot} input nnz coiterated, {n_mul} output nnz", fm, work,
+                   nbytes_m, table=lambda: nb.workspace_parts(nb.OP_SPMUL, ops, nb.F32, wsm))
+            del outm, wsm
         del ops, out, ws, cfg
     for kk in (2, 3):
         cfg = workloads.csr_add_config(kk)
