@@ -397,7 +397,14 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     profile_begin(s);
     const int64_t grain = (P == 0) ? spmv_capacity(dtype) : 0;
-    if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+    // (the partition kernel also writes the zeros of the rows A stores nothing in)
+    ZeroRows zero;
+    zero.base = y;
+    zero.ld = 1;
+    zero.width = 1;
+    zero.elem = (int32_t)dtype_size(dtype);
+    if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s, nullptr, 0,
+                         nullptr, &zero) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
     if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
@@ -431,7 +438,13 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
     profile_begin(s);
     // cost of a stored non-zero = n (broadcast over the dense loop); queries are multiples of n
     const int64_t grain = (P == 0) ? (int64_t)spmm_capacity(dtype) * n : 0;
-    if (launch_partition(dev, n, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s) != hipSuccess)
+    ZeroRows zero;                      // rows of C whose row of A is empty
+    zero.base = C;
+    zero.ld = ldc;
+    zero.width = (int32_t)n;
+    zero.elem = (int32_t)dtype_size(dtype);
+    if (launch_partition(dev, n, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s, nullptr, 0,
+                         nullptr, &zero) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
     if (launch_spmm_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, B, (int)n, ldb, C, ldc,

@@ -88,6 +88,26 @@ __device__ inline int lower_bound_global(const int32_t *__restrict__ crd, int lo
     return lo;
 }
 
+// First row t in [lo, hi) with pos[t + 1] > q, found by the whole wavefront (64 probes
+// per round).  Requires pos[hi] > q.  Rows lo .. t - 1 then hold nothing at or after q.
+__device__ inline int first_row_past(const int32_t *__restrict__ pos, int lo, int hi, int q)
+{
+    const int lane = lane_id();
+    while (hi - lo > 1) {
+        const int span = hi - lo;
+        const int step = (span + NACHO_WAVE - 1) / NACHO_WAVE;
+        int t = lo + lane * step;
+        if (lane == NACHO_WAVE - 1 || t > hi - 1) t = hi - 1;
+        const unsigned long long past = __ballot(pos[t + 1] > q);    // a suffix of the lanes, never empty
+        const int L = __ffsll((long long)past) - 1;
+        const int t_hit = __shfl(t, L, NACHO_WAVE);
+        const int t_prev = __shfl(t, L > 0 ? L - 1 : 0, NACHO_WAVE);
+        if (L > 0) lo = t_prev + 1;
+        hi = t_hit + 1;
+    }
+    return lo;
+}
+
 }  // namespace nacho
 
 // Host-side bookkeeping shared by the translation units.

@@ -43,6 +43,21 @@ struct ClearWords {
     }
 };
 
+}  // namespace
+
+// (declared in kernels.hpp) rows of a dense result that the one-pass CSR kernel sets to zero
+// because the operand stores nothing in them
+__device__ inline void zero_row(const ZeroRows &z, int64_t r, int lane_in_row, int lanes)
+{
+    char *row = static_cast<char *>(z.base) + r * z.ld * z.elem;
+    for (int c = lane_in_row; c < z.width; c += lanes) {
+        if (z.elem == 8) reinterpret_cast<double *>(row)[c] = 0.0;
+        else reinterpret_cast<float *>(row)[c] = 0.0f;
+    }
+}
+
+namespace {
+
 struct LevelResult {
     int64_t x;  // chosen coordinate
     int64_t c;  // C_m(x | prefix), unscaled
@@ -592,7 +607,7 @@ struct QueryRule {
 __global__ void __launch_bounds__(256)
 partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
                       int64_t count, QueryRule rule, int64_t cost_scale, int32_t *__restrict__ coord,
-                      int32_t *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear)
+                      int32_t *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear, ZeroRows zero)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     clear.run(i);
@@ -619,8 +634,10 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
     }
     // As row i: the row fields of the boundaries that fall inside it.
     int64_t b_lo = 0, b_hi = 0;
+    bool empty_row = false;
     if (i < n_rows) {
         const int64_t a = pos[i] - p0, e = pos[i + 1] - p0;
+        empty_row = e == a;
         if (e > a) {
             b_lo = rule.first_reaching(a);
             b_hi = rule.first_reaching(e);
@@ -640,6 +657,20 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
             posn[b * 2 + 0] = r;
         }
     }
+    // Rows without entries: their row of the result is zero, and the executing
+    // wavefronts may then step over them however many there are.
+    if (zero.base) {
+        if (zero.width == 1) {
+            if (empty_row) zero_row(zero, i, 0, 1);
+        } else {
+            unsigned long long left = __ballot(empty_row);
+            while (left) {
+                const int src = __ffsll((long long)left) - 1;
+                left &= left - 1;
+                zero_row(zero, i - lane + src, lane, NACHO_WAVE);
+            }
+        }
+    }
 }
 
 }  // namespace
@@ -647,12 +678,18 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
-                            unsigned long long *clear_words, int64_t n_clear, int32_t *clear_status)
+                            unsigned long long *clear_words, int64_t n_clear, int32_t *clear_status,
+                            const ZeroRows *zero_rows)
 {
     ClearWords clear;
     clear.words = clear_words;
     clear.n = clear_words ? n_clear : 0;
     clear.status = clear_status;
+    ZeroRows zero;
+    zero.base = nullptr;
+    zero.ld = 0;
+    zero.width = zero.elem = 0;
+    if (zero_rows) zero = *zero_rows;
     if (ops.k == 1 && ops.d == 2 && ops.lvl[0][0].kind == NACHO_DENSE && !queries && !ops.start[0] &&
         (grain == 0 || grain % cost_scale == 0)) {
         QueryRule rule;
@@ -664,9 +701,10 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
         if (clear.n > threads) threads = clear.n;
         hipLaunchKernelGGL(partition_csr1_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            ops.lvl[0][1].pos, ops.lvl[0][1].crd, n_rows, ops.lvl[0][1].count, rule, cost_scale,
-                           coord, posn, cost, clear);
+                           coord, posn, cost, clear, zero);
         return hipGetLastError();
     }
+    if (zero_rows) return hipErrorInvalidValue;      // only the one-pass kernel above writes them
     int64_t waves = (P + 1 + kGroup - 1) / kGroup;
     if (clear.n > waves * NACHO_WAVE) waves = (clear.n + NACHO_WAVE - 1) / NACHO_WAVE;
     const int waves_per_block = 256 / NACHO_WAVE;

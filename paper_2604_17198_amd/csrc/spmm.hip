@@ -57,24 +57,35 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     int cur_end = n1;                                  // its end inside the partition
     if (nrows > 0) { const int e = spos[1]; cur_end = e < n1 ? e : n1; }
 
-    // store the finished (or, at the partition's end, the started) row `cur` and move on
-    auto flush = [&]() {
+    // store row `cur` (to C, or to the carry buffer when the row started in an earlier partition)
+    auto store = [&]() {
         if (has_head && cur == r0) { if (col) carry_val[(int64_t)p * NACHO_WAVE + lane] = acc; }
         else if (col) C[(int64_t)cur * ldc + lane] = acc;
         acc = T(0);
+    };
+    // move on to the row that holds position q (cur_end <= q < n1).  The rows in between are
+    // empty: their rows of C are zero already (the partition kernel wrote them), so they are
+    // stepped over however many there are.
+    auto advance = [&](int q) {
         ++cur;
-        if (cur < next_first) {
-            if (cur + 1 - blk0 > RBLK) {               // slide the staged pos window
-                __syncthreads();
-                blk0 = cur;
-                const int left = next_first - blk0;
-                const int cnt = left < RBLK ? left : RBLK;
-                for (int i = lane; i <= cnt; i += NACHO_WAVE) spos[i] = pos[blk0 + i];
-                __syncthreads();
-            }
-            const int e = spos[cur + 1 - blk0];
-            cur_end = e < n1 ? e : n1;
+        const int left0 = next_first - blk0;
+        int cnt = left0 < RBLK ? left0 : RBLK;
+        if (spos[cnt] <= q) {                          // beyond the staged window: search pos
+            cur = first_row_past(pos, blk0 + cnt, next_first, q);
+            cnt = 0;                                   // forces a reload below
+        } else {
+            while (spos[cur + 1 - blk0] <= q) ++cur;   // inside the window: at most RBLK cheap steps
         }
+        if (cnt == 0 || cur + 1 - blk0 > RBLK) {       // slide the staged pos window
+            __syncthreads();
+            blk0 = cur;
+            const int left = next_first - blk0;
+            const int c2 = left < RBLK ? left : RBLK;
+            for (int i = lane; i <= c2; i += NACHO_WAVE) spos[i] = pos[blk0 + i];
+            __syncthreads();
+        }
+        const int e = spos[cur + 1 - blk0];
+        cur_end = e < n1 ? e : n1;
     };
 
     for (int q0 = n0; q0 < n1; q0 += kUnroll) {
@@ -91,12 +102,14 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
         for (int u = 0; u < kUnroll; ++u) {
             const int q = q0 + u;
             if (q < n1) {
-                while (q >= cur_end) flush();
+                if (q >= cur_end) { store(); advance(q); }
                 acc += v[u] * b[u];
             }
         }
     }
-    while (cur < next_first) flush();
+    // the row of the last non-zero (or, for a partition without work that starts inside a
+    // row, a zero carry); every row after it up to the next partition is empty
+    if (cur < next_first) store();
     if (lane == 0) carry_row[p] = has_head ? r0 : -1;
 }
 

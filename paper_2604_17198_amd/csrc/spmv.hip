@@ -118,6 +118,14 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
             __syncthreads();
             for (int i = lane; i <= nr; i += NACHO_WAVE) spos[i] = pos[r0 + rb + i];
             __syncthreads();
+            // A block of rows without entries: empty rows are zero already (the partition
+            // kernel wrote them), so the wavefront steps over them, however many there are.
+            const int q = spos[0];
+            if (q == spos[nr]) {
+                if (q >= n1) break;                     // every product of the partition is summed
+                rb = first_row_past(pos, r0 + rb + nr, r0 + nrows, q) - r0 - RBLK;
+                continue;
+            }
         }
         for (int rr0 = 0; rr0 < nr; rr0 += NACHO_WAVE) {
             const int rr = rr0 + lane;

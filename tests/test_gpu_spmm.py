@@ -63,6 +63,21 @@ def test_degenerate_shapes():
             _check(A, B, P, name)
 
 
+def test_long_runs_of_empty_rows():
+    rng = np.random.default_rng(23)
+    n_rows, n_cols = 300_000, 3000
+    lens = {90_000: 2000, 90_001: 1, 90_600: 30, 200_000: 1500, 200_513: 5, 299_999: 300}
+    rows = np.repeat(list(lens), list(lens.values()))
+    cols = np.concatenate([np.sort(rng.choice(n_cols, l, replace=False)) for l in lens.values()])
+    pos, crd = to_csr(np.stack([rows, cols], 1), n_rows)
+    A = {"n_rows": n_rows, "n_cols": n_cols, "pos": pos, "crd": crd,
+         "val": rng.uniform(-1, 1, crd.shape[0]).astype(np.float32)}
+    for n in (64, 9):
+        B = rng.uniform(-1, 1, (n_cols, n)).astype(np.float32)
+        for P in (0, 1, 6):
+            _check(A, B, P, "empty runs")
+
+
 def test_leading_dimensions():
     rng = np.random.default_rng(23)
     c = random_coords(rng, (500, 400), 6000)

@@ -71,6 +71,23 @@ def test_degenerate_shapes(dtype):
             _check(A, x, P, name)
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_long_runs_of_empty_rows(dtype):
+    """A few stored rows among hundreds of thousands of empty ones (at the start, between stored
+    rows, at the end): the empty rows are exactly 0 and cost the executing wavefronts nothing."""
+    rng = np.random.default_rng(5)
+    n_rows, n_cols = 700_000, 4000
+    lens = {150_000: 3000, 150_001: 1, 150_700: 40, 420_000: 2500, 420_513: 7, 699_998: 600}
+    rows = np.repeat(list(lens), list(lens.values()))
+    cols = np.concatenate([np.sort(rng.choice(n_cols, l, replace=False)) for l in lens.values()])
+    pos, crd = to_csr(np.stack([rows, cols], 1), n_rows)
+    A = {"n_rows": n_rows, "n_cols": n_cols, "pos": pos, "crd": crd,
+         "val": rng.uniform(-1, 1, crd.shape[0]).astype(dtype)}
+    x = rng.uniform(-1, 1, n_cols).astype(dtype)
+    for P in (0, 1, 5, 64):
+        _check(A, x, P, "empty runs")
+
+
 def test_config1_all_partition_counts():
     cfg = workloads.config(1)
     for P in (0, 1, 20, 333, 50_000):          # 50_000 > nnz: repeated boundaries
