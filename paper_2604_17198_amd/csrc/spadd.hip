@@ -147,6 +147,7 @@ struct Tile {
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
     uint32_t srun[NACHO_MAX_OPERANDS];             // start of run t | marks summed before it << 16
     uint32_t wave_x[kWaves];                       // per-wavefront partial of a scan across the workgroup
+    uint32_t wave_e[kWaves];                       // per-wavefront number of emitted entries (known after the ranking)
     unsigned long long wave_cnt[kWaves];           // per-wavefront counts of the assembly (rows << 31 | nnz)
     unsigned long long base;                       // the partition's offset (rows << 31 | nnz)
     __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
@@ -430,16 +431,33 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         // inclusive prefix sum of the marks (bits 0..15) over all runs at once; a
         // thread owns R consecutive words, the other bits stay
         uint32_t v[R];
-        int sum = 0;
+        int sum = 0, emitted = 0;
         const int at = tid * (R + 1);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             v[j] = w.marks[at + j];
             sum += (int)(v[j] & 0xffffu);
+            // entry tid * R + j is emitted when no operand before its own stores its key
+            // (kMul: when all k - 1 operands before its own do)
+            const int met = (int)((v[j] >> kDupShift) & 0xfu);
+            if (tid * R + j < n) emitted += (kMul ? met == k - 1 : met == 0) ? 1 : 0;
         }
         const int incl = wave_inclusive_scan(sum);
         if (lane == NACHO_WAVE - 1) w.wave_x[wave] = (uint32_t)incl;
+        if (FMT != SPADD_DCSR) {
+            emitted = wave_sum<int>(emitted);
+            if (lane == 0) w.wave_e[wave] = (uint32_t)emitted;
+        }
         __syncthreads();
+        if (FMT != SPADD_DCSR && tid == 0) {
+            // The partition's output count is known here, long before its offset is needed:
+            // published now, the workgroups after this one rarely find it missing.
+            unsigned e = 0;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) e += w.wave_e[ww];
+            unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);
+            __hip_atomic_store(&words[p], kWordValid | e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         int run = incl - sum;
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww)
@@ -533,7 +551,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
         unsigned long long *totals = tile_state;                                        // one per chunk
         unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
-        if (lane == 0)
+        if (FMT == SPADD_DCSR && lane == 0)       // (the other formats published after the ranking)
             __hip_atomic_store(&words[p], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int64_t chunk = p / kChunk, c0 = chunk * kChunk;
