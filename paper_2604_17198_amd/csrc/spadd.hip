@@ -218,8 +218,10 @@ __device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
 // kMapped: the operands are remapped ones (Section 3.3): CSR over the rows all
 // operands store, positions counted over those rows only; the entries of row
 // i' of operand t are read from start[t][i'] on.
+// (second launch bound, wavefronts per SIMD the register budget must allow: the remapped
+// variant is held to the three workgroups per CU that its LDS footprint allows)
 template <int FMT, typename T, int K, bool kMul, bool kMapped>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, kMapped ? 6 : 1)
 spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
              unsigned long long *__restrict__ tile_state, SpaddOut out)
