@@ -66,22 +66,26 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     // move on to the row that holds position q (cur_end <= q < n1).  The rows in between are
     // empty: their rows of C are zero already (the partition kernel wrote them), so they are
     // stepped over however many there are.
+    int win = nrows < RBLK ? nrows : RBLK;             // rows whose pos entries are staged: blk0 .. blk0 + win
     auto advance = [&](int q) {
         ++cur;
-        const int left0 = next_first - blk0;
-        int cnt = left0 < RBLK ? left0 : RBLK;
-        if (spos[cnt] <= q) {                          // beyond the staged window: search pos
-            cur = first_row_past(pos, blk0 + cnt, next_first, q);
-            cnt = 0;                                   // forces a reload below
-        } else {
-            while (spos[cur + 1 - blk0] <= q) ++cur;   // inside the window: at most RBLK cheap steps
+        const int idx = cur + 1 - blk0;
+        if (idx <= win) {
+            const int e = spos[idx];
+            if (e > q) {                               // the next row holds q: the common case
+                cur_end = e < n1 ? e : n1;
+                return;
+            }
         }
-        if (cnt == 0 || cur + 1 - blk0 > RBLK) {       // slide the staged pos window
+        if (spos[win] > q) {
+            while (spos[cur + 1 - blk0] <= q) ++cur;   // inside the window: at most RBLK cheap steps
+        } else {                                       // beyond the staged window: search pos, restage
+            cur = first_row_past(pos, blk0 + win, next_first, q);
             __syncthreads();
             blk0 = cur;
             const int left = next_first - blk0;
-            const int c2 = left < RBLK ? left : RBLK;
-            for (int i = lane; i <= c2; i += NACHO_WAVE) spos[i] = pos[blk0 + i];
+            win = left < RBLK ? left : RBLK;
+            for (int i = lane; i <= win; i += NACHO_WAVE) spos[i] = pos[blk0 + i];
             __syncthreads();
         }
         const int e = spos[cur + 1 - blk0];
