@@ -123,6 +123,9 @@ __device__ inline int pad(int x) { return x + (x >> kPadShift); }
 //   bits 16..19  number of equal keys met in operands with a smaller index (> 0: duplicate)
 //   bits 20..31  sum of the positions this entry found in larger runs (< kTile)
 constexpr int kDupShift = 16, kDirectShift = 20;
+// (the count of equal keys stays below 8: bit 19 is free)
+//   bit  19      DCSR: some other run holds an entry of this entry's row that precedes it in the merged order
+constexpr uint32_t kRowLater = 1u << 19;
 // Word of a merged slot (in the memory of the ranking words, which are dead by then):
 //   bits  0..11  position of the slot's entry in keys      } written when the ranks are known
 //   bit   12     the entry is a duplicate                  }
@@ -147,9 +150,10 @@ struct Tile {
     int32_t soff[NACHO_MAX_OPERANDS + 1];          // start of run t in keys
     uint32_t srun[NACHO_MAX_OPERANDS];             // start of run t | marks summed before it << 16
     uint32_t wave_x[kWaves];                       // per-wavefront partial of a scan across the workgroup
-    uint32_t wave_e[kWaves];                       // per-wavefront number of emitted entries (known after the ranking)
+    uint32_t emit_total;                           // emitted entries | rows started << 16 (known after the ranking)
     unsigned long long wave_cnt[kWaves];           // per-wavefront counts of the assembly (rows << 31 | nnz)
-    unsigned long long base;                       // the partition's offset (rows << 31 | nnz)
+    unsigned long long share_off[kWaves + 1];      // offset of every wavefront's share of the merged order
+                                                   // (rows << 31 | nnz; the last one: end of the partition)
     __device__ T *dups() { return sizeof(T) <= sizeof(KeyT) ? dupval : dupval_wide; }
 };
 
@@ -179,7 +183,11 @@ __device__ inline bool larger_run(int nu, int u, int nt, int t) { return nu > nt
 
 // Ranking of NI consecutive 64-entry blocks of run t, starting at entry r0,
 // against the larger run u: one search per entry.
-template <typename KeyT, int NI, typename TileT>
+// kRows (DCSR): the searches also settle which entry is the first of its row in the merged
+// order.  An entry that finds an entry of its own row right before its place in run u is not;
+// and if the entry of u at its place is u's first of that row, that one is not (unless it is the
+// same coordinate in an operand with a smaller index, which precedes this entry).
+template <typename KeyT, int NI, bool kRows, typename TileT>
 __device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
 {
     const int off_t = uni(w.soff[t]), nt = uni(w.soff[t + 1]) - off_t;
@@ -200,6 +208,13 @@ __device__ inline void rank_blocks(TileT &w, int t, int u, int r0, int lane)
         const int il = r0 + i * NACHO_WAVE + lane;
         const KeyT at = w.keys[off_u + (lb[i] < nu ? lb[i] : nu - 1)];
         const unsigned eq = (lb[i] < nu && at == key[i]) ? 1u : 0u;
+        if (kRows) {
+            const uint32_t rw = row_of(key[i]);
+            const bool row_before = lb[i] > 0 && row_of(w.keys[off_u + lb[i] - 1]) == rw;
+            if (row_before) atomicOr(&w.marks[pad(off_t + il)], kRowLater);
+            else if (lb[i] < nu && row_of(at) == rw && !(eq && u < t))
+                atomicOr(&w.marks[pad(off_u + lb[i])], kRowLater);
+        }
         if (u < t) {
             // run u wins ties: its equal entry precedes this one, which is a duplicate
             if (lb[i] + (int)eq < nu) atomicAdd(&w.marks[pad(off_u + lb[i] + (int)eq)], 1u);
@@ -264,6 +279,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         for (int t = 0; t <= K; ++t) off[t] = 0;
     }
     if (tid == 0) {
+        w.emit_total = 0;
 #pragma unroll
         for (int t = 0; t <= K; ++t) {
             w.soff[t] = off[t];
@@ -298,6 +314,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     }
 
     uint32_t row[D == 2 ? R : 1];
+    unsigned rowfirst = 0;                     // bit j: entry tid * R + j is the first of its row in its run
     if (D == 2) {
         // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
         // (word of the entry in marks), then hand every entry the latest marker
@@ -346,6 +363,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             for (int j = 0; j < R; ++j) {
                 v[j] = w.marks[at + j];
                 cur = v[j] ? v[j] : cur;
+                if (FMT == SPADD_DCSR && v[j]) rowfirst |= 1u << j;
             }
             uint32_t incl = cur;                      // latest marker up to the end of this thread's words
 #pragma unroll
@@ -401,6 +419,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     }
 
     // ---- 2. ranks: slot of every entry in the merged order -----------------------
+    bool cont = false;                     // the partition starts inside a row whose head is elsewhere
+    if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
     for (int i = tid; i < kPadded; i += kThreads) w.marks[i] = 0;
     __syncthreads();
     int n_max = 0, t_max = 0;                  // the largest run searches nothing
@@ -422,9 +442,9 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 // a long run is searched four blocks at a time (the chains of LDS reads
                 // overlap), a short one block by block (more wavefronts share it)
                 for (; nt > 8 * NACHO_WAVE && r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE, ++unit)
-                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4>(w, t, u, r0, lane);
+                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4, FMT == SPADD_DCSR>(w, t, u, r0, lane);
                 for (; r0 < nt; r0 += NACHO_WAVE, ++unit)
-                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1>(w, t, u, r0, lane);
+                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1, FMT == SPADD_DCSR>(w, t, u, r0, lane);
             }
         }
     }
@@ -441,24 +461,28 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             sum += (int)(v[j] & 0xffffu);
             // entry tid * R + j is emitted when no operand before its own stores its key
             // (kMul: when all k - 1 operands before its own do)
-            const int met = (int)((v[j] >> kDupShift) & 0xfu);
-            if (tid * R + j < n) emitted += (kMul ? met == k - 1 : met == 0) ? 1 : 0;
+            const int met = (int)((v[j] >> kDupShift) & 0x7u);
+            const bool out_entry = tid * R + j < n && (kMul ? met == k - 1 : met == 0);
+            // (counted over the wavefront with ballots: no vector registers at this crowded point)
+            emitted += __popcll(__ballot(out_entry));
+            // DCSR: a row of the output starts at the emitted entry that is the first of its row in
+            // its own run and has no entry of that row before it in any other run
+            if (FMT == SPADD_DCSR)
+                emitted += __popcll(__ballot(out_entry && ((rowfirst >> j) & 1u) && !(v[j] & kRowLater))) << 16;
         }
         const int incl = wave_inclusive_scan(sum);
         if (lane == NACHO_WAVE - 1) w.wave_x[wave] = (uint32_t)incl;
-        if (FMT != SPADD_DCSR) {
-            emitted = wave_sum<int>(emitted);
-            if (lane == 0) w.wave_e[wave] = (uint32_t)emitted;
-        }
+        if (lane == 0) atomicAdd(&w.emit_total, (uint32_t)emitted);    // both counts stay below 2^13
         __syncthreads();
-        if (FMT != SPADD_DCSR && tid == 0) {
-            // The partition's output count is known here, long before its offset is needed:
-            // published now, the workgroups after this one rarely find it missing.
-            unsigned e = 0;
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) e += w.wave_e[ww];
+        if (tid == 0) {
+            // The partition's output counts are known here, long before its offset is needed:
+            // published now, the workgroups after this one rarely find them missing.
+            const unsigned e = w.emit_total;
+            unsigned e_rows = e >> 16;
+            if (FMT == SPADD_DCSR && n > 0 && cont) e_rows -= 1;      // the first row's head is elsewhere
             unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);
-            __hip_atomic_store(&words[p], kWordValid | e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&words[p], kWordValid | (e_rows << 14) | (e & 0xffffu), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         }
         int run = incl - sum;
 #pragma unroll
@@ -483,7 +507,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const uint32_t mk = w.marks[pad(c)];
         const uint32_t sr = w.srun[tr[r]];
         const int m = (c - (int)(sr & 0xffffu)) + (int)(mk >> kDirectShift) + ((int)(mk & 0xffffu) - (int)(sr >> 16));
-        const int dup = ((mk >> kDupShift) & 0xfu) ? 0x8000 : 0;
+        const int dup = ((mk >> kDupShift) & 0x7u) ? 0x8000 : 0;
         slot[r] = m | dup;
     }
     __syncthreads();                           // all ranking words are read: the assembly may overwrite them
@@ -497,8 +521,6 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // ---- 3. assembly: heads and row heads before every merged slot ------------------
     // wavefront v walks the slots v * kShare .. (v + 1) * kShare - 1; the counts in
     // the words are relative to the start of that share
-    bool cont = false;                     // the partition starts inside a row whose head is elsewhere
-    if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
     int heads = 0, rheads = 0;
 #pragma unroll
     for (int b = 0; b < kShare / NACHO_WAVE; ++b) {
@@ -553,9 +575,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const long long t_nnz = (long long)(tot & 0x7fffffffull), t_rows = (long long)((tot >> 31) & 0x7fffffffull);
         unsigned long long *totals = tile_state;                                        // one per chunk
         unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
-        if (FMT == SPADD_DCSR && lane == 0)       // (the other formats published after the ranking)
-            __hip_atomic_store(&words[p], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz,
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // (the workgroup's own word was published after the ranking)
         const int64_t chunk = p / kChunk, c0 = chunk * kChunk;
         {
             // words of the workgroups before this one in its chunk, all loads in flight together
@@ -612,7 +632,13 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             b_rows += c_rows;
         }
         if (lane == 0) {
-            w.base = pack_counts(b_rows, b_nnz);
+            unsigned long long at = pack_counts(b_rows, b_nnz);
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                w.share_off[ww] = at;
+                at += w.wave_cnt[ww];
+            }
+            w.share_off[kWaves] = at;
             if (gave_up) *out.status = NACHO_ERR_HIP;
             if (broken) *out.status = NACHO_ERR_INVALID_ARG;
             if (p == P - 1) {
@@ -635,16 +661,6 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         }
     }
     __syncthreads();
-    // offsets of the wavefronts' shares of the merged order
-    long long share_nnz[kWaves + 1], share_rows[kWaves + 1];
-    share_nnz[0] = (long long)(w.base & 0x7fffffffull);
-    share_rows[0] = (long long)((w.base >> 31) & 0x7fffffffull);
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) {
-        share_nnz[ww + 1] = share_nnz[ww] + (long long)(w.wave_cnt[ww] & 0x7fffffffull);
-        share_rows[ww + 1] = share_rows[ww] + (long long)((w.wave_cnt[ww] >> 31) & 0x7fffffffull);
-    }
-
     // ---- 5. compute: write the partition's output ------------------------------
     if (FMT == SPADD_CSR) {
         // pos of every row that starts inside this partition: offset of the first
@@ -657,17 +673,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 const int m = (l + h) >> 1;
                 if (row_of(keys[slotw[m] & kSlotPos]) < (uint32_t)rr) l = m + 1; else h = m;
             }
-            long long at = share_nnz[kWaves];              // past the last entry of the partition
-            if (l < n) {
-                at = (long long)((slotw[l] >> kSlotHeads) & 0x1ffu);
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww)
-                    if (l / kShare == ww) at += share_nnz[ww];
-            }
+            long long at = (long long)(w.share_off[kWaves] & 0x7fffffffull);   // past the partition's last entry
+            if (l < n)
+                at = (long long)((slotw[l] >> kSlotHeads) & 0x1ffu) +
+                     (long long)(w.share_off[l / kShare] & 0x7fffffffull);
             out.pos1[rr] = (int32_t)at;
         }
-        __syncthreads();                       // keys are read: the duplicates' values may overwrite them
     }
+    // columns (and rows) come back from the keys: not held in registers through the stages above
+    int colr[R];
+    uint32_t rowr[D == 2 ? R : 1];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = r * kThreads + tid;
+        const KeyT key = c < n ? keys[c] : KeyT(0);
+        colr[r] = (int)(uint32_t)key;
+        if (D == 2) rowr[r] = row_of(key);
+    }
+    if (sizeof(T) <= sizeof(KeyT)) __syncthreads();   // keys are read: the duplicates' values may overwrite them
     T *dv = w.dups();
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -693,17 +716,16 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 if (more) sum += dv[m + g];
             }
         }
-        long long wpos = (long long)((word >> kSlotHeads) & 0x1ffu), wr = (long long)((word >> kSlotRows) & 0x1ffu);
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww)
-            if (m / kShare == ww) { wpos += share_nnz[ww]; wr += share_rows[ww]; }
+        const unsigned long long so = w.share_off[m / kShare];
+        const long long wpos = (long long)((word >> kSlotHeads) & 0x1ffu) + (long long)(so & 0x7fffffffull);
+        const long long wr = (long long)((word >> kSlotRows) & 0x1ffu) + (long long)((so >> 31) & 0x7fffffffull);
         if (wpos < out.cap_nnz) {
-            out.crd1[wpos] = col[r];
+            out.crd1[wpos] = colr[r];
             static_cast<T *>(out.val)[wpos] = sum;
         }
         if (FMT == SPADD_DCSR && (word & kSlotEmit)) {
             if (wr < out.cap_rows) {
-                out.crd0[wr] = (int32_t)row[r];
+                out.crd0[wr] = (int32_t)rowr[r];
                 out.pos1[wr] = (int32_t)wpos;
             }
         }
