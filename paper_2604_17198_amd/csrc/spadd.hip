@@ -521,6 +521,21 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // ---- 3. assembly: heads and row heads before every merged slot ------------------
     // wavefront v walks the slots v * kShare .. (v + 1) * kShare - 1; the counts in
     // the words are relative to the start of that share
+    // Wavefront 0 asks for the counts of the workgroups before this one in its chunk already
+    // now: they were published long ago as a rule, and the answer travels during the assembly.
+    unsigned early[kChunk / NACHO_WAVE];
+    {
+        const unsigned int *words = reinterpret_cast<const unsigned int *>(tile_state + n_chunks);
+        const int64_t c0 = (p / kChunk) * kChunk;
+        const int m = (int)(p - c0);
+#pragma unroll
+        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+            const int j = i * NACHO_WAVE + lane;
+            early[i] = kWordValid;
+            if (wave == 0 && i * NACHO_WAVE < m && j < m)
+                early[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     int heads = 0, rheads = 0;
 #pragma unroll
     for (int b = 0; b < kShare / NACHO_WAVE; ++b) {
@@ -581,14 +596,14 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             // words of the workgroups before this one in its chunk, all loads in flight together
             const int m = (int)(p - c0);
             int spins = 0;
-            for (;;) {
+            for (bool first = true;; first = false) {
                 unsigned v[kChunk / NACHO_WAVE];
                 bool missing = false;
 #pragma unroll
                 for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
                     const int j = i * NACHO_WAVE + lane;
-                    v[i] = kWordValid;
-                    if (i * NACHO_WAVE < m && j < m)
+                    v[i] = first ? early[i] : kWordValid;
+                    if (!first && i * NACHO_WAVE < m && j < m)
                         v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 int l_nnz = 0, l_rows = 0;
