@@ -179,6 +179,11 @@ def bench_others(steps, warmup):
                     "GBps_algorithmic": nbytes / ms / 1e6,
                     "frac_of_hbm_peak": nbytes / ms / 1e6 / PEAK_HBM_GBS,
                     "kernel_ms": _kernel_ms(fn, 5)}
+        # measured HBM bytes per launch of the call's kernels, where a rocprofv3 measurement is committed
+        tr = {k: _traffic(k, tag) for k in res[tag]["kernel_ms"]}
+        tr = {k: v for k, v in tr.items() if v is not None}
+        if tr:
+            res[tag]["traffic"] = tr
         if table is not None:
             # work per partition from the table the fused call stored in its workspace (a partition is
             # executed by one wavefront (SpMM) or dealt out evenly over the 8 wavefronts of a workgroup (SpAdd))
