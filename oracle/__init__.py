@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "nacho_oracle.c")
 _LIB = os.path.join(_HERE, "libnacho_oracle.so")
 
-DENSE, COMPRESSED = 0, 1
+DENSE, COMPRESSED, NONUNIQUE, SINGLETON = 0, 1, 2, 3
 MAXL = 3
 
 
@@ -54,6 +54,8 @@ def lib():
         _lib.ora_spadd_csr.restype = C.c_int64
         _lib.ora_spmul_vec.restype = C.c_int64
         _lib.ora_spmul_csr.restype = C.c_int64
+        _lib.ora_spadd_coo.restype = C.c_int64
+        _lib.ora_spmul_coo.restype = C.c_int64
     return _lib
 
 
@@ -75,10 +77,17 @@ class Tensor:
                 t.lvl[m].kind, t.lvl[m].extent = DENSE, int(l[1])
                 t.lvl[m].pos = None
                 t.lvl[m].crd = None
+            elif l[0] == "singleton":
+                crd = _i32(l[2])
+                self._keep += [crd]
+                t.lvl[m].kind, t.lvl[m].extent = SINGLETON, int(l[1])
+                t.lvl[m].pos = None
+                t.lvl[m].crd = crd.ctypes.data
             else:
                 pos, crd = _i32(l[2]), _i32(l[3])
                 self._keep += [pos, crd]
-                t.lvl[m].kind, t.lvl[m].extent = COMPRESSED, int(l[1])
+                t.lvl[m].kind = NONUNIQUE if l[0] == "nonunique" else COMPRESSED
+                t.lvl[m].extent = int(l[1])
                 t.lvl[m].pos = pos.ctypes.data
                 t.lvl[m].crd = crd.ctypes.data
         self.c = t
@@ -96,6 +105,13 @@ def csr(pos, crd, n_rows, n_cols):
 
 def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols):
     return Tensor([("compressed", n_rows, pos0, crd0), ("compressed", n_cols, pos1, crd1)])
+
+
+def coo(rows, cols, n_rows, n_cols):
+    """Coordinate list sorted by (row, col): a non-unique compressed row level over a singleton column level."""
+    rows = _i32(rows)
+    return Tensor([("nonunique", n_rows, np.array([0, rows.shape[0]], dtype=np.int32), rows),
+                   ("singleton", n_cols, cols)])
 
 
 def _pack(ops):
@@ -374,3 +390,31 @@ def recursive_partition_dcsr(mats, n_cols, P, queries=None):
         raise ValueError("ora_recursive_partition_dcsr rejected its arguments")
     return {"rows": rows[:M].copy(), "rpos": rpos[:, :M].copy(), "T": T[:M].copy(), "Tprime": Tprime,
             "coord": coord, "lpos": lpos, "before": before, "cost": cost}
+
+
+def _coo_combine(fn, mats, cap):
+    k = len(mats)
+    rows = [_i32(m["row"]) for m in mats]
+    cols = [_i32(m["col"]) for m in mats]
+    vals, is64 = _vals([m["val"] for m in mats])
+    nnz = np.array([r.shape[0] for r in rows], dtype=np.int64)
+    o_r = np.empty(cap, dtype=np.int32)
+    o_c = np.empty(cap, dtype=np.int32)
+    o_v = np.empty(cap, dtype=np.float64)
+    o_a = np.empty(cap, dtype=np.float64)
+    n = fn(k, _ptr_array(rows), _ptr_array(cols), _ptr_array(vals), nnz.ctypes.data_as(C.c_void_p), is64,
+           o_r.ctypes.data_as(C.c_void_p), o_c.ctypes.data_as(C.c_void_p), o_v.ctypes.data_as(C.c_void_p),
+           o_a.ctypes.data_as(C.c_void_p))
+    if n < 0:
+        raise ValueError("the COO oracle rejected its arguments")
+    return {"row": o_r[:n].copy(), "col": o_c[:n].copy(), "val": o_v[:n].copy(), "abs": o_a[:n].copy()}
+
+
+def spadd_coo(mats):
+    """Union add of k COO matrices given as dicts(row, col, val) sorted by (row, col)."""
+    return _coo_combine(lib().ora_spadd_coo, mats, max(1, sum(len(m["row"]) for m in mats)))
+
+
+def spmul_coo(mats):
+    """Hadamard product of k COO matrices given as dicts(row, col, val) sorted by (row, col)."""
+    return _coo_combine(lib().ora_spmul_coo, mats, max(1, min(len(m["row"]) for m in mats)))

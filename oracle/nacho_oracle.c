@@ -29,6 +29,8 @@
  *        stored coordinates, each with the product (in operand order) of the
  *        k values; the k-finger loop of Section 2.1 as printed ("all operands
  *        match"), for sparse vectors and for the columns of every CSR row.
+ *        Coordinate lists (COO: a non-unique compressed level over a Singleton
+ *        level, Section 4.2.1) coiterate coordinate pairs in the same two loops.
  *
  * Precision: products and sums are accumulated wider than the GPU's working
  * type (long double for the fp64 kernels, double for the fp32 kernels) and the
@@ -56,6 +58,14 @@
 
 #define ORA_DENSE 0
 #define ORA_COMPRESSED 1
+/* The two levels of a coordinate-list (COO) matrix in the level-format vocabulary of
+ * Section 4.2.1 (Dense, Compressed, Singleton):
+ *   NONUNIQUE  a Compressed level whose sorted coordinates may repeat (one entry per
+ *              stored non-zero; pos = {0, nnz} at the top);
+ *   SINGLETON  exactly one coordinate per position of the level above: position p of
+ *              the level above has the single child position p with coordinate crd[p]. */
+#define ORA_NONUNIQUE 2
+#define ORA_SINGLETON 3
 #define ORA_MAXL 3
 #define ORA_MAXK 16
 
@@ -78,7 +88,8 @@ typedef struct {
 static int64_t child_begin(const ora_tensor *T, int m, int64_t p)
 {
     const ora_level *c = &T->lvl[m + 1];
-    return c->kind == ORA_COMPRESSED ? (int64_t)c->pos[p] : p * c->extent;
+    if (c->kind == ORA_SINGLETON) return p;
+    return (c->kind == ORA_COMPRESSED || c->kind == ORA_NONUNIQUE) ? (int64_t)c->pos[p] : p * c->extent;
 }
 
 /* Number of innermost (leaf) positions that precede every leaf below level-m
@@ -92,7 +103,7 @@ static int64_t leaf_begin(const ora_tensor *T, int m, int64_t p)
 static void root_segment(const ora_tensor *T, int64_t *lo, int64_t *hi)
 {
     const ora_level *l = &T->lvl[0];
-    if (l->kind == ORA_COMPRESSED) { *lo = l->pos[0]; *hi = l->pos[1]; }
+    if (l->kind == ORA_COMPRESSED || l->kind == ORA_NONUNIQUE) { *lo = l->pos[0]; *hi = l->pos[1]; }
     else { *lo = 0; *hi = l->extent; }
 }
 
@@ -111,7 +122,7 @@ static int64_t lower_bound(const int32_t *crd, int64_t lo, int64_t hi, int64_t x
 static int64_t locate(const ora_tensor *T, int m, int64_t lo, int64_t hi, int64_t x)
 {
     const ora_level *l = &T->lvl[m];
-    if (l->kind == ORA_COMPRESSED) return lower_bound(l->crd, lo, hi, x);
+    if (l->kind != ORA_DENSE) return lower_bound(l->crd, lo, hi, x);   /* every sparse kind is sorted */
     (void)hi;
     return lo + x;
 }
@@ -178,13 +189,16 @@ int ora_find_partition(const ora_tensor *ops, int k, int d, int64_t tail_extent,
             const ora_tensor *T = &ops[t];
             int64_t p = locate(T, m, lo[t], hi[t], xm);
             posn[(size_t)t * d + m] = p;
-            if (T->lvl[m].kind == ORA_COMPRESSED)
+            if (T->lvl[m].kind != ORA_DENSE)
                 present[t] = (p < hi[t] && (int64_t)T->lvl[m].crd[p] == xm);
             else
                 present[t] = (xm < N);
             if (m + 1 < d) {                      /* descend into x_m's children   */
+                /* the positions that hold coordinate x_m: one, or (NONUNIQUE) all its repeats */
+                int64_t p_end = present[t] ? p + 1 : p;
+                if (T->lvl[m].kind == ORA_NONUNIQUE) p_end = lower_bound(T->lvl[m].crd, p, hi[t], xm + 1);
                 lo[t] = child_begin(T, m, p);
-                hi[t] = present[t] ? child_begin(T, m, p + 1) : lo[t];
+                hi[t] = child_begin(T, m, p_end);
             }
         }
     }
@@ -701,4 +715,63 @@ int ora_recursive_partition_dcsr(int k, const int32_t *const *pos1, const int32_
     }
     free(rows_before);
     return 0;
+}
+
+
+/* ---- coordinate-list (COO) matrices ---------------------------------------- */
+
+/* Union add / intersection multiply of k COO matrices (rows[t], cols[t] sorted by (row, col),
+ * no repeated pair): the k-finger coiteration of Section 2.1 over coordinate PAIRS, "any" for the
+ * sum and "all" for the product, values combined in operand order.  Outputs hold sum_t nnz_t
+ * (add) or min_t nnz_t (multiply) entries; returns the number written. */
+static int64_t coo_merge(int multiply, int k, const int32_t *const *rows, const int32_t *const *cols,
+                         const void *const *val, const int64_t *nnz, int is_f64,
+                         int32_t *out_row, int32_t *out_col, double *out_val, double *out_abs)
+{
+    int64_t p[ORA_MAXK], n_out = 0;
+    if (k < 1 || k > ORA_MAXK) return -1;
+    for (int t = 0; t < k; ++t) p[t] = 0;
+    for (;;) {
+        int any = 0, all = 1;
+        int64_t bi = 0, bj = 0;
+        for (int t = 0; t < k; ++t) {
+            if (p[t] >= nnz[t]) { all = 0; continue; }
+            int64_t i = rows[t][p[t]], j = cols[t][p[t]];
+            if (!any || i < bi || (i == bi && j < bj)) { bi = i; bj = j; }
+            any = 1;
+        }
+        if (!any || (multiply && !all)) break;      /* a product ends with its first exhausted operand */
+        double acc = multiply ? 1.0 : 0.0, sabs = 0.0;
+        int holders = 0;
+        for (int t = 0; t < k; ++t)
+            if (p[t] < nnz[t] && rows[t][p[t]] == bi && cols[t][p[t]] == bj) {
+                double v = load_value(val[t], is_f64, p[t]);
+                if (multiply) acc *= v; else { acc += v; sabs += fabs(v); }
+                ++holders;
+            }
+        if (!multiply || holders == k) {
+            out_row[n_out] = (int32_t)bi;
+            out_col[n_out] = (int32_t)bj;
+            out_val[n_out] = acc;
+            if (out_abs) out_abs[n_out] = multiply ? fabs(acc) : sabs;
+            ++n_out;
+        }
+        for (int t = 0; t < k; ++t)
+            if (p[t] < nnz[t] && rows[t][p[t]] == bi && cols[t][p[t]] == bj) ++p[t];
+    }
+    return n_out;
+}
+
+int64_t ora_spadd_coo(int k, const int32_t *const *rows, const int32_t *const *cols,
+                      const void *const *val, const int64_t *nnz, int is_f64,
+                      int32_t *out_row, int32_t *out_col, double *out_val, double *out_abs)
+{
+    return coo_merge(0, k, rows, cols, val, nnz, is_f64, out_row, out_col, out_val, out_abs);
+}
+
+int64_t ora_spmul_coo(int k, const int32_t *const *rows, const int32_t *const *cols,
+                      const void *const *val, const int64_t *nnz, int is_f64,
+                      int32_t *out_row, int32_t *out_col, double *out_val, double *out_abs)
+{
+    return coo_merge(1, k, rows, cols, val, nnz, is_f64, out_row, out_col, out_val, out_abs);
 }

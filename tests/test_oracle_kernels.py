@@ -225,3 +225,53 @@ def test_spmul_csr_vs_scipy_medium():
     ref.sort_indices()
     assert out["pos"].tolist() == ref.indptr.tolist() and out["crd"].tolist() == ref.indices.tolist()
     assert np.allclose(out["val"], ref.data, rtol=1e-14, atol=0) and out["crd"].shape[0] > 1000
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_coo_add_and_multiply_vs_dense_and_scipy(k):
+    rng = np.random.default_rng(40 + k)
+    shape = (31, 23)
+    for trial in range(10):
+        mats, dense_sum, dense_prod = [], np.zeros(shape), np.ones(shape)
+        any_mask, all_mask = np.zeros(shape, bool), np.ones(shape, bool)
+        sp_sum = sp.csr_matrix(shape)
+        for t in range(k):
+            c = random_coords(rng, shape, int(rng.integers(0, 400)))
+            v = rng.uniform(0.5, 1.5, c.shape[0]) * rng.choice([-1, 1], c.shape[0])
+            mats.append({"row": c[:, 0].astype(np.int32), "col": c[:, 1].astype(np.int32), "val": v})
+            d = np.zeros(shape)
+            d[c[:, 0], c[:, 1]] = v
+            m = np.zeros(shape, bool)
+            m[c[:, 0], c[:, 1]] = True
+            dense_sum += d
+            dense_prod *= d
+            any_mask |= m
+            all_mask &= m
+            sp_sum = sp_sum + sp.csr_matrix((v, (c[:, 0], c[:, 1])), shape=shape)
+        z = oracle.spadd_coo(mats)
+        ii, jj = np.nonzero(any_mask)                     # row-major order = sorted by (row, col)
+        assert z["row"].tolist() == ii.tolist() and z["col"].tolist() == jj.tolist()
+        np.testing.assert_allclose(z["val"], dense_sum[ii, jj], rtol=1e-12, atol=1e-15)
+        zs = sp_sum.tocoo()
+        np.testing.assert_allclose(sp.csr_matrix((z["val"], (z["row"], z["col"])), shape=shape).toarray(),
+                                   zs.toarray(), rtol=1e-12, atol=1e-15)
+        y = oracle.spmul_coo(mats)
+        ii, jj = np.nonzero(all_mask)
+        assert y["row"].tolist() == ii.tolist() and y["col"].tolist() == jj.tolist()
+        np.testing.assert_allclose(y["val"], dense_prod[ii, jj], rtol=1e-12)
+
+
+def test_coo_results_equal_dcsr_results():
+    rng = np.random.default_rng(44)
+    shape = (200, 150)
+    cs = [random_coords(rng, shape, 6000) for _ in range(3)]
+    vs = [rng.standard_normal(c.shape[0]) for c in cs]
+    coo = [{"row": c[:, 0].astype(np.int32), "col": c[:, 1].astype(np.int32), "val": v} for c, v in zip(cs, vs)]
+    dc = []
+    for c, v in zip(cs, vs):
+        p0, c0, p1, c1 = to_dcsr(c)
+        dc.append({"pos0": p0, "crd0": c0, "pos1": p1, "crd1": c1, "val": v})
+    for f_coo, f_dcsr in ((oracle.spadd_coo, oracle.spadd_dcsr), (oracle.spmul_coo, oracle.spmul_dcsr)):
+        a, b = f_coo(coo), f_dcsr(dc)
+        assert np.array_equal(a["col"], b["crd1"]) and np.array_equal(a["val"], b["val"])
+        assert np.array_equal(a["row"], np.repeat(b["crd0"], np.diff(b["pos1"])))

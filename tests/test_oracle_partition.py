@@ -101,6 +101,8 @@ def _make(fmt, coords, shape):
         return oracle.csr(pos, crd, shape[0], shape[1])
     if fmt == "dcsr":
         return oracle.dcsr(*to_dcsr(coords), shape[0], shape[1])
+    if fmt == "coo":
+        return oracle.coo(coords[:, 0].astype(np.int32), coords[:, 1].astype(np.int32), shape[0], shape[1])
     if fmt == "csf3":
         p0, c0, p1, c1, p2, c2 = to_csf3(coords)
         return oracle.Tensor([("compressed", shape[0], p0, c0), ("compressed", shape[1], p1, c1),
@@ -121,12 +123,14 @@ def _brute_boundary(fmt, coord_lists, shape, Q):
         for m in range(d):
             if fmt == "csr" and m == 0:
                 posn[t, m] = x[0]                     # dense level: position == coordinate
+            elif fmt == "coo" and m == 0:
+                posn[t, m] = sum(1 for c in cl if int(c[0]) < x[0])   # one level-0 entry per non-zero
             else:
                 posn[t, m] = count_prefix_less(cl, m, x)
     return x, posn, cost
 
 
-CASES = [("vec", (40,)), ("csr", (7, 9)), ("dcsr", (9, 7)), ("csf3", (4, 5, 6))]
+CASES = [("vec", (40,)), ("csr", (7, 9)), ("dcsr", (9, 7)), ("coo", (9, 7)), ("csf3", (4, 5, 6))]
 
 
 @pytest.mark.parametrize("fmt,shape", CASES)
@@ -313,3 +317,35 @@ def test_cost_is_monotone_and_hierarchically_consistent():
     for Q in range(len(merged)):
         coord, _, cost = oracle.find_partition(ops, Q)
         assert cost == C(coord.tolist())
+
+
+def test_coo_boundaries_equal_dcsr_boundaries():
+    """A coordinate list and the DCSR form of the same matrices: same boundary coordinates, same
+    positions of the non-zeros, same costs (only the row-level positions mean different things:
+    stored rows before the boundary row vs non-zeros before it)."""
+    rng = np.random.default_rng(321)
+    shape = (60, 45)
+    for trial in range(10):
+        k = int(rng.integers(1, 5))
+        cs = [random_coords(rng, shape, int(rng.integers(0, 900))) for _ in range(k)]
+        coo = [_make("coo", c, shape) for c in cs]
+        dcsr = [_make("dcsr", c, shape) for c in cs]
+        for P in (1, 3, 16, 250):
+            a, b = oracle.partition(coo, P), oracle.partition(dcsr, P)
+            assert np.array_equal(a["coord"], b["coord"])
+            assert np.array_equal(a["cost"], b["cost"])
+            assert np.array_equal(a["posn"][:, :, 1], b["posn"][:, :, 1])
+            for t, c in enumerate(cs):
+                starts = np.searchsorted(c[:, 0], a["coord"][:, 0], side="left")
+                assert np.array_equal(a["posn"][:, t, 0], starts)
+
+
+def test_fig3a_as_coordinate_lists(golden_dir):
+    g = _load(golden_dir, "fig3a_dcsr_add_partition.json")
+    ops = [oracle.coo([c[0] for c in g[key]], [c[1] for c in g[key]], g["n_rows"], g["n_cols"]) for key in ("A", "B")]
+    parts = oracle.partition(ops, g["P"])
+    assert np.diff(parts["cost"]).tolist() == [6, 6, 6, 6]
+    for t, key in enumerate(("A_membership", "B_membership")):
+        counts = np.bincount(g[key], minlength=g["P"])
+        assert parts["posn"][:, t, 1].tolist() == [0] + np.cumsum(counts).tolist()
+    assert parts["coord"][1:-1].tolist() == [[0, 5], [2, 6], [3, 4]]
