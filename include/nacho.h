@@ -54,7 +54,7 @@ typedef enum {
 } nacho_status;
 
 typedef enum { NACHO_F32 = 0, NACHO_F64 = 1 } nacho_dtype;
-typedef enum { NACHO_DENSE = 0, NACHO_COMPRESSED = 1 } nacho_level_kind;
+typedef enum { NACHO_DENSE = 0, NACHO_COMPRESSED = 1, NACHO_NONUNIQUE = 2, NACHO_SINGLETON = 3 } nacho_level_kind;
 typedef enum {
     NACHO_OP_PARTITION = 0, NACHO_OP_SPMV = 1, NACHO_OP_SPMM = 2, NACHO_OP_SPADD = 3, NACHO_OP_SPMUL = 4
 } nacho_op;
@@ -66,7 +66,12 @@ typedef enum {
  *   DENSE:      every coordinate in [0, extent) is present; pos, crd are NULL.
  *   COMPRESSED: pos[parent] .. pos[parent+1] delimit the sorted coordinates
  *               crd[] stored below `parent` (a top level has one parent, so
- *               pos has 2 entries).  `count` is the number of entries of crd. */
+ *               pos has 2 entries).  `count` is the number of entries of crd.
+ *   NONUNIQUE:  a top compressed level whose sorted coordinates may repeat, one
+ *               entry per stored non-zero (the row level of a coordinate list);
+ *               crd[count]; pos is not read.
+ *   SINGLETON:  one coordinate per entry of the level above: crd[count], the
+ *               same count (the column level of a coordinate list).            */
 typedef struct {
     int32_t kind;       /* nacho_level_kind                                    */
     int64_t extent;     /* N_m, at most 2^31 - 1                               */
@@ -79,6 +84,9 @@ typedef struct {
  *   sparse vector  nlevels = 1  {COMPRESSED}
  *   CSR            nlevels = 2  {DENSE, COMPRESSED}
  *   DCSR           nlevels = 2  {COMPRESSED, COMPRESSED}
+ *   COO            nlevels = 2  {NONUNIQUE, SINGLETON}: entries sorted by (row,
+ *                  column), no pair twice (nacho_partition, nacho_spadd_k,
+ *                  nacho_spmul_k)
  * `val` (device, one value per innermost coordinate) may be NULL for
  * nacho_partition. */
 typedef struct {
@@ -107,6 +115,8 @@ typedef struct {
  *   vector: crd1[cap_nnz], val[cap_nnz]; pos1[2] = {0, nnz}
  *   CSR:    pos1[n_rows+1], crd1[cap_nnz], val[cap_nnz]
  *   DCSR:   pos0[2] = {0, rows}, crd0[cap_rows], pos1[cap_rows+1], crd1, val
+ *   COO:    crd0[cap_nnz] (rows), crd1[cap_nnz] (columns), val[cap_nnz];
+ *           pos1[2] = {0, nnz}; cap_rows is not used
  * counts[0] = stored rows (DCSR; n_rows for CSR; 1 for a vector), counts[1] =
  * nnz.  *status is set to NACHO_OK, or to NACHO_ERR_CAPACITY when cap_rows or
  * cap_nnz is too small (then nothing is written beyond the capacities; counts

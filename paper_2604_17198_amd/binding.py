@@ -18,7 +18,7 @@ import torch
 from . import build as _build
 
 F32, F64 = 0, 1
-DENSE, COMPRESSED = 0, 1
+DENSE, COMPRESSED, NONUNIQUE, SINGLETON = 0, 1, 2, 3
 OP_PARTITION, OP_SPMV, OP_SPMM, OP_SPADD, OP_SPMUL = 0, 1, 2, 3, 4
 MAX_OPERANDS, MAX_LEVELS = 8, 2
 
@@ -130,6 +130,14 @@ class Operand:
                 c.lvl[m].pos = None
                 c.lvl[m].crd = None
                 c.lvl[m].count = 0
+            elif l["kind"] in ("nonunique", "singleton"):
+                crd = l["crd"]
+                assert crd.dtype == torch.int32
+                self.keep.append(crd)
+                c.lvl[m].kind = NONUNIQUE if l["kind"] == "nonunique" else SINGLETON
+                c.lvl[m].pos = None
+                c.lvl[m].crd = crd.data_ptr() if crd.numel() else None
+                c.lvl[m].count = int(crd.numel())
             else:
                 pos, crd = l["pos"], l["crd"]
                 assert pos.dtype == torch.int32 and crd.dtype == torch.int32
@@ -160,6 +168,12 @@ def csr(pos, crd, n_rows, n_cols, val=None):
 def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols, val=None):
     return Operand([{"kind": "compressed", "extent": n_rows, "pos": pos0, "crd": crd0},
                     {"kind": "compressed", "extent": n_cols, "pos": pos1, "crd": crd1}], val)
+
+
+def coo(rows, cols, n_rows, n_cols, val=None):
+    """Coordinate list sorted by (row, column), no pair twice."""
+    return Operand([{"kind": "nonunique", "extent": n_rows, "crd": rows},
+                    {"kind": "singleton", "extent": n_cols, "crd": cols}], val)
 
 
 def _pack(ops):
@@ -265,8 +279,12 @@ class SparseOut:
         i32 = dict(dtype=torch.int32, device=device)
         self.fmt = fmt
         self.pos0 = torch.zeros(2, **i32) if fmt == "dcsr" else None
-        self.crd0 = torch.empty(max(cap_rows, 1), **i32) if fmt == "dcsr" else None
-        n_pos1 = {"vector": 2, "csr": n_rows + 1, "dcsr": cap_rows + 1}[fmt]
+        self.crd0 = None
+        if fmt == "dcsr":
+            self.crd0 = torch.empty(max(cap_rows, 1), **i32)
+        elif fmt == "coo":
+            self.crd0 = torch.empty(max(cap_nnz, 1), **i32)      # the rows of the result's entries
+        n_pos1 = {"vector": 2, "coo": 2, "csr": n_rows + 1, "dcsr": cap_rows + 1}[fmt]
         self.pos1 = torch.zeros(n_pos1, **i32)
         self.crd1 = torch.empty(max(cap_nnz, 1), **i32)
         self.val = torch.empty(max(cap_nnz, 1), dtype=dtype, device=device)

@@ -42,7 +42,7 @@ using namespace nacho_host;
 
 namespace {
 
-enum Format { FMT_BAD = 0, FMT_VECTOR, FMT_CSR, FMT_DCSR };
+enum Format { FMT_BAD = 0, FMT_VECTOR, FMT_CSR, FMT_DCSR, FMT_COO };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -51,6 +51,7 @@ Format tensor_format(const nacho_tensor &t)
     if (t.nlevels == 1 && t.lvl[0].kind == NACHO_COMPRESSED) return FMT_VECTOR;
     if (t.nlevels == 2 && t.lvl[0].kind == NACHO_DENSE && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_CSR;
     if (t.nlevels == 2 && t.lvl[0].kind == NACHO_COMPRESSED && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_DCSR;
+    if (t.nlevels == 2 && t.lvl[0].kind == NACHO_NONUNIQUE && t.lvl[1].kind == NACHO_SINGLETON) return FMT_COO;
     return FMT_BAD;
 }
 
@@ -76,7 +77,14 @@ int32_t check_operands(const nacho_tensor *ops, int32_t k, bool need_arrays, Dev
             DevLevel &D = dev->lvl[t][m];
             D.kind = L.kind;
             D.extent = L.extent;
-            if (L.kind == NACHO_COMPRESSED) {
+            if (L.kind == NACHO_NONUNIQUE || L.kind == NACHO_SINGLETON) {
+                // a coordinate list: one row and one column coordinate per stored non-zero
+                if (L.count < 0 || L.count > 0x7fffffffLL || L.count != ops[t].lvl[0].count)
+                    return NACHO_ERR_INVALID_ARG;
+                if (need_arrays && L.count > 0 && (!L.crd || !aligned16(L.crd))) return NACHO_ERR_INVALID_ARG;
+                D.crd = L.crd;
+                D.count = L.count;
+            } else if (L.kind == NACHO_COMPRESSED) {
                 if (L.count < 0 || L.count > 0x7fffffffLL) return NACHO_ERR_INVALID_ARG;
                 if (need_arrays && (!L.pos || (L.count > 0 && !L.crd))) return NACHO_ERR_INVALID_ARG;
                 if (need_arrays && !aligned16(L.crd)) return NACHO_ERR_INVALID_ARG;
@@ -175,7 +183,10 @@ struct RemapWs {
     size_t bytes;
 };
 
-int spadd_fmt(Format f) { return f == FMT_VECTOR ? SPADD_VECTOR : (f == FMT_CSR ? SPADD_CSR : SPADD_DCSR); }
+int spadd_fmt(Format f)
+{
+    return f == FMT_VECTOR ? SPADD_VECTOR : (f == FMT_CSR ? SPADD_CSR : (f == FMT_COO ? SPADD_COO : SPADD_DCSR));
+}
 
 // Partitions a fused call uses: at least P, and enough that one partition's work
 // (ideal share + k - 1 by the tightness bound of Section 3.2.2) fits a wavefront.
@@ -571,6 +582,7 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
         return NACHO_ERR_INVALID_ARG;
     if (out->cap_nnz > 0 && (!out->crd1 || !out->val)) return NACHO_ERR_INVALID_ARG;
     if (fmt == FMT_DCSR && (!out->pos0 || (out->cap_rows > 0 && !out->crd0))) return NACHO_ERR_INVALID_ARG;
+    if (fmt == FMT_COO && out->cap_nnz > 0 && !out->crd0) return NACHO_ERR_INVALID_ARG;
     const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
     const bool recursive = multiply && fmt == FMT_DCSR && k > 1;    // (its own workspace layout)

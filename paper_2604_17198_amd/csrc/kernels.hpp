@@ -45,7 +45,7 @@ hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, 
                              const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream);
 
 // ---- k-way union addition ---------------------------------------------------
-enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2 };
+enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2, SPADD_COO = 3 };
 constexpr int kSpaddCap = 4096;         // entries of all operands one partition (workgroup) stages
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };

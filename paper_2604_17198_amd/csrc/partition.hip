@@ -63,6 +63,38 @@ struct LevelResult {
     int64_t c;  // C_m(x | prefix), unscaled
 };
 
+// How a compressed level's coordinates are read.  Plain: one int32 array.  Pairs: the level is
+// the list of (row, column) pairs of a coordinate-list (COO) operand, i.e. both of its levels
+// taken together as one sorted, duplicate-free level with the 64-bit coordinate row << 32 | column
+// (Algorithm 1 on the two levels and on this one level find the same boundary: the highest row
+// whose cost fits, then the highest column inside it, is the highest pair whose cost fits).
+struct PlainCoords {
+    typedef int type;
+    static constexpr type kNone = INT32_MAX;            // no coordinate
+    __device__ static type load(const DevOperands &ops, int t, int m, int at) { return ops.lvl[t][m].crd[at]; }
+    __device__ static int64_t extent(const DevOperands &ops, int m) { return ops.lvl[0][m].extent; }
+};
+struct PairCoords {
+    typedef long long type;
+    static constexpr type kNone = INT64_MAX;
+    __device__ static type load(const DevOperands &ops, int t, int, int at)
+    {
+        return ((long long)ops.lvl[t][0].crd[at] << 32) | (long long)(unsigned)ops.lvl[t][1].crd[at];
+    }
+    __device__ static int64_t extent(const DevOperands &ops, int) { return ops.lvl[0][0].extent << 32; }
+};
+
+// Least position in [lo, hi) of operand t whose coordinate is >= x; hi if there is none.
+template <class Acc>
+__device__ inline int lower_bound_level(const DevOperands &ops, int t, int m, int shift, int lo, int hi, int64_t x)
+{
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if ((int64_t)Acc::load(ops, t, m, mid + shift) < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
 // Dense level (level 0 of CSR operands): position == coordinate, cost through
 // the next level's pos array.  64-ary search over [0, N].
 template <int K>
@@ -113,13 +145,13 @@ __device__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, in
 // is exact as long as the windows bracket the boundary's positions.  c_low is
 // the cost at coordinate 0 under that clamping.  Used when the sampled search
 // below stops making progress.
-template <bool kLast, int K>
+template <bool kLast, int K, class Acc = PlainCoords>
 __device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, const int *base,
                                       int *wl, int *wh, int64_t c_low, int *p, const int *sh)
 {
     const int lane = lane_id();
     const int k = ops.k;
-    int64_t low = 0, high = ops.lvl[0][m].extent;
+    int64_t low = 0, high = Acc::extent(ops, m);
     while (low < high) {
         const int64_t span = high - low;
         const int64_t step = (span + NACHO_WAVE - 1) / NACHO_WAVE;
@@ -130,7 +162,7 @@ __device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, 
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             if (t >= k) break;
-            const int q = lower_bound_global(ops.lvl[t][m].crd + sh[t], wl[t], wh[t], x);
+            const int q = lower_bound_level<Acc>(ops, t, m, sh[t], wl[t], wh[t], x);
             ip[t] = q;
             c += kLast ? (int64_t)(q - base[t]) : (int64_t)(ops.lvl[t][m + 1].pos[q] - base[t]);
         }
@@ -201,10 +233,11 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 //                pays (used once for a group of neighbouring boundaries) and
 //                return; the result is in W.
 //   otherwise:   R_lo == R_hi; runs until the boundary is found.
-template <bool kLast, int K>
+template <bool kLast, int K, class Acc = PlainCoords>
 __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
                                       Windows<K> &W, bool narrow_only, int *p, const int *sh)
 {
+    typedef typename Acc::type CoordT;
     // costs, positions and coordinates all fit 32 bits (the operands hold fewer than
     // 2^31 entries together; INT32_MAX is no coordinate)
     const int R_lo = (int)R_lo64, R_hi = (int)R_hi64;
@@ -224,7 +257,8 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
     };
     int prev_total = INT32_MAX;
     for (;;) {
-        int v[K], ca[K], cb[K], w[K], mt[K];
+        CoordT v[K];
+        int ca[K], cb[K], w[K], mt[K];
         bool all_small = true;
         int total = 0;
 #pragma unroll
@@ -239,18 +273,18 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
             int64_t c0 = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p, sh);
+            return tracked_search<kLast, K, Acc>(ops, m, R_lo64, base, l, h, c0, p, sh);
         }
         prev_total = total;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             const bool valid = lane < mt[t];
             const int s = valid ? sample_pos(l[t], w[t], lane) : l[t];
-            v[t] = INT32_MAX;
+            v[t] = Acc::kNone;
             cb[t] = s - base[t];
             ca[t] = s + 1 - base[t];
             if (t < k) {
-                if (valid) v[t] = ops.lvl[t][m].crd[s + sh[t]];
+                if (valid) v[t] = Acc::load(ops, t, m, s + sh[t]);
                 if (!kLast) {
                     const int32_t *pos = ops.lvl[t][m + 1].pos;
                     cb[t] = valid ? pos[s] - base[t] : 0;
@@ -274,7 +308,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                 for (int u = 0; u < K; ++u) {
                     if (u == t) continue;
                     const int mid = (lo[t][u] + hi[t][u]) >> 1;
-                    const int xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
+                    const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
                     const bool go = lo[t][u] < hi[t][u];
                     const bool right = xs < v[t];
                     lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
@@ -286,7 +320,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
         // upper bound is within the query are a prefix of the lanes and those whose
         // lower bound exceeds it a suffix: one ballot each finds the largest / smallest
         // such sample, no reduction over the wavefront.
-        int vminus = -1, vplus = INT32_MAX;
+        CoordT vminus = -1, vplus = Acc::kNone;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             int glo = cb[t], ghi = cb[t];           // own operand: the sample's position is exact
@@ -313,11 +347,11 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
             const int n_le = __popcll(__ballot(valid && ghi <= R_lo));   // lanes 0 .. n_le - 1
             const int n_in = __popcll(__ballot(valid && glo <= R_hi));   // lanes n_in .. mt - 1 are after
             if (n_le > 0) {
-                const int cand = __shfl(v[t], n_le - 1, NACHO_WAVE);
+                const CoordT cand = __shfl(v[t], n_le - 1, NACHO_WAVE);
                 vminus = cand > vminus ? cand : vminus;  // largest sample not after the first boundary
             }
             if (n_in < mt[t]) {
-                const int cand = __shfl(v[t], n_in, NACHO_WAVE);
+                const CoordT cand = __shfl(v[t], n_in, NACHO_WAVE);
                 vplus = cand < vplus ? cand : vplus;     // smallest sample after the last boundary
             }
         }
@@ -339,7 +373,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     ncl = eq ? e : (c == 0 ? cl[u] : a);
                 }
             }
-            if (vplus != INT32_MAX) {
+            if (vplus != Acc::kNone) {
                 const int c = __popcll(__ballot(in && v[u] < vplus));
                 nh = c == mt[u] ? h[u] : sample_pos(l[u], w[u], c);
                 if (kLast) nch = nh - base[u];
@@ -358,7 +392,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
                     l[t] = W.l[t]; h[t] = W.h[t];
                     c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K>(ops, m, R_lo64, base, l, h, c0, p, sh);
+                return tracked_search<kLast, K, Acc>(ops, m, R_lo64, base, l, h, c0, p, sh);
             }
             r.x = vminus;
 #pragma unroll
@@ -379,7 +413,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
 // One level of Algorithm 1 for one query, starting from windows that bracket the
 // boundary.  `total` = cost of the level's whole segments.  On return p[t] =
 // position of operand t's first entry with coordinate >= x inside its segment.
-template <bool kLast, int K>
+template <bool kLast, int K, class Acc = PlainCoords>
 __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
                                         const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p,
                                         const int *sh)
@@ -391,7 +425,7 @@ __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R
 #pragma unroll
         for (int t = 0; t < K; ++t)
             if (t < k) p[t] = seg_hi[t];
-        r.x = ops.lvl[0][m].extent;
+        r.x = Acc::extent(ops, m);
         r.c = total;
         return r;
     }
@@ -409,11 +443,11 @@ __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R
 #pragma unroll
         for (int t = 0; t < K; ++t)
             if (t == which) at += sh[t];
-        r.x = ops.lvl[which][m].crd[at];
+        r.x = Acc::load(ops, which, m, at);
         r.c = R;
         return r;
     }
-    return sampled_search<kLast, K>(ops, m, R, R, W, false, p, sh);
+    return sampled_search<kLast, K, Acc>(ops, m, R, R, W, false, p, sh);
 }
 
 template <bool kLast, int K>
@@ -436,7 +470,9 @@ constexpr int kGroup = 1;   // neighbouring boundaries one wavefront searches
 // One wavefront searches kGroup neighbouring boundaries: their searches share
 // the first rounds (the windows are narrowed once around the whole group), then
 // every boundary is finished on its own from the shared windows.
-template <int K>
+// kPairs: the operands are coordinate lists (its own instantiation: the other formats keep
+// their register budget).
+template <int K, bool kPairs>
 __global__ void __launch_bounds__(256)
 partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                  const int64_t *__restrict__ queries, int64_t total_unscaled,
@@ -450,6 +486,7 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
     const int k = ops.k, d = ops.d;
     const int64_t total_scaled = total_unscaled * cost_scale;
     const bool dense0 = ops.lvl[0][0].kind == NACHO_DENSE;
+    constexpr bool pairs = kPairs;                                  // coordinate lists (COO), d == 2
 
     int64_t Qu[kGroup];
     bool interior[kGroup];
@@ -488,7 +525,9 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
     Windows<K> W0;
     if (!dense0 && q_first >= 0) {
         int dummy[K];
-        if (d == 1) {
+        if (pairs) {
+            windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
+        } else if (d == 1) {
             windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
             if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
         } else {
@@ -520,7 +559,28 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
         }
         int seg_lo[K], seg_hi[K], p[K];
         int64_t R = Qu[g];
-        if (d == 1) {
+        if (pairs) {
+            // one search over the (row, column) pairs; the row-level position of an operand is
+            // that of its first entry in the boundary's row
+            Windows<K> W = W0;
+            LevelResult r = compressed_level<true, K, PairCoords>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p,
+                                                                  no_shift);
+            R -= r.c;
+            const int x0 = (int)(r.x >> 32), x1 = (int)(r.x & 0xffffffffLL);
+            int mine = 0, row_at = 0;
+#pragma unroll
+            for (int t = 0; t < K; ++t)
+                if (t < k && lane == t) mine = p[t];
+            if (lane < k) row_at = lower_bound_global(ops.lvl[lane][0].crd, 0, mine, x0);
+            if (lane < k) {
+                pb[lane * 2 + 0] = row_at;
+                pb[lane * 2 + 1] = mine;
+            }
+            if (lane == 0) {
+                cb[0] = x0;
+                cb[1] = x1;
+            }
+        } else if (d == 1) {
             Windows<K> W = W0;
             LevelResult r = compressed_level<true, K>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi, W, p, no_shift);
             R -= r.c;
@@ -710,20 +770,32 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);
     // instantiated for 1, 2, 3, 4 and 8 operands so that small calls keep their state in registers
+    if (ops.lvl[0][0].kind == NACHO_NONUNIQUE) {
+        if (ops.k <= 2)
+            hipLaunchKernelGGL((partition_kernel<2, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        else if (ops.k <= 4)
+            hipLaunchKernelGGL((partition_kernel<4, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        else
+            hipLaunchKernelGGL((partition_kernel<8, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        return hipGetLastError();
+    }
     if (ops.k <= 1)
-        hipLaunchKernelGGL(partition_kernel<1>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<1, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 2)
-        hipLaunchKernelGGL(partition_kernel<2>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<2, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 3)
-        hipLaunchKernelGGL(partition_kernel<3>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<3, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 4)
-        hipLaunchKernelGGL(partition_kernel<4>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<4, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else
-        hipLaunchKernelGGL(partition_kernel<8>, dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<8, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     return hipGetLastError();
 }

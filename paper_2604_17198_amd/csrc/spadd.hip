@@ -243,6 +243,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 {
     typedef typename KeyOf<FMT>::type KeyT;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
+    constexpr bool kCoo = FMT == SPADD_COO;    // coordinate lists: the row of an entry is stored with it
     constexpr int R = kPerThread;
     constexpr int kShare = kTile / kWaves;     // merged slots a wavefront walks in the assembly
     __shared__ Tile<KeyT, T> w;
@@ -287,6 +288,10 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
                 w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
                 w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
+                if (kCoo) {
+                    const int32_t *rows_t = t < k ? ops.lvl[t][0].crd : nullptr;
+                    w.sstart[t] = (unsigned long long)(uintptr_t)(rows_t + q_lo[t] - off[t]);
+                }
                 if (kMapped) {
                     w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.start[t] : nullptr);
                     w.spos[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].pos : nullptr);
@@ -315,7 +320,15 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 
     uint32_t row[D == 2 ? R : 1];
     unsigned rowfirst = 0;                     // bit j: entry tid * R + j is the first of its row in its run
-    if (D == 2) {
+    if (kCoo) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int c = r * kThreads + tid;
+            row[r] = 0;
+            if (c < n) row[r] = (uint32_t)reinterpret_cast<const int32_t *>((uintptr_t)w.sstart[tr[r]])[c];
+        }
+    }
+    if (D == 2 && !kCoo) {
         // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
         // (word of the entry in marks), then hand every entry the latest marker
         // at or before it.  The first entry of every run carries a marker, so no
@@ -420,7 +433,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 
     // ---- 2. ranks: slot of every entry in the merged order -----------------------
     bool cont = false;                     // the partition starts inside a row whose head is elsewhere
-    if (D == 2) cont = row_continues<FMT>(ops, coord, posn, p);
+    if (D == 2 && !kCoo) cont = row_continues<FMT>(ops, coord, posn, p);
     for (int i = tid; i < kPadded; i += kThreads) w.marks[i] = 0;
     __syncthreads();
     int n_max = 0, t_max = 0;                  // the largest run searches nothing
@@ -665,7 +678,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 out.counts[1] = total_nnz;
                 const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
                 if (!fits) *out.status = NACHO_ERR_CAPACITY;
-                if (FMT == SPADD_VECTOR) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
+                if (FMT == SPADD_VECTOR || kCoo) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
                 if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
                 if (FMT == SPADD_DCSR) {
                     out.pos0[0] = 0;
@@ -736,6 +749,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const long long wr = (long long)((word >> kSlotRows) & 0x1ffu) + (long long)((so >> 31) & 0x7fffffffull);
         if (wpos < out.cap_nnz) {
             out.crd1[wpos] = colr[r];
+            if (kCoo) out.crd0[wpos] = (int32_t)rowr[r];
             static_cast<T *>(out.val)[wpos] = sum;
         }
         if (FMT == SPADD_DCSR && (word & kSlotEmit)) {
@@ -789,6 +803,8 @@ hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &op
     NACHO_SPADD_CASE(SPADD_CSR, false)
     NACHO_SPADD_CASE(SPADD_DCSR, false)
     NACHO_SPADD_CASE(SPADD_VECTOR, true)
+    NACHO_SPADD_CASE(SPADD_COO, false)
+    NACHO_SPADD_CASE(SPADD_COO, true)
     if (fmt == SPADD_CSR && multiply && ops.start[0]) {       // remapped operands of a DCSR product
         if (dtype == NACHO_F64)
             return launch_one<SPADD_CSR, double, true, true>(ops, vals, P, coord, posn, tile_state, out, s);
