@@ -237,6 +237,26 @@ def bench_others(steps, warmup):
                    f"rows, {m_rows} in both, {work} of {tot} input nnz coiterated, {n_mul} output nnz", fm, work,
                    nbytes_m, table=lambda: nb.workspace_parts(nb.OP_SPMUL, ops, nb.F32, wsm))
             del outm, wsm
+            # F4: the same two matrices as coordinate lists (COO + COO, COO Hadamard)
+            cops = []
+            for m in cfg["ops"]:
+                rws = np.repeat(m["crd0"], np.diff(m["pos1"])).astype(np.int32)
+                cops.append(nb.coo(dev(rws), dev(m["crd1"]), m["n_rows"], m["n_cols"], dev(m["val"])))
+            outc = nb.SparseOut("coo", 0, tot, torch.float32, "cuda")
+            wsc = torch.empty(nb.workspace_bytes(nb.OP_SPADD, cops, nb.F32), dtype=torch.uint8, device="cuda")
+            fa = lambda: nb.nacho_spadd_k(cops, outc, ws=wsc)
+            fa()
+            torch.cuda.synchronize()
+            n_add = int(outc.counts.cpu().numpy()[1])
+            record("F4_coo2_add", f"COO + COO on the C4 matrices, {tot} input nnz, {n_add} output nnz", fa, tot,
+                   tot * 12 + n_add * 12, table=lambda: nb.workspace_parts(nb.OP_SPADD, cops, nb.F32, wsc))
+            fh = lambda: nb.nacho_spmul_k(cops, outc, ws=wsc)
+            fh()
+            torch.cuda.synchronize()
+            n_had = int(outc.counts.cpu().numpy()[1])
+            record("F4_coo2_mul", f"COO Hadamard product of the C4 matrices, {tot} input nnz, {n_had} output nnz", fh,
+                   tot, tot * 12 + n_had * 12)
+            del cops, outc, wsc
         del ops, out, ws, cfg
     for kk in (2, 3):
         cfg = workloads.csr_add_config(kk)
