@@ -98,7 +98,7 @@ __device__ inline int lower_bound_level(const DevOperands &ops, int t, int m, in
 // Dense level (level 0 of CSR operands): position == coordinate, cost through
 // the next level's pos array.  64-ary search over [0, N].
 template <int K>
-__device__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, int *p)
+__device__ __forceinline__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, int *p)
 {
     const int lane = lane_id();
     const int k = ops.k;
@@ -146,7 +146,7 @@ __device__ LevelResult dense_search(const DevOperands &ops, int m, int64_t R, in
 // the cost at coordinate 0 under that clamping.  Used when the sampled search
 // below stops making progress.
 template <bool kLast, int K, class Acc = PlainCoords>
-__device__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, const int *base,
+__device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, const int *base,
                                       int *wl, int *wh, int64_t c_low, int *p, const int *sh)
 {
     const int lane = lane_id();
@@ -234,7 +234,7 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 //                return; the result is in W.
 //   otherwise:   R_lo == R_hi; runs until the boundary is found.
 template <bool kLast, int K, class Acc = PlainCoords>
-__device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
+__device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
                                       Windows<K> &W, bool narrow_only, int *p, const int *sh)
 {
     typedef typename Acc::type CoordT;
@@ -294,26 +294,52 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
         }
 
         // rank of every sample of t among the samples of u: K*(K-1) binary searches
-        // over the lanes, advanced in lockstep so their shuffles overlap
-        int lo[K][K], hi[K][K];
-#pragma unroll
-        for (int t = 0; t < K; ++t)
-#pragma unroll
-            for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[t][u] = mt[u]; }
-#pragma unroll
-        for (int it = 0; it < 7; ++it) {
+        // over the lanes
+        int lo[K][K];
+        if constexpr (K <= 3) {
+            // few operands: all searches advance in lockstep so that their shuffles overlap
+            int hi[K][K];
 #pragma unroll
             for (int t = 0; t < K; ++t)
 #pragma unroll
-                for (int u = 0; u < K; ++u) {
-                    if (u == t) continue;
-                    const int mid = (lo[t][u] + hi[t][u]) >> 1;
-                    const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
-                    const bool go = lo[t][u] < hi[t][u];
-                    const bool right = xs < v[t];
-                    lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
-                    hi[t][u] = (go && !right) ? mid : hi[t][u];
+                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[t][u] = mt[u]; }
+#pragma unroll
+            for (int it = 0; it < 7; ++it) {
+#pragma unroll
+                for (int t = 0; t < K; ++t)
+#pragma unroll
+                    for (int u = 0; u < K; ++u) {
+                        if (u == t) continue;
+                        const int mid = (lo[t][u] + hi[t][u]) >> 1;
+                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
+                        const bool go = lo[t][u] < hi[t][u];
+                        const bool right = xs < v[t];
+                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
+                        hi[t][u] = (go && !right) ? mid : hi[t][u];
+                    }
+            }
+        } else {
+            // many operands: one operand's searches at a time (the upper ends of all K * K
+            // searches at once do not fit the registers)
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                int hi[K];
+#pragma unroll
+                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[u] = mt[u]; }
+#pragma unroll
+                for (int it = 0; it < 7; ++it) {
+#pragma unroll
+                    for (int u = 0; u < K; ++u) {
+                        if (u == t) continue;
+                        const int mid = (lo[t][u] + hi[u]) >> 1;
+                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
+                        const bool go = lo[t][u] < hi[u];
+                        const bool right = xs < v[t];
+                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
+                        hi[u] = (go && !right) ? mid : hi[u];
+                    }
                 }
+            }
         }
         // Bounds of the cost of every sampled coordinate.  Inside one operand the
         // samples ascend with the lane and so do both bounds, so the samples whose
@@ -414,7 +440,7 @@ __device__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_l
 // boundary.  `total` = cost of the level's whole segments.  On return p[t] =
 // position of operand t's first entry with coordinate >= x inside its segment.
 template <bool kLast, int K, class Acc = PlainCoords>
-__device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
+__device__ __forceinline__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
                                         const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p,
                                         const int *sh)
 {
@@ -438,11 +464,13 @@ __device__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R
 #pragma unroll
         for (int t = 0; t < K; ++t)
             if (t < k) p[t] = seg_lo[t];
-        p[which] = seg_lo[which] + (int)R;
-        int at = p[which];
+        int at = 0;                                    // (no array is indexed by `which`: they stay in registers)
 #pragma unroll
         for (int t = 0; t < K; ++t)
-            if (t == which) at += sh[t];
+            if (t == which) {
+                p[t] = seg_lo[t] + (int)R;
+                at = p[t] + sh[t];
+            }
         r.x = Acc::load(ops, which, m, at);
         r.c = R;
         return r;
@@ -586,7 +614,9 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             R -= r.c;
             if (lane == 0) {
                 cb[0] = (int32_t)r.x;
-                for (int t = 0; t < k; ++t) pb[t] = p[t];
+#pragma unroll
+                for (int t = 0; t < K; ++t)
+                    if (t < k) pb[t] = p[t];
             }
         } else {
             LevelResult r0;
@@ -623,10 +653,12 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             if (lane == 0) {
                 cb[0] = (int32_t)r0.x;
                 cb[1] = (int32_t)r1.x;
-                for (int t = 0; t < k; ++t) {
-                    pb[t * 2 + 0] = p0[t];
-                    pb[t * 2 + 1] = p[t];
-                }
+#pragma unroll
+                for (int t = 0; t < K; ++t)
+                    if (t < k) {
+                        pb[t * 2 + 0] = p0[t];
+                        pb[t * 2 + 1] = p[t];
+                    }
             }
         }
         if (lane == 0) cost[b] = (Qu[g] - R) * cost_scale;
