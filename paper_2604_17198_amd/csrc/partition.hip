@@ -293,67 +293,19 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             }
         }
 
-        // rank of every sample of t among the samples of u: K*(K-1) binary searches
-        // over the lanes
-        int lo[K][K];
-        if constexpr (K <= 3) {
-            // few operands: all searches advance in lockstep so that their shuffles overlap
-            int hi[K][K];
-#pragma unroll
-            for (int t = 0; t < K; ++t)
-#pragma unroll
-                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[t][u] = mt[u]; }
-#pragma unroll
-            for (int it = 0; it < 7; ++it) {
-#pragma unroll
-                for (int t = 0; t < K; ++t)
-#pragma unroll
-                    for (int u = 0; u < K; ++u) {
-                        if (u == t) continue;
-                        const int mid = (lo[t][u] + hi[t][u]) >> 1;
-                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
-                        const bool go = lo[t][u] < hi[t][u];
-                        const bool right = xs < v[t];
-                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
-                        hi[t][u] = (go && !right) ? mid : hi[t][u];
-                    }
-            }
-        } else {
-            // many operands: one operand's searches at a time (the upper ends of all K * K
-            // searches at once do not fit the registers)
-#pragma unroll
-            for (int t = 0; t < K; ++t) {
-                int hi[K];
-#pragma unroll
-                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[u] = mt[u]; }
-#pragma unroll
-                for (int it = 0; it < 7; ++it) {
-#pragma unroll
-                    for (int u = 0; u < K; ++u) {
-                        if (u == t) continue;
-                        const int mid = (lo[t][u] + hi[u]) >> 1;
-                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
-                        const bool go = lo[t][u] < hi[u];
-                        const bool right = xs < v[t];
-                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
-                        hi[u] = (go && !right) ? mid : hi[u];
-                    }
-                }
-            }
-        }
-        // Bounds of the cost of every sampled coordinate.  Inside one operand the
+        // Bounds of the cost of every sampled coordinate, from the rank lo_t[u] of the sample
+        // among the samples of every other operand u.  Inside one operand the
         // samples ascend with the lane and so do both bounds, so the samples whose
         // upper bound is within the query are a prefix of the lanes and those whose
         // lower bound exceeds it a suffix: one ballot each finds the largest / smallest
         // such sample, no reduction over the wavefront.
         CoordT vminus = -1, vplus = Acc::kNone;
-#pragma unroll
-        for (int t = 0; t < K; ++t) {
+        auto bounds_of = [&](int t, const int (&lo_t)[K]) {
             int glo = cb[t], ghi = cb[t];           // own operand: the sample's position is exact
 #pragma unroll
             for (int u = 0; u < K; ++u) {
                 if (u == t) continue;
-                const int c = lo[t][u];             // u's samples below this coordinate
+                const int c = lo_t[u];              // u's samples below this coordinate
                 int costA, costB;
                 if (kLast) {
                     const int posA = c == 0 ? l[u] : sample_pos(l[u], w[u], c - 1) + 1;
@@ -379,6 +331,55 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             if (n_in < mt[t]) {
                 const CoordT cand = __shfl(v[t], n_in, NACHO_WAVE);
                 vplus = cand < vplus ? cand : vplus;     // smallest sample after the last boundary
+            }
+        };
+        // rank of every sample of t among the samples of u: K*(K-1) binary searches over the lanes
+        if constexpr (K <= 3) {
+            // few operands: all searches advance in lockstep so that their shuffles overlap
+            int lo[K][K], hi[K][K];
+#pragma unroll
+            for (int t = 0; t < K; ++t)
+#pragma unroll
+                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[t][u] = mt[u]; }
+#pragma unroll
+            for (int it = 0; it < 7; ++it) {
+#pragma unroll
+                for (int t = 0; t < K; ++t)
+#pragma unroll
+                    for (int u = 0; u < K; ++u) {
+                        if (u == t) continue;
+                        const int mid = (lo[t][u] + hi[t][u]) >> 1;
+                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
+                        const bool go = lo[t][u] < hi[t][u];
+                        const bool right = xs < v[t];
+                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
+                        hi[t][u] = (go && !right) ? mid : hi[t][u];
+                    }
+            }
+#pragma unroll
+            for (int t = 0; t < K; ++t) bounds_of(t, lo[t]);
+        } else {
+            // many operands: one operand at a time, searches and bounds (the state of all
+            // K * K searches at once does not fit the registers)
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                int lo_t[K], hi[K];
+#pragma unroll
+                for (int u = 0; u < K; ++u) { lo_t[u] = 0; hi[u] = mt[u]; }
+#pragma unroll
+                for (int it = 0; it < 7; ++it) {
+#pragma unroll
+                    for (int u = 0; u < K; ++u) {
+                        if (u == t) continue;
+                        const int mid = (lo_t[u] + hi[u]) >> 1;
+                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
+                        const bool go = lo_t[u] < hi[u];
+                        const bool right = xs < v[t];
+                        lo_t[u] = (go && right) ? mid + 1 : lo_t[u];
+                        hi[u] = (go && !right) ? mid : hi[u];
+                    }
+                }
+                bounds_of(t, lo_t);
             }
         }
 
