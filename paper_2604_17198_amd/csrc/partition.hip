@@ -19,6 +19,13 @@
 //     Once every window holds <= 64 entries the bounds are exact and the round
 //     returns the boundary.  A boundary over 10M + 1M + 100k entries takes about
 //     seven rounds, i.e. seven dependent loads instead of several hundred.
+//     (With five to eight operands the K * K rank searches per round outgrow the
+//     registers and the instruction cache; those calls use the 64-ary search over
+//     coordinates with one lower-bound search per operand and probe, inside
+//     tracked windows, throughout.)
+//   * Coordinate lists (COO): both levels are searched as one level of (row,
+//     column) pairs with 64-bit coordinates.
+//   * One CSR operand (SpMV, SpMM): no search at all, see partition_csr1_kernel.
 // The result is the coordinate and the positions the serial search returns: the
 // highest coordinate whose cost does not exceed the residual query (it is then
 // a stored coordinate), and for every operand the position of its first entry

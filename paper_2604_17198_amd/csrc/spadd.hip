@@ -18,7 +18,8 @@
 // Per partition the workgroup
 //   1. stages the operands' coordinate segments in LDS as k sorted runs of keys
 //      (vectors: the index; matrices: row<<32 | column, the row of every entry
-//      recovered from the pos array with a marker + latest-marker scan);
+//      recovered from the pos array with a marker + latest-marker scan, or read
+//      from the stored rows of a coordinate list);
 //   2. ranks: for every pair of runs the entries of the smaller run search the
 //      larger one.  The position found is the number of entries of the larger
 //      run that precede the entry in the stable k-way merge (ties in operand
@@ -28,16 +29,19 @@
 //      that meets an equal key in an operand with a smaller index is flagged as
 //      a duplicate.  Own position + searched positions + summed marks = the
 //      entry's slot in the merged order; a 16-bit descriptor (position in the
-//      runs, duplicate flag) is scattered to that slot;
+//      runs, duplicate flag) is scattered to that slot.  The partition's output
+//      counts are known at this point already (an entry is emitted iff no
+//      earlier operand stores its key; DCSR: the searches also settle which
+//      entry starts a row) and are published for the prefix sum right away;
 //   3. assembly: walks the merged order; a slot that is not a duplicate is the
-//      HEAD of its coordinate.  The number of heads is the partition's output
-//      count (and a head whose predecessor lies in another row starts a row);
-//      every slot keeps the number of heads (and row heads) before it;
-//   4. prefix sum: publishes its counts and reads the counts of everything
-//      before it (two levels, see below); the loads of the values are in
-//      flight meanwhile;
-//   5. compute: every thread goes back to its own entries (coordinates and
-//      values are in its registers).  A head writes coordinate and value at
+//      HEAD of its coordinate (and a head whose predecessor lies in another row
+//      starts a row); every slot keeps the number of heads (and row heads)
+//      before it;
+//   4. prefix sum: reads the counts of everything before the partition (two
+//      levels, see below; requested before the assembly, consumed after it);
+//      the loads of the values are in flight meanwhile;
+//   5. compute: every thread goes back to its own entries (values in its
+//      registers, coordinates re-read from the keys).  A head writes coordinate and value at
 //      offset + heads before its slot; its value is its own plus the
 //      duplicates in the slots that follow it, i.e. in operand order
 //      (duplicates hand their values over through LDS).  The hierarchical
