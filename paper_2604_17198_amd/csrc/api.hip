@@ -494,10 +494,11 @@ static int32_t dcsr_product(const nacho_tensor *ops, int32_t k, int32_t dtype, i
             rows.lvl[t][0] = dev.lvl[t][0];
             rows_total += dev.lvl[t][0].count;
         }
-        if (hipMemsetAsync(w.remap.cost, 0, sizeof(int32_t) * (size_t)(w.Mmax + 1) * k, s) != hipSuccess)
-            return NACHO_ERR_HIP;
+        // (the partition kernel also zeroes the per-row counts; the array starts on a 256-byte
+        // boundary and so does whatever follows it, so whole 64-bit words may be cleared)
+        const int64_t cost_words = ((int64_t)(w.Mmax + 1) * k + 1) / 2;
         if (launch_partition(rows, 1, w.P0, 0, nullptr, rows_total, w.parts0.coord, w.parts0.posn, w.parts0.cost,
-                             s) != hipSuccess)
+                             s, reinterpret_cast<unsigned long long *>(w.remap.cost), cost_words) != hipSuccess)
             return NACHO_ERR_HIP;
         profile_mark("rows_partition");
         if (launch_rows_match(dev, w.P0, w.parts0.posn, w.flags, w.qpos, s) != hipSuccess) return NACHO_ERR_HIP;
