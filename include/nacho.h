@@ -60,7 +60,7 @@ typedef enum {
 } nacho_op;
 
 #define NACHO_MAX_OPERANDS 8
-#define NACHO_MAX_LEVELS 2
+#define NACHO_MAX_LEVELS 3
 
 /* One level of a tensor's coordinate hierarchy (Section 4.2.1).
  *   DENSE:      every coordinate in [0, extent) is present; pos, crd are NULL.
@@ -84,6 +84,8 @@ typedef struct {
  *   sparse vector  nlevels = 1  {COMPRESSED}
  *   CSR            nlevels = 2  {DENSE, COMPRESSED}
  *   DCSR           nlevels = 2  {COMPRESSED, COMPRESSED}
+ *   CSF            nlevels = 3  {COMPRESSED, COMPRESSED, COMPRESSED}: third-order
+ *                  tensors (nacho_partition only)
  *   COO            nlevels = 2  {NONUNIQUE, SINGLETON}: entries sorted by (row,
  *                  column), no pair twice (nacho_partition, nacho_spadd_k,
  *                  nacho_spmul_k)

@@ -20,7 +20,7 @@ from . import build as _build
 F32, F64 = 0, 1
 DENSE, COMPRESSED, NONUNIQUE, SINGLETON = 0, 1, 2, 3
 OP_PARTITION, OP_SPMV, OP_SPMM, OP_SPADD, OP_SPMUL = 0, 1, 2, 3, 4
-MAX_OPERANDS, MAX_LEVELS = 8, 2
+MAX_OPERANDS, MAX_LEVELS = 8, 3
 
 EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
@@ -168,6 +168,13 @@ def csr(pos, crd, n_rows, n_cols, val=None):
 def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols, val=None):
     return Operand([{"kind": "compressed", "extent": n_rows, "pos": pos0, "crd": crd0},
                     {"kind": "compressed", "extent": n_cols, "pos": pos1, "crd": crd1}], val)
+
+
+def csf3(pos0, crd0, pos1, crd1, pos2, crd2, shape, val=None):
+    """Third-order tensor, three compressed levels (nacho_partition only)."""
+    return Operand([{"kind": "compressed", "extent": shape[0], "pos": pos0, "crd": crd0},
+                    {"kind": "compressed", "extent": shape[1], "pos": pos1, "crd": crd1},
+                    {"kind": "compressed", "extent": shape[2], "pos": pos2, "crd": crd2}], val)
 
 
 def coo(rows, cols, n_rows, n_cols, val=None):

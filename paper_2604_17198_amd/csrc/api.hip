@@ -42,7 +42,7 @@ using namespace nacho_host;
 
 namespace {
 
-enum Format { FMT_BAD = 0, FMT_VECTOR, FMT_CSR, FMT_DCSR, FMT_COO };
+enum Format { FMT_BAD = 0, FMT_VECTOR, FMT_CSR, FMT_DCSR, FMT_COO, FMT_CSF3 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -52,6 +52,9 @@ Format tensor_format(const nacho_tensor &t)
     if (t.nlevels == 2 && t.lvl[0].kind == NACHO_DENSE && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_CSR;
     if (t.nlevels == 2 && t.lvl[0].kind == NACHO_COMPRESSED && t.lvl[1].kind == NACHO_COMPRESSED) return FMT_DCSR;
     if (t.nlevels == 2 && t.lvl[0].kind == NACHO_NONUNIQUE && t.lvl[1].kind == NACHO_SINGLETON) return FMT_COO;
+    if (t.nlevels == 3 && t.lvl[0].kind == NACHO_COMPRESSED && t.lvl[1].kind == NACHO_COMPRESSED &&
+        t.lvl[2].kind == NACHO_COMPRESSED)
+        return FMT_CSF3;
     return FMT_BAD;
 }
 
@@ -270,6 +273,7 @@ int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int
         return fused_partitions(op, fmt, dtype, k, total, P);
     case NACHO_OP_SPADD:
     case NACHO_OP_SPMUL:      // (a DCSR product: an upper bound, the count depends on the intersected rows)
+        if (fmt == FMT_CSF3) return 0;
         return fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     default: return 0;
     }
@@ -301,6 +305,7 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
         }
         /* fall through: the pipeline of the union */
     case NACHO_OP_SPADD: {
+        if (fmt == FMT_CSF3) return NACHO_ERR_UNSUPPORTED;
         const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
         *bytes = carve_spadd(nullptr, Pe, k, dev.d).bytes;
         return NACHO_OK;
@@ -570,6 +575,7 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     Format fmt;
     int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
     if (rc != NACHO_OK) return rc;
+    if (fmt == FMT_CSF3) return NACHO_ERR_UNSUPPORTED;          // third-order tensors: partition only
     // (the product of one operand is the operand: the union's pipeline copies it)
     if (multiply && fmt == FMT_DCSR && k == 1) multiply = false;
     SpaddValues vals;

@@ -102,6 +102,16 @@ __device__ inline int lower_bound_level(const DevOperands &ops, int t, int m, in
     return lo;
 }
 
+// Cost of the entries before position q of a level that is not the last one: the start of
+// q's segment one level down -- or, kDeep (level 0 of a three-level operand), the start two
+// levels down, where the non-zeros are.
+template <bool kDeep>
+__device__ inline int cost_at(const DevOperands &ops, int t, int m, int q)
+{
+    const int v = ops.lvl[t][m + 1].pos[q];
+    return kDeep ? ops.lvl[t][m + 2].pos[v] : v;
+}
+
 // Dense level (level 0 of CSR operands): position == coordinate, cost through
 // the next level's pos array.  64-ary search over [0, N].
 template <int K>
@@ -152,7 +162,7 @@ __device__ __forceinline__ LevelResult dense_search(const DevOperands &ops, int 
 // is exact as long as the windows bracket the boundary's positions.  c_low is
 // the cost at coordinate 0 under that clamping.  Used when the sampled search
 // below stops making progress.
-template <bool kLast, int K, class Acc = PlainCoords>
+template <bool kLast, int K, class Acc = PlainCoords, bool kDeep = false>
 __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, int m, int64_t R, const int *base,
                                       int *wl, int *wh, int64_t c_low, int *p, const int *sh)
 {
@@ -171,7 +181,7 @@ __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, in
             if (t >= k) break;
             const int q = lower_bound_level<Acc>(ops, t, m, sh[t], wl[t], wh[t], x);
             ip[t] = q;
-            c += kLast ? (int64_t)(q - base[t]) : (int64_t)(ops.lvl[t][m + 1].pos[q] - base[t]);
+            c += kLast ? (int64_t)(q - base[t]) : (int64_t)(cost_at<kDeep>(ops, t, m, q) - base[t]);
         }
         const unsigned long long ok = __ballot(c <= R);
         const int n = __popcll(ok);
@@ -208,7 +218,7 @@ struct Windows {
     int base[K], l[K], h[K], cl[K], ch[K];
 };
 
-template <bool kLast, int K>
+template <bool kLast, int K, bool kDeep = false>
 __device__ inline void windows_init(const DevOperands &ops, int m, const int *seg_lo, const int *seg_hi,
                                     Windows<K> &W)
 {
@@ -222,9 +232,8 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
                 W.base[t] = seg_lo[t];
                 W.ch[t] = seg_hi[t] - seg_lo[t];
             } else {
-                const int32_t *pos = ops.lvl[t][m + 1].pos;
-                W.base[t] = pos[seg_lo[t]];
-                W.ch[t] = pos[seg_hi[t]] - W.base[t];
+                W.base[t] = cost_at<kDeep>(ops, t, m, seg_lo[t]);
+                W.ch[t] = cost_at<kDeep>(ops, t, m, seg_hi[t]) - W.base[t];
             }
         }
     }
@@ -240,7 +249,7 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 //                pays (used once for a group of neighbouring boundaries) and
 //                return; the result is in W.
 //   otherwise:   R_lo == R_hi; runs until the boundary is found.
-template <bool kLast, int K, class Acc = PlainCoords>
+template <bool kLast, int K, class Acc = PlainCoords, bool kDeep = false>
 __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
                                       Windows<K> &W, bool narrow_only, int *p, const int *sh)
 {
@@ -280,7 +289,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             int64_t c0 = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K, Acc>(ops, m, R_lo64, base, l, h, c0, p, sh);
+            return tracked_search<kLast, K, Acc, kDeep>(ops, m, R_lo64, base, l, h, c0, p, sh);
         }
         prev_total = total;
 #pragma unroll
@@ -293,9 +302,8 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             if (t < k) {
                 if (valid) v[t] = Acc::load(ops, t, m, s + sh[t]);
                 if (!kLast) {
-                    const int32_t *pos = ops.lvl[t][m + 1].pos;
-                    cb[t] = valid ? pos[s] - base[t] : 0;
-                    ca[t] = valid ? pos[s + 1] - base[t] : 0;
+                    cb[t] = valid ? cost_at<kDeep>(ops, t, m, s) - base[t] : 0;
+                    ca[t] = valid ? cost_at<kDeep>(ops, t, m, s + 1) - base[t] : 0;
                 }
             }
         }
@@ -426,7 +434,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
                     l[t] = W.l[t]; h[t] = W.h[t];
                     c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K, Acc>(ops, m, R_lo64, base, l, h, c0, p, sh);
+                return tracked_search<kLast, K, Acc, kDeep>(ops, m, R_lo64, base, l, h, c0, p, sh);
             }
             r.x = vminus;
 #pragma unroll
@@ -447,7 +455,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
 // One level of Algorithm 1 for one query, starting from windows that bracket the
 // boundary.  `total` = cost of the level's whole segments.  On return p[t] =
 // position of operand t's first entry with coordinate >= x inside its segment.
-template <bool kLast, int K, class Acc = PlainCoords>
+template <bool kLast, int K, class Acc = PlainCoords, bool kDeep = false>
 __device__ __forceinline__ LevelResult compressed_level(const DevOperands &ops, int m, int64_t R, int64_t total,
                                         const int *seg_lo, const int *seg_hi, Windows<K> &W, int *p,
                                         const int *sh)
@@ -490,9 +498,9 @@ __device__ __forceinline__ LevelResult compressed_level(const DevOperands &ops, 
         int64_t c0 = 0;
 #pragma unroll
         for (int t = 0; t < K; ++t) c0 += W.cl[t];
-        return tracked_search<kLast, K, Acc>(ops, m, R, W.base, W.l, W.h, c0, p, sh);
+        return tracked_search<kLast, K, Acc, kDeep>(ops, m, R, W.base, W.l, W.h, c0, p, sh);
     }
-    return sampled_search<kLast, K, Acc>(ops, m, R, R, W, false, p, sh);
+    return sampled_search<kLast, K, Acc, kDeep>(ops, m, R, R, W, false, p, sh);
 }
 
 template <bool kLast, int K>
@@ -515,9 +523,9 @@ constexpr int kGroup = 1;   // neighbouring boundaries one wavefront searches
 // One wavefront searches kGroup neighbouring boundaries: their searches share
 // the first rounds (the windows are narrowed once around the whole group), then
 // every boundary is finished on its own from the shared windows.
-// kPairs: the operands are coordinate lists (its own instantiation: the other formats keep
-// their register budget).
-template <int K, bool kPairs>
+// kMode: 0 = vectors, CSR, DCSR; 1 = coordinate lists; 2 = three compressed levels (CSF).  The
+// last two are instantiations of their own: the other formats keep their register budget.
+template <int K, int kMode>
 __global__ void __launch_bounds__(256)
 partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                  const int64_t *__restrict__ queries, int64_t total_unscaled,
@@ -531,7 +539,8 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
     const int k = ops.k, d = ops.d;
     const int64_t total_scaled = total_unscaled * cost_scale;
     const bool dense0 = ops.lvl[0][0].kind == NACHO_DENSE;
-    constexpr bool pairs = kPairs;                                  // coordinate lists (COO), d == 2
+    constexpr bool pairs = kMode == 1;                              // coordinate lists (COO), d == 2
+    constexpr bool csf3 = kMode == 2;                               // three compressed levels, d == 3
 
     int64_t Qu[kGroup];
     bool interior[kGroup];
@@ -572,6 +581,8 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
         int dummy[K];
         if (pairs) {
             windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
+        } else if (csf3) {
+            windows_init<false, K, true>(ops, 0, seg0_lo, seg0_hi, W0);
         } else if (d == 1) {
             windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
             if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
@@ -624,6 +635,64 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             if (lane == 0) {
                 cb[0] = x0;
                 cb[1] = x1;
+            }
+        } else if (csf3) {
+            // three compressed levels: Algorithm 1 level by level; a level's cost counts the
+            // non-zeros below its entries (two pos arrays down at level 0, one at level 1)
+            int p0[K], p1[K];
+            Windows<K> W = W0;
+            LevelResult r0 = compressed_level<false, K, PlainCoords, true>(ops, 0, R, total_unscaled, seg0_lo, seg0_hi,
+                                                                           W, p, no_shift);
+            R -= r0.c;
+            int64_t tot1 = 0;
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                p0[t] = 0;
+                seg_lo[t] = seg_hi[t] = 0;
+                if (t < k) {
+                    p0[t] = p[t];
+                    const int32_t *pos1 = ops.lvl[t][1].pos;
+                    const bool present = p[t] < seg0_hi[t] && (int64_t)ops.lvl[t][0].crd[p[t]] == r0.x;
+                    seg_lo[t] = pos1[p[t]];
+                    seg_hi[t] = present ? pos1[p[t] + 1] : seg_lo[t];
+                    tot1 += ops.lvl[t][2].pos[seg_hi[t]] - ops.lvl[t][2].pos[seg_lo[t]];
+                }
+            }
+            Windows<K> W1;
+            windows_init<false, K>(ops, 1, seg_lo, seg_hi, W1);
+            LevelResult r1 = compressed_level<false, K>(ops, 1, R, tot1, seg_lo, seg_hi, W1, p, no_shift);
+            R -= r1.c;
+            int64_t tot2 = 0;
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                p1[t] = 0;
+                if (t < k) {
+                    p1[t] = p[t];
+                    const int32_t *pos2 = ops.lvl[t][2].pos;
+                    const bool present = p[t] < seg_hi[t] && (int64_t)ops.lvl[t][1].crd[p[t]] == r1.x;
+                    const int lo2 = pos2[p[t]];
+                    seg_hi[t] = present ? pos2[p[t] + 1] : lo2;     // (level-1 bounds are used up)
+                    seg_lo[t] = lo2;
+                    tot2 += seg_hi[t] - seg_lo[t];
+                } else {
+                    seg_lo[t] = seg_hi[t] = 0;
+                }
+            }
+            Windows<K> W2;
+            windows_init<true, K>(ops, 2, seg_lo, seg_hi, W2);
+            LevelResult r2 = compressed_level<true, K>(ops, 2, R, tot2, seg_lo, seg_hi, W2, p, no_shift);
+            R -= r2.c;
+            if (lane == 0) {
+                cb[0] = (int32_t)r0.x;
+                cb[1] = (int32_t)r1.x;
+                cb[2] = (int32_t)r2.x;
+#pragma unroll
+                for (int t = 0; t < K; ++t)
+                    if (t < k) {
+                        pb[t * 3 + 0] = p0[t];
+                        pb[t * 3 + 1] = p1[t];
+                        pb[t * 3 + 2] = p[t];
+                    }
             }
         } else if (d == 1) {
             Windows<K> W = W0;
@@ -819,32 +888,44 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);
     // instantiated for 1, 2, 3, 4 and 8 operands so that small calls keep their state in registers
-    if (ops.lvl[0][0].kind == NACHO_NONUNIQUE) {
+    if (ops.d == 3) {
         if (ops.k <= 2)
-            hipLaunchKernelGGL((partition_kernel<2, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+            hipLaunchKernelGGL((partition_kernel<2, 2>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                                queries, total_unscaled, coord, posn, cost, clear);
         else if (ops.k <= 4)
-            hipLaunchKernelGGL((partition_kernel<4, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+            hipLaunchKernelGGL((partition_kernel<4, 2>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                                queries, total_unscaled, coord, posn, cost, clear);
         else
-            hipLaunchKernelGGL((partition_kernel<8, true>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+            hipLaunchKernelGGL((partition_kernel<8, 2>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        return hipGetLastError();
+    }
+    if (ops.lvl[0][0].kind == NACHO_NONUNIQUE) {
+        if (ops.k <= 2)
+            hipLaunchKernelGGL((partition_kernel<2, 1>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        else if (ops.k <= 4)
+            hipLaunchKernelGGL((partition_kernel<4, 1>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+                               queries, total_unscaled, coord, posn, cost, clear);
+        else
+            hipLaunchKernelGGL((partition_kernel<8, 1>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                                queries, total_unscaled, coord, posn, cost, clear);
         return hipGetLastError();
     }
     if (ops.k <= 1)
-        hipLaunchKernelGGL((partition_kernel<1, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<1, 0>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 2)
-        hipLaunchKernelGGL((partition_kernel<2, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<2, 0>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 3)
-        hipLaunchKernelGGL((partition_kernel<3, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<3, 0>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else if (ops.k <= 4)
-        hipLaunchKernelGGL((partition_kernel<4, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<4, 0>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     else
-        hipLaunchKernelGGL((partition_kernel<8, false>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
+        hipLaunchKernelGGL((partition_kernel<8, 0>), dim3(grid), dim3(256), 0, stream, ops, cost_scale, P, grain,
                            queries, total_unscaled, coord, posn, cost, clear);
     return hipGetLastError();
 }

@@ -8,7 +8,7 @@ import oracle
 from paper_2604_17198_amd import binding as nb
 from paper_2604_17198_amd import workloads
 from gpu_util import csr_operand, dcsr_operand, dev, parts_to_numpy, vector_operand
-from util import random_coords, to_csr, to_dcsr, to_vector
+from util import random_coords, to_csf3, to_csr, to_dcsr, to_vector
 
 pytestmark = pytest.mark.gpu
 
@@ -167,3 +167,39 @@ def test_fused_call_partition_table(op):
             print(f"fused table {op} P={P} -> {t['P']}", flush=True)
             _compare({k: v.cpu().numpy() for k, v in t.items() if k in ("coord", "posn", "cost")},
                      oracle.partition(o, t["P"]), (op, P))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_third_order_csf_random(k):
+    """Three compressed levels: Algorithm 1 level by level, costs two pos arrays down at the top."""
+    rng = np.random.default_rng(900 + k)
+    for trial in range(5):
+        shape = [(4, 5, 6), (30, 40, 50), (200, 3, 400), (2, 1000, 7), (60, 60, 60)][trial]
+        cs = []
+        for t in range(k):
+            n = int(rng.integers(0, min(int(np.prod(shape)) // 2, 6000) + 1))
+            c = random_coords(rng, shape, n)
+            if trial == 1 and t > 0:
+                c = cs[0].copy()                       # every coordinate tied across operands
+            cs.append(c)
+        g, o = [], []
+        for c in cs:
+            arrs = to_csf3(c)
+            g.append(nb.csf3(*[dev(a) for a in arrs], shape))
+            o.append(oracle.Tensor([("compressed", shape[0], arrs[0], arrs[1]), ("compressed", shape[1], arrs[2], arrs[3]),
+                                    ("compressed", shape[2], arrs[4], arrs[5])]))
+        total = sum(len(c) for c in cs)
+        for P in (1, 2, 7, 64, 300, total + 2):
+            print(f"partition csf3 k={k} trial={trial} shape={shape} total={total} P={P}", flush=True)
+            got = parts_to_numpy(nb.nacho_partition(g, P))
+            _compare(got, oracle.partition(o, P), (k, trial, P))
+
+
+def test_third_order_csf_is_partition_only():
+    c = np.array([[0, 1, 2], [1, 0, 0]], dtype=np.int64)
+    arrs = [dev(a) for a in to_csf3(c)]
+    op = nb.csf3(*arrs, (2, 2, 3), dev(np.ones(2, np.float32)))
+    out = nb.SparseOut("vector", 0, 4, torch.float32, "cuda")
+    with pytest.raises(nb.NachoError) as e:
+        nb.nacho_spadd_k([op, op], out)
+    assert e.value.status == -2
