@@ -99,19 +99,41 @@ __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 template <typename KeyT> __device__ inline uint32_t row_of(KeyT k) { return (uint32_t)((uint64_t)k >> 32); }
 
 // Number of keys of the sorted run seg[0, n) that are smaller than key[i], for
-// NI keys per lane at once (n >= 1, the same for all lanes).  Binary lifting:
-// the loop count depends on n only, and the NI chains of LDS reads overlap.
+// NI keys per lane at once (n >= 1, the same for all lanes).  Quaternary lifting
+// (32-bit keys):
+// every level tries to advance by one, two or three steps (three independent LDS
+// reads), the steps shrink by four from level to level -- floor(log4 n) + 1
+// dependent rounds instead of floor(log2 n) + 1, and what a partition's ranking
+// costs is the length of that chain.  The loop count depends on n only.
 template <typename KeyT, int NI>
 __device__ inline void run_lower_bound(const KeyT *seg, int n, const KeyT (&key)[NI], int (&lb)[NI])
 {
 #pragma unroll
     for (int i = 0; i < NI; ++i) lb[i] = 0;
-    for (int step = 1 << (31 - __builtin_clz((unsigned)n)); step > 0; step >>= 1) {
+    if (sizeof(KeyT) == 8) {
+        // 64-bit keys: three probes per level would cost the registers that keep three
+        // workgroups on a CU; plain binary lifting
+        for (int step = 1 << (31 - __builtin_clz((unsigned)n)); step > 0; step >>= 1) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int j = lb[i] + step;
+                const KeyT v = seg[(j <= n ? j : n) - 1];
+                lb[i] = (j <= n && v < key[i]) ? j : lb[i];
+            }
+        }
+        return;
+    }
+    for (int step = 1 << ((31 - __builtin_clz((unsigned)n)) & ~1); step > 0; step >>= 2) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int j = lb[i] + step;
-            const KeyT v = seg[(j <= n ? j : n) - 1];
-            lb[i] = (j <= n && v < key[i]) ? j : lb[i];
+            const int j1 = lb[i] + step, j2 = j1 + step, j3 = j2 + step;
+            const KeyT v1 = seg[(j1 <= n ? j1 : n) - 1];
+            const KeyT v2 = seg[(j2 <= n ? j2 : n) - 1];
+            const KeyT v3 = seg[(j3 <= n ? j3 : n) - 1];
+            // (the run is sorted: a later probe is below the key only if the earlier ones are)
+            const int adv = ((j1 <= n && v1 < key[i]) ? 1 : 0) + ((j2 <= n && v2 < key[i]) ? 1 : 0) +
+                            ((j3 <= n && v3 < key[i]) ? 1 : 0);
+            lb[i] += adv * step;
         }
     }
 }
@@ -458,8 +480,9 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 int r0 = 0;
                 // a long run is searched four blocks at a time (the chains of LDS reads
                 // overlap), a short one block by block (more wavefronts share it)
-                for (; nt > 8 * NACHO_WAVE && r0 + 2 * NACHO_WAVE < nt; r0 += 4 * NACHO_WAVE, ++unit)
-                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 4, FMT == SPADD_DCSR>(w, t, u, r0, lane);
+                constexpr int kB = 4;
+                for (; nt > 8 * NACHO_WAVE && r0 + (kB / 2) * NACHO_WAVE < nt; r0 += kB * NACHO_WAVE, ++unit)
+                    if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, kB, FMT == SPADD_DCSR>(w, t, u, r0, lane);
                 for (; r0 < nt; r0 += NACHO_WAVE, ++unit)
                     if ((unit & (kWaves - 1)) == wave) rank_blocks<KeyT, 1, FMT == SPADD_DCSR>(w, t, u, r0, lane);
             }
