@@ -233,9 +233,24 @@ def bench_others(steps, warmup):
             work = int(tab["cost"][-1])                 # entries in the rows both operands store
             m_rows = int(tab["coord"][-1, 0])
             nbytes_m = work * 8 + rows * 4 + m_rows * 2 * 4 * len(ops) + n_mul * 8 + r_mul * 8
+            # what the remapped cost function buys (the paper's comparison of recursive and plain hierarchical
+            # partitioning, Section 5): the same number of partitions by the plain non-zero count, and
+            # the entries each of them would really coiterate (those in rows both operands store)
+            plain = nb.nacho_partition(ops, int(tab["P"]))
+            torch.cuda.synchronize()
+            pos_plain = plain["posn"].cpu().numpy()[:, :, 1]
+            both = np.intersect1d(cfg["ops"][0]["crd0"], cfg["ops"][1]["crd0"])
+            work_plain = np.zeros(int(tab["P"]), dtype=np.int64)
+            for t, m in enumerate(cfg["ops"]):
+                in_both = np.isin(m["crd0"], both)
+                cum = np.concatenate([[0], np.cumsum(np.repeat(in_both, np.diff(m["pos1"])), dtype=np.int64)])
+                work_plain += np.diff(cum[pos_plain[:, t]])
+            plain_balance = {"max": int(work_plain.max()), "mean": float(work_plain.mean()),
+                             "max_over_mean": float(work_plain.max() / max(work_plain.mean(), 1e-9))}
             record("F3_dcsr2", f"DCSR Hadamard product of the C4 matrices (recursive partitioning): {rows} stored "
                    f"rows, {m_rows} in both, {work} of {tot} input nnz coiterated, {n_mul} output nnz", fm, work,
                    nbytes_m, table=lambda: nb.workspace_parts(nb.OP_SPMUL, ops, nb.F32, wsm))
+            res["F3_dcsr2"]["balance_with_plain_nonzero_cost"] = plain_balance
             del outm, wsm
             # F4: the same two matrices as coordinate lists (COO + COO, COO Hadamard)
             cops = []
