@@ -144,6 +144,20 @@ def test_matrices_random(fmt, k):
             check(mats, shape, P, f"{fmt}{trial}")
 
 
+@pytest.mark.parametrize("k", [2, 3, 5, 8])
+def test_dcsr_short_rows_many_operands(k):
+    """Rows of one to three entries, shared by many operands, equal sizes (every run searches and
+    is searched): where a row of the output starts is settled by the searches of the ranking."""
+    rng = np.random.default_rng(70 + k)
+    for shape, dens in (((6000, 3), 0.5), ((3000, 8), 0.3), ((20000, 2), 0.2)):
+        mats = []
+        for t in range(k):
+            c = random_coords(rng, shape, int(dens * shape[0] * shape[1]))
+            mats.append((c, rng.uniform(-1, 1, c.shape[0]).astype(np.float32)))
+        for P in (0, 3, 50):
+            check_dcsr(mats, shape, P, f"short rows {shape}")
+
+
 def test_degenerate_matrices():
     rng = np.random.default_rng(9)
     z = np.zeros((0, 2), np.int64)
