@@ -252,6 +252,19 @@ int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Debug aid, not part of the hot path: checks on the device the preconditions
+ * that the other entry points rely on without looking -- pos arrays start at 0,
+ * never decrease and end at the level's count; coordinates lie inside the
+ * extents and ascend strictly inside every segment (coordinate lists: the
+ * (row, column) pairs ascend strictly).  Enqueues only.  *status (device)
+ * becomes NACHO_OK or NACHO_ERR_INVALID_ARG; info (device int64[3], may be
+ * NULL) = {operand, level, position} of one violation, {-1, -1, -1} if none.
+ * The return value covers what the host can see (null pointers, kinds, counts).
+ */
+int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status /* device */,
+                       int64_t *info /* device */, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the hot path).  While enabled,
  * every fused call brackets each of its kernels with HIP events on the call's
  * stream.  nacho_profile_read synchronises on those events and returns the

@@ -25,7 +25,7 @@ MAX_OPERANDS, MAX_LEVELS = 8, 3
 EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
     "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
-    "nacho_profile_enable", "nacho_profile_read",
+    "nacho_validate", "nacho_profile_enable", "nacho_profile_read",
 ]
 
 
@@ -84,6 +84,7 @@ def lib():
         L.nacho_workspace_parts.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
+        L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -326,6 +327,19 @@ def nacho_spmul_k(ops, out: SparseOut, P=0, ws=None):
     _check(lib().nacho_spmul_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
                                ws.numel(), _stream()), "nacho_spmul_k")
     return out
+
+
+def nacho_validate(ops):
+    """Checks the operands' preconditions on the device.  Returns (status, (operand, level, position))
+    after synchronising: status 0, or -1 with the place of one violation."""
+    dev = ops[0].keep[0].device
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    info = torch.zeros(3, dtype=torch.int64, device=dev)
+    arr = _pack(ops)
+    _check(lib().nacho_validate(C.cast(arr, C.c_void_p), len(ops), _ptr(status), _ptr(info), _stream()),
+           "nacho_validate")
+    torch.cuda.synchronize()
+    return int(status.cpu()[0]), tuple(int(v) for v in info.cpu())
 
 
 def profile_enable(on: bool):

@@ -17,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libnacho.so")
 
-SOURCES = ["api.hip", "partition.hip", "spmv.hip", "spmm.hip", "spadd.hip", "remap.hip"]
+SOURCES = ["api.hip", "partition.hip", "spmv.hip", "spmm.hip", "spadd.hip", "remap.hip", "validate.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -625,6 +625,17 @@ int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     return sparse_combine(true, ops, k, dtype, P, out, ws, ws_bytes, hip_stream);
 }
 
+int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status, int64_t *info, void *hip_stream)
+{
+    if (!status) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    int32_t rc = check_operands(ops, k, true, &dev, &total, nullptr);
+    if (rc != NACHO_OK) return rc;
+    if (launch_validate(dev, status, info, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return NACHO_ERR_HIP;
+    return NACHO_OK;
+}
+
 int32_t nacho_profile_enable(int32_t on)
 {
     profiler().enabled = on != 0;

@@ -94,4 +94,7 @@ hipError_t launch_compact_rows(int64_t M, const RemapArrays &r, const int32_t *p
                                int64_t *info, int32_t *tsum, hipStream_t s);
 hipError_t launch_empty_result(const SpaddOut &out, int64_t *info, hipStream_t s);
 
+// ---- debug aid: the preconditions of the operands, checked on the device -----------
+hipError_t launch_validate(const DevOperands &ops, int32_t *status, int64_t *info, hipStream_t s);
+
 }  // namespace nacho
