@@ -12,8 +12,13 @@
  *                       Section 4.2.2, second listing);
  *   - nacho_spadd_k   : partition -> assembly (count) -> prefix sum -> compute
  *                       (Section 4.3, 4.4, pipeline of Figure 7(a)) for the
- *                       k-operand union of sparse vectors, CSR or DCSR matrices
- *                       (Section 2.1, 2.2).
+ *                       k-operand union of sparse vectors, CSR, DCSR or COO
+ *                       matrices (Section 2.1, 2.2);
+ *   - nacho_spmul_k   : the same pipeline for the k-operand intersection with
+ *                       products (Section 2.1); DCSR operands intersect on the
+ *                       outer level and take the recursive partitioning of
+ *                       Section 3.3 (Algorithm 2);
+ *   - nacho_validate  : debug aid, checks the preconditions below on the device.
  *
  * Conventions that hold for every entry point
  *   * Descriptor structs (nacho_tensor, nacho_parts, nacho_sparse_out) live in
@@ -23,7 +28,9 @@
  *     caller.  The library allocates and frees nothing; scratch memory comes
  *     from the `ws` argument, sized by nacho_workspace_bytes().
  *   * A call only enqueues kernels on `hip_stream` (a hipStream_t passed as
- *     void*; NULL is the default stream) and returns without synchronising.
+ *     void*; NULL is the default stream) and returns without synchronising
+ *     (one exception: nacho_spmul_k on DCSR operands waits once, see there;
+ *     nacho_workspace_parts for that call reads one word back).
  *   * Indices and positions are int32; costs are int64.  Preconditions (not
  *     checked): coordinates sorted and unique inside each segment, `pos`
  *     non-decreasing with pos[0] = 0, sum of the operands' nnz < 2^31, all
@@ -142,8 +149,10 @@ const char *nacho_status_string(int32_t status);
 /* Number of partitions a fused call uses for these operands (host descriptors;
  * only counts/extents are read) when the caller asks for `P` (0 = automatic).
  * Fused calls never use fewer partitions than needed for one partition's work
- * to fit the staging buffer of its wavefront (SpMV, SpMM) or workgroup (SpAdd), so the result is >= P.  `n_dense`:
- * SpMM's dense extent (0 otherwise).  Returns 0 on bad input. */
+ * to fit the staging buffer of its wavefront (SpMV, SpMM) or workgroup (SpAdd,
+ * SpMul), so the result is >= P.  For a DCSR product it is an upper bound (the
+ * count depends on the rows the operands share).  `n_dense`: SpMM's dense
+ * extent (0 otherwise).  Returns 0 on bad input. */
 int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                              int64_t n_dense, int64_t P);
 
