@@ -163,7 +163,7 @@ def bench_spmv(args):
     }
 
 
-def bench_others(steps, warmup):
+def bench_others(steps, warmup, only=None):
     """Configurations 3, 4 and 5 of the benchmark spec, one fused call per step, same timing
     protocol; algorithmic bytes = every input array once + every output array once."""
     import torch
@@ -192,7 +192,10 @@ def bench_others(steps, warmup):
             res[tag]["balance"] = {"partitions": int(work.shape[0]), "max": int(work.max()),
                                    "mean": float(work.mean()), "max_over_mean": float(work.max() / work.mean())}
 
+    want = lambda tag: only is None or tag in only
     for c, fmt in ((3, "vector"), (4, "dcsr")):
+        if not want(f"C{c}"):
+            continue
         cfg = workloads.config(c)
         if fmt == "vector":
             ops = [nb.vector(dev(v["i"]), v["extent"], dev(v["v"])) for v in cfg["ops"]]
@@ -274,6 +277,8 @@ def bench_others(steps, warmup):
             del cops, outc, wsc
         del ops, out, ws, cfg
     for kk in (2, 3):
+        if not want(f"F1_k{kk}"):
+            continue
         cfg = workloads.csr_add_config(kk)
         ops = [nb.csr(dev(m["pos"]), dev(m["crd"]), m["n_rows"], m["n_cols"], dev(m["val"])) for m in cfg["ops"]]
         tot = sum(o.nnz for o in ops)
@@ -294,6 +299,8 @@ def bench_others(steps, warmup):
             record("F2_csr2", f"CSR Hadamard product of the same two matrices, {tot} input nnz, {n_mul} output nnz",
                    fm, tot, tot * 8 + n_mul * 8 + 3 * (cfg["n_rows"] + 1) * 4)
         del ops, out, ws, cfg
+    if not want("C5"):
+        return res
     cfg = workloads.config(5)
     A = cfg["A"]
     op = nb.csr(dev(A["pos"]), dev(A["crd"]), A["n_rows"], A["n_cols"], dev(A["val"]))
@@ -315,6 +322,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--headline-only", action="store_true",
                     help="time configuration 2 only (skip the other configurations)")
+    ap.add_argument("--only", default=None,
+                    help="comma-separated workload tags (C3, C4, C5, F1_k2, F1_k3): time only these, "
+                         "print their records and skip the headline (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run two device-to-device copies of 256 MiB (a kernel of known "
                          "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -325,6 +335,9 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.only:
+        print(json.dumps({"workloads": bench_others(args.steps, args.warmup, set(args.only.split(",")))}))
+        return
     out = bench_spmv(args)
     if not args.headline_only:
         out["workloads"] = bench_others(max(5, args.steps // 5), 2)
