@@ -57,7 +57,8 @@ typedef enum {
     NACHO_ERR_UNSUPPORTED = -2, /* level formats / operand count outside what is implemented      */
     NACHO_ERR_WORKSPACE = -3,   /* ws_bytes smaller than nacho_workspace_bytes() reports           */
     NACHO_ERR_CAPACITY = -4,    /* sparse output larger than the caller's capacity                 */
-    NACHO_ERR_HIP = -5          /* a HIP call failed                                               */
+    NACHO_ERR_HIP = -5,         /* a HIP call failed                                               */
+    NACHO_ERR_TOO_LARGE = -6    /* nacho_spmv_static: the call needs more than the built-in scratch */
 } nacho_status;
 
 typedef enum { NACHO_F32 = 0, NACHO_F64 = 1 } nacho_dtype;
@@ -209,6 +210,25 @@ int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, in
  */
 int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * nacho_spmv for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc).  Same operation, arguments, results and status codes as nacho_spmv,
+ * but the partition table and the carries live in a scratch array that is part of
+ * the library's code object (one copy per GPU, nacho_static_scratch_bytes() bytes,
+ * held until the process ends) instead of a caller's workspace.  The call
+ * allocates and frees nothing and only enqueues.  A matrix whose partitions do
+ * not fit that array (about 36 bytes per partition, i.e. per 512 fp64 / 1024 fp32
+ * non-zeros, or per requested partition when P is given) is refused with
+ * NACHO_ERR_TOO_LARGE before anything is launched.  All calls on one GPU share
+ * the array: two calls that overlap in time on one GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  The first call on a
+ * device looks the array's address up (hipGetSymbolAddress), once.
+ */
+int32_t nacho_spmv_static(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
+                          void *hip_stream);
+size_t nacho_static_scratch_bytes(void);
 
 /*
  * C = A B with A in CSR and B, C dense row-major (loop order i -> j -> k, dense

@@ -25,7 +25,8 @@ MAX_OPERANDS, MAX_LEVELS = 8, 3
 EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
     "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
-    "nacho_validate", "nacho_profile_enable", "nacho_profile_read",
+    "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
+    "nacho_static_scratch_bytes",
 ]
 
 
@@ -76,6 +77,8 @@ def lib():
                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
                                  C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nacho_spmv_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p]
+        L.nacho_static_scratch_bytes.restype = C.c_size_t
         L.nacho_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spadd_k.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
@@ -264,6 +267,19 @@ def nacho_spmv(A: Operand, x, y=None, P=0, ws=None):
     _check(lib().nacho_spmv(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dt, P, _ptr(ws),
                             ws.numel(), _stream()), "nacho_spmv")
     return y
+
+
+def nacho_spmv_static(A: Operand, x, y, P=0):
+    """y = A x on the library's built-in scratch memory: no workspace, nothing allocated (y is the
+    caller's)."""
+    arr = _pack([A])
+    _check(lib().nacho_spmv_static(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dtype_code(x.dtype), P,
+                                   _stream()), "nacho_spmv_static")
+    return y
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().nacho_static_scratch_bytes())
 
 
 def nacho_spmm(A: Operand, B, Cout=None, P=0, ws=None):

@@ -1,6 +1,7 @@
 // C-ABI entry points: argument checks, workspace carving, kernel sequencing.
 // Nothing here computes; every step of the hot path runs in the kernels.
 #include <cstring>
+#include <mutex>
 
 #include "common.hpp"
 #include "kernels.hpp"
@@ -237,6 +238,61 @@ RemapWs carve_remap(void *ws, const nacho_tensor *ops, int k, int32_t dtype, int
     return w;
 }
 
+
+// The three launches of y = A x on a carved workspace (caller's or the built-in one).
+int32_t spmv_enqueue(const nacho_tensor *A, const DevOperands &dev, int64_t nnz, const void *x, void *y,
+                     int32_t dtype, int64_t P, int64_t Pe, const CarryWs &w, hipStream_t s)
+{
+    const int64_t n_rows = A->lvl[0].extent;
+    profile_begin(s);
+    const int64_t grain = (P == 0) ? spmv_capacity(dtype) : 0;
+    // (the partition kernel also writes the zeros of the rows A stores nothing in)
+    ZeroRows zero;
+    zero.base = y;
+    zero.ld = 1;
+    zero.width = 1;
+    zero.elem = (int32_t)dtype_size(dtype);
+    if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s, nullptr, 0,
+                         nullptr, &zero) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
+                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, grain, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_exec");
+    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_fixup");
+    return NACHO_OK;
+}
+
+// Scratch memory of nacho_spmv_static: one array per GPU inside the loaded code object, alive
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address on the current device is looked up once per device and
+// that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(void **base)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return NACHO_ERR_HIP;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NACHO_ERR_HIP;
+        g_scratch_ptr[device] = p;
+    }
+    *base = g_scratch_ptr[device];
+    return NACHO_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -252,6 +308,7 @@ const char *nacho_status_string(int32_t status)
     case NACHO_ERR_WORKSPACE: return "workspace too small";
     case NACHO_ERR_CAPACITY: return "output capacity too small";
     case NACHO_ERR_HIP: return "HIP call failed";
+    case NACHO_ERR_TOO_LARGE: return "operands need more than the built-in scratch memory of the no-allocation entry point";
     default: return "unknown status";
     }
 }
@@ -406,32 +463,37 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
     if (rc != NACHO_OK) return rc;
     if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
     if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
-    const int64_t n_rows = A->lvl[0].extent;
     const int64_t Pe = fused_partitions(NACHO_OP_SPMV, fmt, dtype, 1, nnz, P);
     CarryWs w = carve_carry(ws, Pe, dtype, 1);
     if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    profile_begin(s);
-    const int64_t grain = (P == 0) ? spmv_capacity(dtype) : 0;
-    // (the partition kernel also writes the zeros of the rows A stores nothing in)
-    ZeroRows zero;
-    zero.base = y;
-    zero.ld = 1;
-    zero.width = 1;
-    zero.elem = (int32_t)dtype_size(dtype);
-    if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s, nullptr, 0,
-                         nullptr, &zero) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("partition");
-    if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
-                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, grain, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spmv_exec");
-    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spmv_fixup");
-    return NACHO_OK;
+    return spmv_enqueue(A, dev, nnz, x, y, dtype, P, Pe, w, static_cast<hipStream_t>(hip_stream));
 }
+
+int32_t nacho_spmv_static(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
+                          void *hip_stream)
+{
+    if (!A || !x || !y || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &nnz, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = fused_partitions(NACHO_OP_SPMV, fmt, dtype, 1, nnz, P);
+    // sizes first: nothing is touched when the call does not fit the built-in scratch memory
+    if (carve_carry(nullptr, Pe, dtype, 1).bytes > kStaticScratchBytes) return NACHO_ERR_TOO_LARGE;
+    void *base = nullptr;
+    rc = static_scratch(&base);
+    if (rc != NACHO_OK) return rc;
+    CarryWs w = carve_carry(base, Pe, dtype, 1);
+    // (every word of the table and of the carries that a kernel reads is written earlier in the
+    // same call, so nothing of the previous call's contents needs clearing)
+    return spmv_enqueue(A, dev, nnz, x, y, dtype, P, Pe, w, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t nacho_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb, void *C, int64_t ldc,
                    int32_t dtype, int64_t P, void *ws, size_t ws_bytes, void *hip_stream)
