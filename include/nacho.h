@@ -294,6 +294,25 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status /* de
                        int64_t *info /* device */, void *hip_stream);
 
 /*
+ * Per-wavefront measurements (not part of the hot path; benchmarks and tests of
+ * the load balance use it).  Only the instrumented build of the library
+ * (libnacho_instr.so, the same sources compiled with -DNACHO_INSTRUMENT) records
+ * anything; the ordinary build returns NACHO_ERR_UNSUPPORTED.  After
+ * nacho_instrument(records, capacity), wavefront i of every launch of an
+ * executing kernel (SpMV, SpMM: workgroup i; the merge kernel: workgroup i / 8,
+ * wavefront i % 8) overwrites record i < capacity of the caller's DEVICE buffer
+ * when it ends; records = NULL switches the log off.  A record is
+ * nacho_instrument_record_bytes() = 48 bytes:
+ *   uint64 t_begin, t_end   constant 100 MHz counter, comparable across the chip
+ *   uint64 cycles           shader clock cycles between the two
+ *   uint32 items, rows      stored non-zeros (merge kernel: merged places) and rows
+ *                           (merge kernel: output rows started) the wavefront worked on
+ *   uint32 hw_id, xcc_id    where it ran (HW_ID and XCC_ID hardware registers)
+ */
+int32_t nacho_instrument(void *records /* device */, int64_t capacity);
+int32_t nacho_instrument_record_bytes(void);
+
+/*
  * Per-kernel timing for benchmarks (not part of the hot path).  While enabled,
  * every fused call brackets each of its kernels with HIP events on the call's
  * stream.  nacho_profile_read synchronises on those events and returns the

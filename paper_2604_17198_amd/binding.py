@@ -26,7 +26,7 @@ EXPORTS = [
     "nacho_version", "nacho_status_string", "nacho_num_partitions", "nacho_workspace_bytes",
     "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
-    "nacho_static_scratch_bytes",
+    "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
 ]
 
 
@@ -57,17 +57,29 @@ class _SparseOut(C.Structure):
 
 
 _lib = None
+_libs = {}
+_instrumented = False
+
+
+def select_library(instrumented: bool):
+    """Route all calls to libnacho.so (default) or to libnacho_instr.so, the instrumented build."""
+    global _lib, _instrumented
+    _instrumented = bool(instrumented)
+    _lib = None
 
 
 def lib():
     """The loaded library; raises if it has not been built."""
     global _lib
+    if _lib is None and _instrumented in _libs:
+        _lib = _libs[_instrumented]
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        path = _build.LIB_INSTR if _instrumented else _build.LIB
+        if not os.path.exists(path):
             raise RuntimeError(
-                f"{_build.LIB} is missing: build it with `python -m paper_2604_17198_amd.build` "
+                f"{path} is missing: build it with `python -m paper_2604_17198_amd.build` "
                 "(the HIP path has no fallback)")
-        L = C.CDLL(_build.LIB)
+        L = C.CDLL(path)
         L.nacho_status_string.restype = C.c_char_p
         L.nacho_num_partitions.restype = C.c_int64
         L.nacho_num_partitions.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64]
@@ -88,6 +100,8 @@ def lib():
                                             C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
+        _libs[_instrumented] = L
         _lib = L
     return _lib
 
@@ -356,6 +370,21 @@ def nacho_validate(ops):
            "nacho_validate")
     torch.cuda.synchronize()
     return int(status.cpu()[0]), tuple(int(v) for v in info.cpu())
+
+
+WAVE_RECORD = [("t_begin", "<u8"), ("t_end", "<u8"), ("cycles", "<u8"), ("items", "<u4"), ("rows", "<u4"),
+               ("hw_id", "<u4"), ("xcc_id", "<u4")]
+
+
+def instrument(records, capacity=None):
+    """Instrumented library only: executing kernels log one WAVE_RECORD per wavefront into the
+    device uint8 tensor `records` (None: stop logging)."""
+    rb = int(lib().nacho_instrument_record_bytes())
+    if records is None:
+        _check(lib().nacho_instrument(None, 0), "nacho_instrument")
+        return
+    cap = records.numel() // rb if capacity is None else capacity
+    _check(lib().nacho_instrument(_ptr(records), cap), "nacho_instrument")
 
 
 def profile_enable(on: bool):

@@ -16,6 +16,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libnacho.so")
+# the same sources with -DNACHO_INSTRUMENT: every executing wavefront logs what it did (benchmarks, balance tests)
+LIB_INSTR = os.path.join(PKG, "libnacho_instr.so")
 
 SOURCES = ["api.hip", "partition.hip", "spmv.hip", "spmm.hip", "spadd.hip", "remap.hip", "validate.hip"]
 
@@ -35,9 +37,11 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(job) -> str:
+    src, instrumented = job
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + (".instr.o" if instrumented else ".o"))
+    extra = ["-DNACHO_INSTRUMENT"] if instrumented else []
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -52,17 +56,25 @@ def sources_present() -> list[str]:
     return [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
 
 
-def build(jobs: int = 4) -> str:
-    os.makedirs(OBJ, exist_ok=True)
-    srcs = sources_present()
-    with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, srcs))
-    tmp = LIB + f".{os.getpid()}.tmp"
+def _link(objs, lib):
+    tmp = lib + f".{os.getpid()}.tmp"
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
+
+
+def build(jobs: int = 8, instrumented: bool = True) -> str:
+    """Compiles libnacho.so and (unless instrumented=False) libnacho_instr.so."""
+    os.makedirs(OBJ, exist_ok=True)
+    srcs = sources_present()
+    work = [(s, False) for s in srcs] + ([(s, True) for s in srcs] if instrumented else [])
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(_compile, work))
+    _link(objs[:len(srcs)], LIB)
+    if instrumented:
+        _link(objs[len(srcs):], LIB_INSTR)
     return LIB
 
 
@@ -75,4 +87,4 @@ def is_stale() -> bool:
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(instrumented="--fast" not in sys.argv))

@@ -14,6 +14,12 @@ Profiler &profiler()
     return p;
 }
 
+nacho::WaveLog &wave_log()
+{
+    static nacho::WaveLog log = {nullptr, 0};
+    return log;
+}
+
 void profile_begin(hipStream_t s)
 {
     Profiler &p = profiler();
@@ -199,7 +205,7 @@ int64_t fused_partitions(int32_t op, Format fmt, int32_t dtype, int32_t k, int64
     int64_t cap;
     if (op == NACHO_OP_SPMV) cap = spmv_capacity(dtype);
     else if (op == NACHO_OP_SPMM) cap = spmm_capacity(dtype);
-    else cap = spadd_capacity(spadd_fmt(fmt)) - k;
+    else cap = spadd_capacity(spadd_fmt(fmt), dtype) - k;
     const int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
     return P > need ? P : need;
 }
@@ -697,6 +703,17 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status, int6
     if (launch_validate(dev, status, info, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return NACHO_ERR_HIP;
     return NACHO_OK;
 }
+
+int32_t nacho_instrument(void *records, int64_t capacity)
+{
+    if (!kInstrument) return NACHO_ERR_UNSUPPORTED;
+    if (capacity < 0 || (capacity > 0 && !records)) return NACHO_ERR_INVALID_ARG;
+    wave_log().rec = static_cast<WaveRecord *>(records);
+    wave_log().capacity = records ? capacity : 0;
+    return NACHO_OK;
+}
+
+int32_t nacho_instrument_record_bytes(void) { return (int32_t)sizeof(WaveRecord); }
 
 int32_t nacho_profile_enable(int32_t on)
 {

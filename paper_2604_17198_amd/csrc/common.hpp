@@ -108,6 +108,55 @@ __device__ inline int first_row_past(const int32_t *__restrict__ pos, int lo, in
     return lo;
 }
 
+// ---- instrumented build (-DNACHO_INSTRUMENT): what every wavefront did, and when -----------
+// The executing kernels take a log descriptor as their last argument.  In the ordinary build the
+// flag below is false and every use of it folds away; in the instrumented build lane 0 of
+// wavefront i of a launch fills record i (if the caller gave a buffer): the items and rows it
+// worked on, its first and last time stamp (constant 100 MHz counter, comparable across the
+// chip), its shader-clock cycles and where it ran.
+#ifdef NACHO_INSTRUMENT
+constexpr bool kInstrument = true;
+#else
+constexpr bool kInstrument = false;
+#endif
+struct WaveRecord {
+    unsigned long long t_begin, t_end;   // wall_clock64()
+    unsigned long long cycles;           // clock64() span
+    uint32_t items, rows;                // work items (stored non-zeros / merged places) and rows touched
+    uint32_t hw_id, xcc_id;              // HW_ID and XCC_ID registers of the wavefront
+};
+struct WaveLog {
+    WaveRecord *rec;
+    long long capacity;
+};
+struct WaveStamp { unsigned long long t, c; };
+__device__ inline WaveStamp wave_begin()
+{
+    WaveStamp s = {0ull, 0ull};
+    if (kInstrument) { s.t = wall_clock64(); s.c = clock64(); }
+    return s;
+}
+__device__ inline void wave_end(const WaveLog &log, long long index, const WaveStamp &s, uint32_t items,
+                                uint32_t rows)
+{
+    if (!kInstrument) return;
+    if (log.rec == nullptr || index >= log.capacity || lane_id() != 0) return;
+    WaveRecord r;
+    r.t_begin = s.t;
+    r.t_end = wall_clock64();
+    r.cycles = clock64() - s.c;
+    r.items = items;
+    r.rows = rows;
+    uint32_t hw = 0, xcc = 0;
+#ifdef NACHO_INSTRUMENT
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+#endif
+    r.hw_id = hw;
+    r.xcc_id = xcc;
+    log.rec[index] = r;
+}
+
 }  // namespace nacho
 
 // Host-side bookkeeping shared by the translation units.
@@ -128,5 +177,8 @@ void profile_begin(hipStream_t s);
 void profile_mark(const char *kernel_name);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Where the executing kernels of an instrumented build log their wavefronts (null otherwise).
+nacho::WaveLog &wave_log();
 
 }  // namespace nacho_host

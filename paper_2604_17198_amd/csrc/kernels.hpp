@@ -46,7 +46,6 @@ hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, 
 
 // ---- k-way union addition ---------------------------------------------------
 enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2, SPADD_COO = 3 };
-constexpr int kSpaddCap = 4096;         // entries of all operands one partition (workgroup) stages
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
 struct SpaddOut {
@@ -56,7 +55,8 @@ struct SpaddOut {
     int64_t *counts;
     int32_t *status;
 };
-int spadd_capacity(int fmt);
+// Entries of all operands one partition (workgroup) may hold.
+int spadd_capacity(int fmt, int dtype);
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
 // Count, prefix sum and fill in one kernel, one workgroup per partition.  `multiply`: the k-way

@@ -24,8 +24,9 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
                  const T *__restrict__ val, const T *__restrict__ B, int n, int64_t ldb,
                  T *__restrict__ C, int64_t ldc, const int32_t *__restrict__ coord,
                  const int32_t *__restrict__ posn, T *__restrict__ carry_val,
-                 int32_t *__restrict__ carry_row)
+                 int32_t *__restrict__ carry_row, WaveLog wlog)
 {
+    const WaveStamp stamp = wave_begin();
     __shared__ int32_t s_crd[G];
     __shared__ T s_val[G];
     __shared__ int32_t spos[RBLK + 1];
@@ -115,6 +116,7 @@ spmm_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     // row, a zero carry); every row after it up to the next partition is empty
     if (cur < next_first) store();
     if (lane == 0) carry_row[p] = has_head ? r0 : -1;
+    wave_end(wlog, blockIdx.x, stamp, (uint32_t)(n1 - n0), (uint32_t)nrows);
 }
 
 template <typename T>
@@ -177,11 +179,11 @@ hipError_t launch_spmm_exec(int dtype, const int32_t *pos, const int32_t *crd, c
     if (dtype == NACHO_F64)
         hipLaunchKernelGGL((spmm_exec_kernel<double, kGrain, kRows>), dim3((unsigned)P), dim3(NACHO_WAVE),
                            0, stream, pos, crd, (const double *)val, (const double *)B, n, ldb,
-                           (double *)C, ldc, coord, posn, (double *)carry_val, carry_row);
+                           (double *)C, ldc, coord, posn, (double *)carry_val, carry_row, nacho_host::wave_log());
     else
         hipLaunchKernelGGL((spmm_exec_kernel<float, kGrain, kRows>), dim3((unsigned)P), dim3(NACHO_WAVE),
                            0, stream, pos, crd, (const float *)val, (const float *)B, n, ldb,
-                           (float *)C, ldc, coord, posn, (float *)carry_val, carry_row);
+                           (float *)C, ldc, coord, posn, (float *)carry_val, carry_row, nacho_host::wave_log());
     return hipGetLastError();
 }
 

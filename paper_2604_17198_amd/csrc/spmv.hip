@@ -30,8 +30,9 @@ __global__ void __launch_bounds__(NACHO_WAVE)
 spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                  const T *__restrict__ val, const T *__restrict__ x, T *__restrict__ y,
                  int nnz, const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
-                 T *__restrict__ carry_val, int32_t *__restrict__ carry_row, int n_rows, int grain)
+                 T *__restrict__ carry_val, int32_t *__restrict__ carry_row, int n_rows, int grain, WaveLog wlog)
 {
+    const WaveStamp stamp = wave_begin();
     __shared__ T prod[G + 8];
     __shared__ int32_t spos[RBLK + 1];
 
@@ -156,6 +157,7 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
         }
     }
     if (lane == 0) carry_row[p] = has_head ? r0 : -1;
+    wave_end(wlog, blockIdx.x, stamp, (uint32_t)(n1 - n0), (uint32_t)nrows);
 }
 
 // Carry fix-up, one lane per partition.  The carries of a row sit in
@@ -261,12 +263,12 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
         hipLaunchKernelGGL((spmv_exec_kernel<double, kGrainF64, kRowsF64>), dim3((unsigned)P),
                            dim3(NACHO_WAVE), 0, stream, pos, crd, (const double *)val,
                            (const double *)x, (double *)y, (int)nnz, coord, posn,
-                           (double *)carry_val, carry_row, (int)n_rows, (int)grain);
+                           (double *)carry_val, carry_row, (int)n_rows, (int)grain, nacho_host::wave_log());
     else
         hipLaunchKernelGGL((spmv_exec_kernel<float, kGrainF32, kRowsF32>), dim3((unsigned)P),
                            dim3(NACHO_WAVE), 0, stream, pos, crd, (const float *)val,
                            (const float *)x, (float *)y, (int)nnz, coord, posn,
-                           (float *)carry_val, carry_row, (int)n_rows, (int)grain);
+                           (float *)carry_val, carry_row, (int)n_rows, (int)grain, nacho_host::wave_log());
     return hipGetLastError();
 }
 
