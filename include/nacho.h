@@ -302,7 +302,7 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status /* de
  * executing kernel (SpMV, SpMM: workgroup i; the merge kernel: workgroup i / 8,
  * wavefront i % 8) overwrites record i < capacity of the caller's DEVICE buffer
  * when it ends; records = NULL switches the log off.  A record is
- * nacho_instrument_record_bytes() = 48 bytes:
+ * nacho_instrument_record_bytes() = 40 bytes:
  *   uint64 t_begin, t_end   constant 100 MHz counter, comparable across the chip
  *   uint64 cycles           shader clock cycles between the two
  *   uint32 items, rows      stored non-zeros (merge kernel: merged places) and rows

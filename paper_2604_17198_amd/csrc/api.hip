@@ -178,6 +178,21 @@ SpaddWs carve_spadd(void *ws, int64_t P, int k, int d)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Compute units of the current device (256 on an MI355X), asked once.
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
 // Workspace of a DCSR product (recursive partitioning, Section 3.3)
 constexpr int64_t kRowGrain = 2048;     // level-0 coordinates of all operands per partition of the row loop
 struct RemapWs {
@@ -206,7 +221,14 @@ int64_t fused_partitions(int32_t op, Format fmt, int32_t dtype, int32_t k, int64
     if (op == NACHO_OP_SPMV) cap = spmv_capacity(dtype);
     else if (op == NACHO_OP_SPMM) cap = spmm_capacity(dtype);
     else cap = spadd_capacity(spadd_fmt(fmt), dtype) - k;
-    const int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
+    int64_t need = total_nnz > 0 ? ceil_div(total_nnz, cap) : 1;
+    if (P == 0 && op != NACHO_OP_SPMV && op != NACHO_OP_SPMM) {
+        // The merge kernel keeps spadd_resident() workgroups per compute unit, and its partitions all
+        // take about the same time: they run in rounds of that many workgroups per unit.  With the
+        // partition count a whole number of rounds the last round is as full as the others.
+        const int64_t round = (int64_t)compute_units() * spadd_resident();
+        if (need > round) need = ceil_div(need, round) * round;
+    }
     return P > need ? P : need;
 }
 

@@ -57,6 +57,8 @@ struct SpaddOut {
 };
 // Entries of all operands one partition (workgroup) may hold.
 int spadd_capacity(int fmt, int dtype);
+// Workgroups of the merge kernel that run on one compute unit at a time.
+int spadd_resident();
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
 // Count, prefix sum and fill in one kernel, one workgroup per partition.  `multiply`: the k-way

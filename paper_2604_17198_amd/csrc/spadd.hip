@@ -55,7 +55,10 @@ namespace {
 template <int FMT> struct KeyOf { typedef uint64_t type; };
 template <> struct KeyOf<SPADD_VECTOR> { typedef uint32_t type; };
 
-constexpr int kWaves = 8;                          // wavefronts per workgroup
+#ifndef NACHO_MERGE_WAVES
+#define NACHO_MERGE_WAVES 8
+#endif
+constexpr int kWaves = NACHO_MERGE_WAVES;           // wavefronts per workgroup
 constexpr int kThreads = kWaves * NACHO_WAVE;
 constexpr int kMaxRuns = NACHO_MAX_OPERANDS;
 constexpr int kSlack = 4 * kMaxRuns;               // sentinels, gaps left by merged runs, reads past the last run
@@ -65,10 +68,10 @@ constexpr int kSlack = 4 * kMaxRuns;               // sentinels, gaps left by me
 
 // Places of the merged order a thread owns.  Odd: thread i's places start at word
 // i * kIpt of the LDS arrays, and an odd stride spreads the lanes of a wavefront
-// over all banks.  Chosen so that three (64-bit keys) or four (32-bit keys, 32-bit values)
-// workgroups fit the LDS of a compute unit.
+// over all banks.  Chosen so that three workgroups fit the LDS of a compute unit (the
+// scalar registers of the kernel allow no more than three anyway).
 template <typename KeyT, typename T> struct Shape {
-    static constexpr int kIpt = (sizeof(KeyT) + sizeof(T) <= 8) ? 9 : 7;
+    static constexpr int kIpt = (sizeof(KeyT) + sizeof(T) <= 8) ? 11 : 7;
     static constexpr int kTile = kThreads * kIpt;
     // entries a partition may hold: every round of pairwise merges hands out whole threads per pair
     // (at most kMaxRuns / 2 pairs), and all of them must fit the workgroup
@@ -89,7 +92,7 @@ constexpr int kChunk = 512;           // workgroups per chunk
 constexpr int kSpinLimit = 1 << 14;   // polls (each a sleep + one round trip to memory: tens of milliseconds in all)
 constexpr unsigned kWordValid = 0x80000000u;
 constexpr unsigned long long kTotalValid = 1ull << 63;
-static_assert(kThreads * 9 < (1 << 14), "a partition's counts fit the 14-bit fields of its word");
+static_assert(kThreads * 11 < (1 << 14), "a partition's counts fit the 14-bit fields of its word");
 
 __device__ inline unsigned long long pack_counts(long long rows, long long nnz)
 {
@@ -131,6 +134,7 @@ struct Tile {
     uint32_t wave_x[kWaves];              // per-wavefront partial of a scan across the workgroup
     long long base_nnz, base_rows;        // output offsets of the partition (known after the prefix sum)
     uint32_t tile_cnt;                    // emitted entries | rows started of the partition
+    uint32_t early_hits;                  // early count: entries found to repeat a key (union) / found everywhere (product)
     int32_t gave_up;
 };
 
@@ -196,6 +200,21 @@ __device__ inline void merge_share(const char *kb, const char *vb, int sx, int n
         xk = tx ? nk : xk;
         yk = tx ? yk : nk;
     }
+}
+
+
+// Number of keys of the sorted run keys[s, s + n) (followed by its sentinel) that are
+// smaller than `key` (n >= 1): binary lifting, `bits` >= number of bits of n.
+template <typename KeyT>
+__device__ inline int run_lower_bound(const KeyT *keys, int s, int n, int bits, KeyT key)
+{
+    int pos = 0;
+    for (int step = 1 << (bits - 1); step > 0; step >>= 1) {
+        const int cand = pos + step;
+        const int at = cand < n ? cand : n;
+        pos = keys[s + at - 1] < key ? at : pos;
+    }
+    return pos;
 }
 
 // kMul: the k-way intersection with products (an entry is emitted when all k
@@ -414,7 +433,66 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     if (tid == K) keys[0] = kSentinel;
     bool cont = false;                     // the partition starts inside a row whose head is elsewhere
     if (D == 2 && !kCoo) cont = row_continues<FMT>(ops, coord, posn, p);
+    if (tid == 0) w.early_hits = 0;
     __syncthreads();
+
+    // ---- 1b. the partition's output count, early, when it is cheap to get -----------------
+    // The workgroups behind this one wait for its count (stage 4), so it is worth knowing before the
+    // merge: the union emits one entry per DISTINCT key, n minus the entries whose key an earlier
+    // run stores as well (or: a later run -- whichever direction needs fewer look-ups); the product
+    // emits the entries of the shortest run that every other run stores.  Each such entry costs one
+    // binary search per other run; done only when that is at most two searches per thread (one
+    // operand dominates the partition), otherwise the count is published after the assembly.
+    bool published = false;                // (uniform)
+    if (FMT != SPADD_DCSR) {
+        int cost_fwd = 0, cost_bwd = 0, n_min = n, t_min = 0;
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
+            const int nt = off[t + 1] - off[t];
+            cost_fwd += nt * t;
+            cost_bwd += t < k ? nt * (k - 1 - t) : 0;
+            if (t < k && nt < n_min) { n_min = nt; t_min = t; }
+        }
+        const bool fwd = cost_fwd <= cost_bwd;
+        const int cost = kMul ? n_min * (k - 1) : (fwd ? cost_fwd : cost_bwd);
+        if (cost <= 2 * kThreads) {
+            published = true;
+            uint32_t hits = 0;
+#pragma unroll
+            for (int t = 0; t < K; ++t) {
+                if (t >= k) break;
+                const int nt = off[t + 1] - off[t];
+                if (kMul ? t != t_min : (fwd ? t == 0 : t == k - 1)) continue;      // (uniform)
+                for (int i0 = 0; i0 < nt; i0 += kThreads) {
+                    const int i = i0 + tid;
+                    const KeyT key = keys[off[t] + t + 1 + (i < nt ? i : 0)];
+                    bool any = false, all = true;
+#pragma unroll
+                    for (int u = 0; u < K; ++u) {
+                        if (u >= k || u == t) continue;
+                        if (!kMul && (fwd ? u > t : u < t)) continue;
+                        const int nu = off[u + 1] - off[u];
+                        bool hit = false;
+                        if (nu > 0) {                                              // (uniform)
+                            const int bits = 32 - __builtin_clz((unsigned)nu);
+                            const int at = run_lower_bound<KeyT>(keys, off[u] + u + 1, nu, bits, key);
+                            hit = keys[off[u] + u + 1 + at] == key;                // (past the run: its sentinel)
+                        }
+                        any = any || hit;
+                        all = all && hit;
+                    }
+                    hits += (uint32_t)__popcll(__ballot(i < nt && (kMul ? all : any)));
+                }
+            }
+            if (lane == 0 && hits) atomicAdd(&w.early_hits, hits);
+            __syncthreads();
+            if (tid == 0) {
+                const uint32_t e = kMul ? w.early_hits : (uint32_t)n - w.early_hits;
+                unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);
+                __hip_atomic_store(&words[p], kWordValid | e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
 
     // ---- 2. merge: adjacent runs pairwise, in rounds, in place -------------------
     // (all of this is uniform over the workgroup except the thread's own share)
@@ -580,7 +658,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         const long long t_nnz = (long long)(tile_cnt & 0xffffu), t_rows = (long long)(tile_cnt >> 16);
         unsigned long long *totals = tile_state;                                        // one per chunk
         unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
-        if (lane == 0)
+        if (lane == 0 && !published)
             __hip_atomic_store(&words[p], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         long long b_rows = 0, b_nnz = 0;
@@ -762,6 +840,10 @@ hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P
 }
 
 }  // namespace
+
+// Workgroups of the merge kernel a compute unit holds at a time: its registers allow seven
+// wavefronts per SIMD.
+int spadd_resident() { return 28 / kWaves; }
 
 int spadd_capacity(int fmt, int dtype)
 {
