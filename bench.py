@@ -9,11 +9,16 @@ power-law CSR SpMV (2M x 2M, ~50M nnz, fp64), inputs resident in HBM.
 Extra objects on the line:
   roofline      dominant kernel's algorithmic bytes / its measured duration vs
                 the 8 TB/s HBM peak (durations from HIP events recorded by the
-                library around each kernel on the launch stream)
+                library around each kernel on the launch stream), and vs the
+                streaming-read ceiling measured in the same run
+  ceilings      this GPU's own streaming read, copy and independent-gather rates,
+                measured in the same run with the library's probe kernels
   cpu_baseline  the serial CPU oracle timed on this machine's host cores
-  balance       max/mean work per wavefront from the partition table
-  workloads     throughput of the other configurations (one call each, same
-                protocol), for context
+  balance       max/mean work per wavefront: from the partition table, and
+                measured (items, items + rows, cycles per wavefront) with the
+                instrumented build of the library
+  workloads     the other configurations (one call each, same protocol), each
+                with its own roofline object
 """
 from __future__ import annotations
 
@@ -31,16 +36,15 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 
 
-def _traffic(kernel: str, workload: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-    recorded in profiles/traffic.json; None when no measurement is committed."""
+def _traffic_entry(kernel: str, workload: str):
+    """HBM/fabric bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), recorded in
+    profiles/traffic.json with the commit they were measured on; None when nothing is committed."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
         return None
     with open(path) as f:
         t = json.load(f)
-    e = t.get(f"{kernel}@{workload}")
-    return None if e is None else e.get("bytes_per_launch")
+    return t.get(f"{kernel}@{workload}")
 
 
 def _time_steps(fn, steps, warmup):
@@ -91,7 +95,80 @@ def _paper_protocol(fn):
     return float(np.mean(ts))
 
 
-def bench_spmv(args):
+def _measured_balance(fn, n_waves):
+    """One call through the instrumented build of the library: what every wavefront of the
+    executing kernel really worked on (its item and row counters) and how long it took."""
+    import torch
+    from paper_2604_17198_amd import binding as nb
+    rb = np.dtype(nb.WAVE_RECORD).itemsize
+    nb.select_library(True)
+    try:
+        fn()                                    # (first use of the instrumented code object)
+        torch.cuda.synchronize()
+        rec = torch.zeros(n_waves * rb, dtype=torch.uint8, device="cuda")
+        nb.instrument(rec)
+        fn()
+        torch.cuda.synchronize()
+        nb.instrument(None)
+        r = rec.cpu().numpy().view(np.dtype(nb.WAVE_RECORD))
+    finally:
+        nb.select_library(False)
+    r = r[r["t_begin"] > 0]
+    items = r["items"].astype(np.float64)
+    both = items + r["rows"].astype(np.float64)
+    cyc = r["cycles"].astype(np.float64)
+    busy = items > 0
+    span_us = float((r["t_end"].max() - r["t_begin"].min()) / 100.0)
+    return {"wavefronts": int(r.shape[0]), "items_total": int(items.sum()),
+            "items_max_over_mean": float(items.max() / items.mean()),
+            "items_plus_rows_max_over_mean": float(both.max() / both.mean()),
+            "cycles_max_over_mean": float(cyc[busy].max() / cyc[busy].mean()),
+            "cycles_mean": float(cyc[busy].mean()), "kernel_span_us": span_us}
+
+
+def measure_ceilings():
+    """Streaming read, copy and gather rates of this GPU (the library's probe kernels, HIP events)."""
+    import torch
+    from paper_2604_17198_amd import binding as nb
+    n = 512 * 1024 * 1024                                   # bytes
+    src = torch.ones(n // 8, dtype=torch.float64, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(2, dtype=torch.int64, device="cuda")
+    out = {}
+
+    def timed(fn, reps=10):
+        fn()
+        ms, _ = _time_steps(fn, reps, 2)
+        return ms
+
+    ms = timed(lambda: nb.probe(nb.PROBE_READ, sink, src, n))
+    out["stream_read_GBps"] = n / ms / 1e6
+    ms = timed(lambda: nb.probe(nb.PROBE_COPY, dst, src, n))
+    out["copy_GBps_read_plus_write"] = 2 * n / ms / 1e6
+    g = 1 << 26
+    for label, window in (("gather_1MiB_window_Gper_s", 1 << 20), ("gather_16MiB_window_Gper_s", 1 << 24),
+                          ("gather_512MiB_window_Gper_s", n)):
+        ms = timed(lambda: nb.probe(nb.PROBE_GATHER, sink, src, window, g), 5)
+        out[label] = g / ms / 1e6
+    out["bytes"] = n
+    out["gathers"] = g
+    return out
+
+
+def _cpu_info():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return model, os.cpu_count()
+
+
+def bench_spmv(args, ceilings):
     import torch
     from paper_2604_17198_amd import binding as nb
     from paper_2604_17198_amd import workloads
@@ -122,21 +199,23 @@ def bench_spmv(args):
     torch.cuda.synchronize()
     parts = nb.workspace_parts(nb.OP_SPMV, [op], nb.F64, ws)
     work = np.diff(parts["cost"].cpu().numpy())
+    rows_touched = np.diff(parts["coord"].cpu().numpy()[:, 0].astype(np.int64)) + 1
+    both = work + rows_touched
     balance = {"partitions": int(P), "max_over_mean_nnz": float(work.max() / work.mean()),
-               "max": int(work.max()), "mean": float(work.mean())}
+               "max": int(work.max()), "mean": float(work.mean()),
+               "table_nnz_plus_rows_max_over_mean": float(both.max() / both.mean()),
+               "measured": _measured_balance(step, int(P))}
 
-    # parity spot check of the timed configuration (full vector, oracle below)
+    # parity check of the timed configuration (full vector) and the oracle's own time
     import oracle
-    t0 = time.perf_counter()
-    ref, sabs = oracle.spmv(A["pos"], A["crd"], A["val"], cfg["x"])
-    best = time.perf_counter() - t0
-    for _ in range(2):
-        t0 = time.perf_counter()
-        oracle.spmv(A["pos"], A["crd"], A["val"], cfg["x"])
-        best = min(best, time.perf_counter() - t0)
+    best, ref, sabs = oracle.time_spmv_native(A["pos"], A["crd"], A["val"], cfg["x"], reps=3)
+    step()
+    torch.cuda.synchronize()
     got = y.cpu().numpy()
     ok = bool(np.all(np.abs(got - ref) <= 1e-12 * np.maximum(np.abs(ref), sabs)))
+    cpu_model, nproc = _cpu_info()
 
+    tr = _traffic_entry("spmv_exec", "C2")
     return {
         "metric": "nnz/s (balanced CSR SpMV, partitioning included)",
         "value": nnz / (ms * 1e-3),
@@ -155,15 +234,22 @@ def bench_spmv(args):
         "roofline": {"bound": "hbm", "kernel": "spmv_exec", "achieved": achieved, "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
                      "algorithmic_bytes_per_launch": exec_bytes,
-                     "traffic": _traffic("spmv_exec", "C2")},
+                     "traffic": None if tr is None else tr.get("bytes_per_launch"),
+                     "traffic_measured_on_commit": None if tr is None else tr.get("commit"),
+                     "ceiling_GBps": ceilings["stream_read_GBps"],
+                     "frac_of_ceiling": achieved / ceilings["stream_read_GBps"],
+                     "gathers_per_launch": nnz,
+                     "gather_rate_Gper_s": nnz / exec_ms / 1e6,
+                     "gather_ceiling_16MiB_Gper_s": ceilings["gather_16MiB_window_Gper_s"]},
         "balance": balance,
         "cpu_baseline": {"value": nnz / best, "unit": "nnz/s", "cores": 1, "kind": "oracle",
-                         "seconds": best,
+                         "seconds": best, "nproc": nproc, "cpu_model": cpu_model,
+                         "build": "gcc -O3 -march=native (this host), timed in C with CLOCK_MONOTONIC",
                          "sample": "the whole C2 matrix, best of 3 runs of the serial long-double oracle"},
     }
 
 
-def bench_others(steps, warmup, only=None):
+def bench_others(steps, warmup, only=None, ceilings=None):
     """Configurations 3, 4 and 5 of the benchmark spec, one fused call per step, same timing
     protocol; algorithmic bytes = every input array once + every output array once."""
     import torch
@@ -173,24 +259,36 @@ def bench_others(steps, warmup, only=None):
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
     res = {}
 
-    def record(tag, what, fn, nnz, nbytes, table=None):
+    def record(tag, what, fn, nnz, nbytes, table=None, main_kernel=None, waves=0, note=None):
         ms, _ = _time_steps(fn, steps, warmup)
+        kms = _kernel_ms(fn, 5)
         res[tag] = {"workload": what, "ms_per_step": ms, "nnz_per_s": nnz / (ms * 1e-3),
                     "GBps_algorithmic": nbytes / ms / 1e6,
                     "frac_of_hbm_peak": nbytes / ms / 1e6 / PEAK_HBM_GBS,
-                    "kernel_ms": _kernel_ms(fn, 5)}
-        # measured HBM bytes per launch of the call's kernels, where a rocprofv3 measurement is committed
-        tr = {k: _traffic(k, tag) for k in res[tag]["kernel_ms"]}
-        tr = {k: v for k, v in tr.items() if v is not None}
-        if tr:
-            res[tag]["traffic"] = tr
+                    "kernel_ms": kms}
+        if main_kernel is not None:
+            # the workload's own roofline object: its dominant kernel against the HBM peak and this GPU's ceiling
+            k_ms = kms[main_kernel]
+            tr = _traffic_entry(main_kernel, tag)
+            ach = nbytes / k_ms / 1e6
+            roof = {"bound": "hbm", "kernel": main_kernel, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": ach / PEAK_HBM_GBS, "algorithmic_bytes_per_launch": int(nbytes),
+                    "duration_ms": k_ms, "traffic": None if tr is None else tr.get("bytes_per_launch"),
+                    "traffic_measured_on_commit": None if tr is None else tr.get("commit")}
+            if ceilings is not None:
+                roof["ceiling_GBps"] = ceilings["copy_GBps_read_plus_write"]
+                roof["frac_of_ceiling"] = ach / ceilings["copy_GBps_read_plus_write"]
+            if note:
+                roof["note"] = note
+            res[tag]["roofline"] = roof
         if table is not None:
-            # work per partition from the table the fused call stored in its workspace (a partition is
-            # executed by one wavefront (SpMM) or dealt out evenly over the 8 wavefronts of a workgroup (SpAdd))
+            # work per partition from the table the fused call stored in its workspace
             torch.cuda.synchronize()
             work = np.diff(table()["cost"].cpu().numpy())
             res[tag]["balance"] = {"partitions": int(work.shape[0]), "max": int(work.max()),
                                    "mean": float(work.mean()), "max_over_mean": float(work.max() / work.mean())}
+            if waves:
+                res[tag]["balance"]["measured"] = _measured_balance(fn, waves)
 
     want = lambda tag: only is None or tag in only
     for c, fmt in ((3, "vector"), (4, "dcsr")):
@@ -214,8 +312,10 @@ def bench_others(steps, warmup, only=None):
         nbytes = tot * 8 + n_out * 8 + (rows * 8 + n_rows_out * 8 if fmt == "dcsr" else 0)
         what = ("C3: 3 sparse vectors (10M + 1M + 100k nnz, index space 2^30), fp32 union add" if c == 3 else
                 "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
+        P_add = nb.num_partitions(nb.OP_SPADD, ops, nb.F32)
         record(f"C{c}", what + f", {tot} input nnz, {n_out} output nnz", fn, tot, nbytes,
-               table=lambda: nb.workspace_parts(nb.OP_SPADD, ops, nb.F32, ws))
+               table=lambda: nb.workspace_parts(nb.OP_SPADD, ops, nb.F32, ws), main_kernel="spadd_merge",
+               waves=P_add * nb.merge_wavefronts())
         if c == 3:
             fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
             fm()
@@ -276,10 +376,10 @@ def bench_others(steps, warmup, only=None):
                    tot, tot * 12 + n_had * 12)
             del cops, outc, wsc
         del ops, out, ws, cfg
-    for kk in (2, 3):
+    for kk in (2, 3, 8):
         if not want(f"F1_k{kk}"):
             continue
-        cfg = workloads.csr_add_config(kk)
+        cfg = workloads.csr_add_config(kk) if kk < 8 else workloads.csr_add_config(kk, nnz_each=2_000_000)
         ops = [nb.csr(dev(m["pos"]), dev(m["crd"]), m["n_rows"], m["n_cols"], dev(m["val"])) for m in cfg["ops"]]
         tot = sum(o.nnz for o in ops)
         out = nb.SparseOut("csr", 0, tot, torch.float32, "cuda", n_rows=cfg["n_rows"])
@@ -289,8 +389,9 @@ def bench_others(steps, warmup, only=None):
         torch.cuda.synchronize()
         n_out = int(out.counts.cpu().numpy()[1])
         nbytes = tot * 8 + n_out * 8 + (kk + 1) * (cfg["n_rows"] + 1) * 4
-        record(f"F1_k{kk}", f"fused {kk}-way CSR add, power-law 100,000 x 100,000, 5M nnz each (shape of the paper's "
-               f"skew experiment), fp32, {tot} input nnz, {n_out} output nnz", fn, tot, nbytes)
+        record(f"F1_k{kk}", f"fused {kk}-way CSR add, power-law 100,000 x 100,000 (shape of the paper's "
+               f"skew experiment), fp32, {tot} input nnz, {n_out} output nnz", fn, tot, nbytes,
+               main_kernel="spadd_merge")
         if kk == 2:
             fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
             fm()
@@ -309,9 +410,12 @@ def bench_others(steps, warmup, only=None):
     ws = torch.empty(nb.workspace_bytes(nb.OP_SPMM, [op], nb.F32, 64), dtype=torch.uint8, device="cuda")
     nnz = int(A["pos"][-1])
     nbytes = nnz * 8 + (A["n_rows"] + 1) * 4 + A["n_cols"] * 64 * 4 + A["n_rows"] * 64 * 4
+    P5 = nb.num_partitions(nb.OP_SPMM, [op], nb.F32, 64)
     record("C5", f"C5: CSR (1,000,000 x 1,000,000, {nnz} nnz) x dense 1,000,000 x 64, fp32 SpMM",
            lambda: nb.nacho_spmm(op, B, C, ws=ws), nnz, nbytes,
-           table=lambda: nb.workspace_parts(nb.OP_SPMM, [op], nb.F32, ws, 64))
+           table=lambda: nb.workspace_parts(nb.OP_SPMM, [op], nb.F32, ws, 64), main_kernel="spmm_exec", waves=P5,
+           note="compulsory bytes (B and C once); the i -> j -> k order re-reads a 256-byte row of B per stored "
+                f"non-zero: {nnz * 256 / 1e9:.2f} GB through the fabric, which is what bounds this kernel")
     return res
 
 
@@ -323,7 +427,7 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="time configuration 2 only (skip the other configurations)")
     ap.add_argument("--only", default=None,
-                    help="comma-separated workload tags (C3, C4, C5, F1_k2, F1_k3): time only these, "
+                    help="comma-separated workload tags (C3, C4, C5, F1_k2, F1_k3, F1_k8): time only these, "
                          "print their records and skip the headline (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run two device-to-device copies of 256 MiB (a kernel of known "
@@ -338,9 +442,11 @@ def main():
     if args.only:
         print(json.dumps({"workloads": bench_others(args.steps, args.warmup, set(args.only.split(",")))}))
         return
-    out = bench_spmv(args)
+    ceilings = measure_ceilings()
+    out = bench_spmv(args, ceilings)
+    out["ceilings"] = ceilings
     if not args.headline_only:
-        out["workloads"] = bench_others(max(5, args.steps // 5), 2)
+        out["workloads"] = bench_others(max(5, args.steps // 5), 2, ceilings=ceilings)
     if args.calibrate_copy:
         a = torch.zeros(32 * 1024 * 1024, dtype=torch.float64, device="cuda")
         b = torch.empty_like(a)

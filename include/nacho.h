@@ -294,6 +294,19 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status /* de
                        int64_t *info /* device */, void *hip_stream);
 
 /*
+ * Machine ceilings for benchmarks (not part of the hot path): kernels of known
+ * traffic, timed by the caller on the same GPU in the same run.  Enqueues only.
+ *   NACHO_PROBE_READ    reads `bytes` of src once (dst: 8 writable device bytes)
+ *   NACHO_PROBE_COPY    copies `bytes` from src to dst
+ *   NACHO_PROBE_GATHER  `gathers` independent 8-byte loads at pseudo-random places
+ *                       of the first `bytes` of src (dst: 8 writable device bytes):
+ *                       what a row-major CSR SpMV does to x per stored non-zero
+ * src, dst: device, 16-byte aligned; bytes >= 16.
+ */
+typedef enum { NACHO_PROBE_READ = 0, NACHO_PROBE_COPY = 1, NACHO_PROBE_GATHER = 2 } nacho_probe_kind;
+int32_t nacho_probe(int32_t kind, void *dst, const void *src, size_t bytes, int64_t gathers, void *hip_stream);
+
+/*
  * Per-wavefront measurements (not part of the hot path; benchmarks and tests of
  * the load balance use it).  Only the instrumented build of the library
  * (libnacho_instr.so, the same sources compiled with -DNACHO_INSTRUMENT) records
@@ -311,6 +324,8 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status /* de
  */
 int32_t nacho_instrument(void *records /* device */, int64_t capacity);
 int32_t nacho_instrument_record_bytes(void);
+/* Wavefronts per workgroup (= per partition) of the merge kernel of nacho_spadd_k / nacho_spmul_k. */
+int32_t nacho_merge_wavefronts(void);
 
 /*
  * Per-kernel timing for benchmarks (not part of the hot path).  While enabled,

@@ -33,6 +33,28 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def time_spmv_native(pos, crd, val, x, reps=3):
+    """Benchmarks only: the same source compiled for THIS host (-O3 -march=native, into a temporary
+    file: the library that travels with the tree must run on any host) and timed in C with the
+    monotonic clock; returns (best seconds of `reps` runs of the fp64 SpMV, y, s)."""
+    import tempfile
+    path = os.path.join(tempfile.gettempdir(), f"libnacho_oracle_native_{os.getpid()}.so")
+    subprocess.check_call(["gcc", "-O3", "-march=native", "-std=c11", "-fPIC", "-shared", "-o", path, _SRC, "-lm"])
+    nat = C.CDLL(path)
+    nat.ora_time_spmv_f64.restype = C.c_double
+    pos, crd = _i32(pos), _i32(crd)
+    val = np.ascontiguousarray(val, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    n_rows = pos.shape[0] - 1
+    y = np.zeros(n_rows, dtype=np.float64)
+    s = np.zeros(n_rows, dtype=np.float64)
+    best = nat.ora_time_spmv_f64(C.c_int64(n_rows), pos.ctypes.data_as(C.c_void_p), crd.ctypes.data_as(C.c_void_p),
+                                 val.ctypes.data_as(C.c_void_p), x.ctypes.data_as(C.c_void_p),
+                                 y.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p), C.c_int32(reps))
+    os.remove(path)
+    return float(best), y, s
+
+
 class _Level(C.Structure):
     _fields_ = [("kind", C.c_int32), ("extent", C.c_int64),
                 ("pos", C.c_void_p), ("crd", C.c_void_p)]

@@ -1,3 +1,4 @@
+#define _POSIX_C_SOURCE 200809L
 /*
  * CPU oracle -- TEST INFRASTRUCTURE ONLY.
  *
@@ -774,4 +775,23 @@ int64_t ora_spmul_coo(int k, const int32_t *const *rows, const int32_t *const *c
                       int32_t *out_row, int32_t *out_col, double *out_val, double *out_abs)
 {
     return coo_merge(1, k, rows, cols, val, nnz, is_f64, out_row, out_col, out_val, out_abs);
+}
+
+/* Timing aid for benchmarks (no arithmetic of its own): runs ora_spmv_f64 `reps`
+ * times and returns the shortest duration in seconds, measured with the
+ * monotonic clock around the call. */
+#include <time.h>
+double ora_time_spmv_f64(int64_t n_rows, const int32_t *pos, const int32_t *crd, const double *val,
+                         const double *x, double *y, double *s, int32_t reps)
+{
+    double best = -1.0;
+    for (int32_t r = 0; r < reps; ++r) {
+        struct timespec a, b;
+        clock_gettime(CLOCK_MONOTONIC, &a);
+        ora_spmv_f64(n_rows, pos, crd, val, x, y, s);
+        clock_gettime(CLOCK_MONOTONIC, &b);
+        double t = (double)(b.tv_sec - a.tv_sec) + 1e-9 * (double)(b.tv_nsec - a.tv_nsec);
+        if (best < 0.0 || t < best) best = t;
+    }
+    return best;
 }

@@ -27,6 +27,7 @@ EXPORTS = [
     "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
     "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
+    "nacho_probe", "nacho_merge_wavefronts",
 ]
 
 
@@ -101,6 +102,7 @@ def lib():
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
+        L.nacho_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p]
         _libs[_instrumented] = L
         _lib = L
     return _lib
@@ -385,6 +387,18 @@ def instrument(records, capacity=None):
         return
     cap = records.numel() // rb if capacity is None else capacity
     _check(lib().nacho_instrument(_ptr(records), cap), "nacho_instrument")
+
+
+def merge_wavefronts() -> int:
+    return int(lib().nacho_merge_wavefronts())
+
+
+PROBE_READ, PROBE_COPY, PROBE_GATHER = 0, 1, 2
+
+
+def probe(kind, dst, src, nbytes, gathers=0):
+    """Enqueue one of the library's kernels of known traffic (see nacho_probe)."""
+    _check(lib().nacho_probe(kind, _ptr(dst), _ptr(src), nbytes, gathers, _stream()), "nacho_probe")
 
 
 def profile_enable(on: bool):

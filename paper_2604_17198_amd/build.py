@@ -19,7 +19,7 @@ LIB = os.path.join(PKG, "libnacho.so")
 # the same sources with -DNACHO_INSTRUMENT: every executing wavefront logs what it did (benchmarks, balance tests)
 LIB_INSTR = os.path.join(PKG, "libnacho_instr.so")
 
-SOURCES = ["api.hip", "partition.hip", "spmv.hip", "spmm.hip", "spadd.hip", "remap.hip", "validate.hip"]
+SOURCES = ["api.hip", "partition.hip", "spmv.hip", "spmm.hip", "spadd.hip", "remap.hip", "validate.hip", "probe.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

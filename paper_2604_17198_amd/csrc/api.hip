@@ -726,6 +726,24 @@ int32_t nacho_validate(const nacho_tensor *ops, int32_t k, int32_t *status, int6
     return NACHO_OK;
 }
 
+int32_t nacho_probe(int32_t kind, void *dst, const void *src, size_t bytes, int64_t gathers, void *hip_stream)
+{
+    if (!src || !dst || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u))
+        return NACHO_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    switch (kind) {
+    case NACHO_PROBE_READ: e = launch_probe_read(src, bytes, dst, s); break;
+    case NACHO_PROBE_COPY: e = launch_probe_copy(dst, src, bytes, s); break;
+    case NACHO_PROBE_GATHER:
+        if (gathers < 1) return NACHO_ERR_INVALID_ARG;
+        e = launch_probe_gather(src, bytes, gathers, dst, s);
+        break;
+    default: return NACHO_ERR_INVALID_ARG;
+    }
+    return e == hipSuccess ? NACHO_OK : NACHO_ERR_HIP;
+}
+
 int32_t nacho_instrument(void *records, int64_t capacity)
 {
     if (!kInstrument) return NACHO_ERR_UNSUPPORTED;
@@ -736,6 +754,8 @@ int32_t nacho_instrument(void *records, int64_t capacity)
 }
 
 int32_t nacho_instrument_record_bytes(void) { return (int32_t)sizeof(WaveRecord); }
+
+int32_t nacho_merge_wavefronts(void) { return spadd_wavefronts(); }
 
 int32_t nacho_profile_enable(int32_t on)
 {

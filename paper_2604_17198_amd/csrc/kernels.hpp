@@ -59,6 +59,8 @@ struct SpaddOut {
 int spadd_capacity(int fmt, int dtype);
 // Workgroups of the merge kernel that run on one compute unit at a time.
 int spadd_resident();
+// Wavefronts of one of its workgroups (the instrumented build logs one record per wavefront).
+int spadd_wavefronts();
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
 // Count, prefix sum and fill in one kernel, one workgroup per partition.  `multiply`: the k-way
@@ -95,6 +97,11 @@ hipError_t launch_compact_rows(int64_t M, const RemapArrays &r, const int32_t *p
                                const int64_t *counts_in, const SpaddOut &out, const int64_t *info_vals,
                                int64_t *info, int32_t *tsum, hipStream_t s);
 hipError_t launch_empty_result(const SpaddOut &out, int64_t *info, hipStream_t s);
+
+// ---- measurement aids: kernels of known traffic (streaming read, copy, independent gathers) ----
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t s);
+hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+hipError_t launch_probe_gather(const void *table, size_t window_bytes, int64_t gathers, void *sink, hipStream_t s);
 
 // ---- debug aid: the preconditions of the operands, checked on the device -----------
 hipError_t launch_validate(const DevOperands &ops, int32_t *status, int64_t *info, hipStream_t s);

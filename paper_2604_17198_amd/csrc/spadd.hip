@@ -844,6 +844,7 @@ hipError_t launch_one(const DevOperands &ops, const SpaddValues &vals, int64_t P
 // Workgroups of the merge kernel a compute unit holds at a time: its registers allow seven
 // wavefronts per SIMD.
 int spadd_resident() { return 28 / kWaves; }
+int spadd_wavefronts() { return kWaves; }
 
 int spadd_capacity(int fmt, int dtype)
 {

@@ -20,7 +20,8 @@ def _both(A, x, P):
     y_new = torch.full_like(y_ref, float("nan"))
     nb.nacho_spmv(op, xd, y_ref, P=P)
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    allocations = lambda: torch.cuda.memory_stats().get("allocation.all.allocated", 0)
+    before = allocations()                  # (allocation events of torch's allocator so far)
     # straight through the C ABI: descriptors, device pointers, stream
     arr = nb._pack([op])
     rc = nb.lib().nacho_spmv_static(C.cast(arr, C.c_void_p), C.c_void_p(xd.data_ptr()),
@@ -28,7 +29,7 @@ def _both(A, x, P):
                                     C.c_void_p(torch.cuda.current_stream().cuda_stream))
     assert rc == 0, nb.status_string(rc)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert allocations() == before
     a, b = y_ref.cpu().numpy(), y_new.cpu().numpy()
     assert not np.isnan(b).any()
     assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
