@@ -29,8 +29,8 @@
  *     from the `ws` argument, sized by nacho_workspace_bytes().
  *   * A call only enqueues kernels on `hip_stream` (a hipStream_t passed as
  *     void*; NULL is the default stream) and returns without synchronising
- *     (one exception: nacho_spmul_k on DCSR operands waits once, see there;
- *     nacho_workspace_parts for that call reads one word back).
+ *     (nacho_workspace_parts, which launches nothing, reads one word back for a
+ *     DCSR product and waits for it).
  *   * Indices and positions are int32; costs are int64.  Preconditions (not
  *     checked): coordinates sorted and unique inside each segment, `pos`
  *     non-decreasing with pos[0] = 0, sum of the operands' nnz < 2^31, all
@@ -190,14 +190,17 @@ int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, 
  * `parts` (host struct) with the number of partitions the fused call `op` uses
  * for these operands and with DEVICE pointers into the workspace `ws` the call
  * was (or will be) given; the table is valid once that call has run.  Nothing
- * is launched.  `grain` (host, may be NULL) receives G when the call uses the
+ * is launched.  One case waits: for nacho_spmul_k on DCSR operands the number of
+ * partitions is a result of the call's own kernels; it is read back on
+ * `hip_stream` (the stream that call was enqueued on) and the function returns
+ * once the stream has reached that point.  `hip_stream` is not used otherwise.  `grain` (host, may be NULL) receives G when the call uses the
  * fixed-grain queries Q_p = min(p*G, Q_total) (SpMV and SpMM with P = 0; G is
  * in scaled units, a multiple of n_dense for SpMM), 0 when it uses
  * Q_p = floor(p*Q_total/P).  Arguments as for nacho_workspace_bytes.
  */
 int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                               int64_t n_dense, int64_t P, void *ws, size_t ws_bytes,
-                              nacho_parts *parts /* host */, int64_t *grain /* host */);
+                              nacho_parts *parts /* host */, int64_t *grain /* host */, void *hip_stream);
 
 /*
  * y = A x with A in CSR (Section 4.2.2 uses this expression for the broadcast
@@ -273,9 +276,10 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
  * those of the remapped nest, a CSR-like space: coord = (i', j), posn[..][0] =
  * i', posn[..][1] = the number of entries the operand stores in the
  * intersected rows before the boundary.  Workspace: nacho_workspace_bytes with
- * NACHO_OP_SPMUL.  Unlike the other calls this one waits for the stream once,
- * after the row loop: the size of the remapped space decides what is launched
- * next.
+ * NACHO_OP_SPMUL.  Like every other call this one only enqueues: the size of the
+ * remapped space stays on the device, the kernels after the row loop are launched
+ * for upper bounds (the sizes the workspace is carved for) and read the real
+ * sizes there.
  */
 int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);

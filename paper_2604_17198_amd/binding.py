@@ -98,7 +98,7 @@ def lib():
                                     C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spmul_k.argtypes = L.nacho_spadd_k.argtypes
         L.nacho_workspace_parts.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
-                                            C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+                                            C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
@@ -258,7 +258,8 @@ def workspace_parts(op, ops, dtype, ws, n_dense=0, P=0):
     grain = C.c_int64(0)
     arr = _pack(ops)
     _check(lib().nacho_workspace_parts(op, C.cast(arr, C.c_void_p), len(ops), dtype, n_dense, P, _ptr(ws),
-                                       ws.numel(), C.byref(parts), C.byref(grain)), "nacho_workspace_parts")
+                                       ws.numel(), C.byref(parts), C.byref(grain), _stream()),
+           "nacho_workspace_parts")
     base = ws.data_ptr()
     k, d, Pe = parts.k, parts.d, int(parts.P)
 
@@ -348,9 +349,8 @@ def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):
 
 
 def nacho_spmul_k(ops, out: SparseOut, P=0, ws=None):
-    """Z = product of the operands over the intersection of their coordinates (vectors, CSR, DCSR).
-    Enqueues only, except for DCSR operands, where the call waits once for the number of rows all
-    operands store."""
+    """Z = product of the operands over the intersection of their coordinates (vectors, CSR, DCSR, COO).
+    Enqueues only."""
     dt = dtype_code(ops[0].val.dtype)
     dev = ops[0].val.device
     if ws is None:

@@ -401,7 +401,7 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
 
 int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, int32_t dtype,
                               int64_t n_dense, int64_t P, void *ws, size_t ws_bytes,
-                              nacho_parts *parts, int64_t *grain)
+                              nacho_parts *parts, int64_t *grain, void *hip_stream)
 {
     if (!parts || !ws || P < 0) return NACHO_ERR_INVALID_ARG;
     if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
@@ -429,8 +429,12 @@ int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, in
         if (fmt == FMT_DCSR && k > 1) {
             RemapWs c = carve_remap(ws, ops, k, dtype, total, P);
             if (ws_bytes < c.bytes) return NACHO_ERR_WORKSPACE;
+            // (the partition count of this call is a result of its kernels: read back behind them)
             int64_t info[4];
-            if (hipMemcpy(info, c.info, sizeof(info), hipMemcpyDeviceToHost) != hipSuccess) return NACHO_ERR_HIP;
+            hipStream_t s = static_cast<hipStream_t>(hip_stream);
+            if (hipMemcpyAsync(info, c.info, sizeof(info), hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess)
+                return NACHO_ERR_HIP;
             if (info[0] < 0 || info[0] > c.Pmax) return NACHO_ERR_INVALID_ARG;   // no call has run on ws
             w = c.parts;
             Pe = info[0];
@@ -576,80 +580,75 @@ static int32_t dcsr_product(const nacho_tensor *ops, int32_t k, int32_t dtype, i
     bool empty = false;
     for (int t = 0; t < k; ++t)
         if (ops[t].lvl[0].count == 0 || ops[t].lvl[1].count == 0) empty = true;
-    int32_t head[1 + NACHO_MAX_OPERANDS] = {0};
-    int64_t remapped_total = 0;
-    if (!empty) {
-        // 1. the row loop on its own partitions (Algorithm 1 on the level-0 coordinate arrays)
-        DevOperands rows;
-        std::memset(&rows, 0, sizeof(rows));
-        rows.k = k;
-        rows.d = 1;
-        int64_t rows_total = 0;
-        for (int t = 0; t < k; ++t) {
-            rows.lvl[t][0] = dev.lvl[t][0];
-            rows_total += dev.lvl[t][0].count;
-        }
-        // (the partition kernel also zeroes the per-row counts; the array starts on a 256-byte
-        // boundary and so does whatever follows it, so whole 64-bit words may be cleared)
-        const int64_t cost_words = ((int64_t)(w.Mmax + 1) * k + 1) / 2;
-        if (launch_partition(rows, 1, w.P0, 0, nullptr, rows_total, w.parts0.coord, w.parts0.posn, w.parts0.cost,
-                             s, reinterpret_cast<unsigned long long *>(w.remap.cost), cost_words) != hipSuccess)
-            return NACHO_ERR_HIP;
-        profile_mark("rows_partition");
-        if (launch_rows_match(dev, w.P0, w.parts0.posn, w.flags, w.qpos, s) != hipSuccess) return NACHO_ERR_HIP;
-        profile_mark("rows_match");
-        // 2. T (per operand) and the rows' places, 3. its prefix sums: the remapped cost function
-        if (launch_remap_rows(dev, w.flags, w.qpos, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
-        profile_mark("remap_rows");
-        if (launch_remap_costs(k, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
-        profile_mark("remap_costs");
-        // the size of the remapped space decides the launch of everything below
-        if (hipMemcpyAsync(head, w.remap.head, sizeof(int32_t) * (size_t)(1 + k), hipMemcpyDeviceToHost, s) !=
-                hipSuccess ||
-            hipStreamSynchronize(s) != hipSuccess)
-            return NACHO_ERR_HIP;
-        for (int t = 0; t < k; ++t) remapped_total += head[1 + t];
-        empty = head[0] == 0 || remapped_total == 0;
-    }
     if (empty) {
+        // (an operand without rows or entries: known from the descriptors)
         if (launch_empty_result(o, w.info, s) != hipSuccess) return NACHO_ERR_HIP;
         profile_mark("empty_result");
         return NACHO_OK;
     }
-    const int64_t M = head[0];
+    // 1. the row loop on its own partitions (Algorithm 1 on the level-0 coordinate arrays)
+    DevOperands rows;
+    std::memset(&rows, 0, sizeof(rows));
+    rows.k = k;
+    rows.d = 1;
+    int64_t rows_total = 0;
+    for (int t = 0; t < k; ++t) {
+        rows.lvl[t][0] = dev.lvl[t][0];
+        rows_total += dev.lvl[t][0].count;
+    }
+    // (the partition kernel also zeroes the per-row counts; the array starts on a 256-byte
+    // boundary and so does whatever follows it, so whole 64-bit words may be cleared)
+    const int64_t cost_words = ((int64_t)(w.Mmax + 1) * k + 1) / 2;
+    if (launch_partition(rows, 1, w.P0, 0, nullptr, rows_total, w.parts0.coord, w.parts0.posn, w.parts0.cost,
+                         s, reinterpret_cast<unsigned long long *>(w.remap.cost), cost_words) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("rows_partition");
+    if (launch_rows_match(dev, w.P0, w.parts0.posn, w.flags, w.qpos, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("rows_match");
+    // 2. T (per operand) and the rows' places, 3. its prefix sums: the remapped cost function
+    if (launch_remap_rows(dev, w.flags, w.qpos, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("remap_rows");
+    if (launch_remap_costs(k, w.remap, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("remap_costs");
+    // The size of the remapped space (rows all operands store, entries in them) stays on the device:
+    // everything below is launched for the upper bounds the workspace was carved for, reads the real
+    // sizes there, and lets the surplus workgroups leave at once.  The call never waits for the stream.
+    const int64_t capacity = spadd_capacity(SPADD_CSR, dtype) - k;
+    if (launch_remap_plan(k, w.remap, capacity, (int64_t)compute_units() * spadd_resident(), P, w.Pmax, w.info,
+                          s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("remap_plan");
     DevOperands mapped;
     std::memset(&mapped, 0, sizeof(mapped));
     mapped.k = k;
     mapped.d = 2;
     for (int t = 0; t < k; ++t) {
         mapped.lvl[t][0].kind = NACHO_DENSE;
-        mapped.lvl[t][0].extent = M;
+        mapped.lvl[t][0].extent = w.Mmax;                       // (upper bound; the real extent is dyn_head[0])
         mapped.lvl[t][1].kind = NACHO_COMPRESSED;
         mapped.lvl[t][1].extent = dev.lvl[t][1].extent;
         mapped.lvl[t][1].pos = w.remap.cost + (size_t)t * (w.Mmax + 1);
         mapped.lvl[t][1].crd = dev.lvl[t][1].crd;
-        mapped.lvl[t][1].count = head[1 + t];
+        mapped.lvl[t][1].count = dev.lvl[t][1].count;           // (upper bound; dyn_head[1 + t])
         mapped.start[t] = w.remap.start + (size_t)t * w.Mmax;
     }
-    int64_t Pe = fused_partitions(NACHO_OP_SPADD, FMT_CSR, dtype, k, remapped_total, P);
-    if (Pe > w.Pmax) Pe = w.Pmax;          // (cannot happen: remapped_total <= total)
+    mapped.dyn_head = w.remap.head;
+    mapped.dyn_plan = w.info;
     SpaddOut mo = o;                        // the remapped result: CSR over the intersected rows
     mo.pos0 = nullptr;
     mo.crd0 = nullptr;
     mo.pos1 = w.pos_full;
-    mo.cap_rows = M;
+    mo.cap_rows = w.Mmax;
     mo.counts = w.counts;
-    if (launch_partition(mapped, 1, Pe, 0, nullptr, remapped_total, w.parts.coord, w.parts.posn, w.parts.cost, s,
-                         w.tile_state, spadd_state_words(Pe), o.status) != hipSuccess)
+    if (launch_partition(mapped, 1, w.Pmax, 0, nullptr, total, w.parts.coord, w.parts.posn, w.parts.cost, s,
+                         w.tile_state, spadd_state_words(w.Pmax), o.status) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
-    if (launch_spadd(SPADD_CSR, dtype, true, mapped, vals, Pe, w.parts.coord, w.parts.posn, w.tile_state, mo, s) !=
-        hipSuccess)
+    if (launch_spadd(SPADD_CSR, dtype, true, mapped, vals, w.Pmax, w.parts.coord, w.parts.posn, w.tile_state, mo,
+                     s) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("spmul_merge");
-    const int64_t info_vals[3] = {Pe, M, remapped_total};
-    if (launch_compact_rows(M, w.remap, w.pos_full, w.counts, o, info_vals, w.info, w.tsum, s) != hipSuccess)
-        return NACHO_ERR_HIP;
+    if (launch_compact_rows(w.remap, w.pos_full, w.counts, o, w.tsum, s) != hipSuccess) return NACHO_ERR_HIP;
     profile_mark("rows_compact");
     return NACHO_OK;
 }

@@ -27,7 +27,25 @@ struct DevOperands {
     // row i' of operand t are stored from position start[t][i'] of crd / val on, while the
     // level-1 pos array counts only the entries of the intersected rows.  NULL otherwise.
     const int32_t *start[NACHO_MAX_OPERANDS];
+    // Remapped operands only: their sizes are results of earlier kernels of the same call and are
+    // read on the device.  dyn_head[0] = rows all operands store (the extent of the dense level),
+    // dyn_head[1 + t] = entries operand t stores in them (the count of its compressed level);
+    // dyn_plan[0] = partitions of the remapped nest, dyn_plan[2] = its total cost.  The extents and
+    // counts in lvl[][] are upper bounds then (what the launches are sized for).  NULL otherwise.
+    const int32_t *dyn_head;
+    const int64_t *dyn_plan;
 };
+
+// Extent of the dense level 0 / count of the last level of operand t: the stored ones, or (remapped
+// operands) the values earlier kernels of the call left on the device.
+__device__ inline int64_t level0_extent(const DevOperands &ops)
+{
+    return ops.dyn_head ? (int64_t)ops.dyn_head[0] : ops.lvl[0][0].extent;
+}
+__device__ inline int64_t last_count(const DevOperands &ops, int t)
+{
+    return ops.dyn_head ? (int64_t)ops.dyn_head[1 + t] : ops.lvl[t][ops.d - 1].count;
+}
 
 // floor(p * total / P) for 0 <= p <= P < 2^31 without leaving int64.
 __host__ __device__ inline int64_t equal_query(int64_t p, int64_t total, int64_t P)

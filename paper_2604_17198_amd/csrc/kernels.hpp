@@ -91,11 +91,15 @@ hipError_t launch_remap_rows(const DevOperands &ops, const int32_t *flags, const
                              const RemapArrays &r, int32_t *tsum, hipStream_t s);
 // r.cost: per-row counts -> exclusive prefix sums (in place), head[1 + t]
 hipError_t launch_remap_costs(int k, const RemapArrays &r, int32_t *tsum, hipStream_t s);
-// Result rows that hold an entry: pos_full[M + 1] over the intersected rows -> out.pos0 / crd0 /
-// pos1 / counts (counts_in = {M, nnz} of the remapped result); info[0..2] = info_vals.
-hipError_t launch_compact_rows(int64_t M, const RemapArrays &r, const int32_t *pos_full,
-                               const int64_t *counts_in, const SpaddOut &out, const int64_t *info_vals,
-                               int64_t *info, int32_t *tsum, hipStream_t s);
+// Result rows that hold an entry: pos_full[0 .. head[0]] over the intersected rows -> out.pos0 / crd0 /
+// pos1 / counts (counts_in = {rows, nnz} of the remapped result).
+hipError_t launch_compact_rows(const RemapArrays &r, const int32_t *pos_full,
+                               const int64_t *counts_in, const SpaddOut &out, int32_t *tsum, hipStream_t s);
+// plan[0..2] = {partitions of the remapped nest, intersected rows, remapped total cost}, computed on the
+// device from r.head: capacity = entries one partition may hold, round = resident workgroups of the
+// chip (the count is rounded up to whole rounds when P_min == 0), P_max = what the launches are sized for.
+hipError_t launch_remap_plan(int k, const RemapArrays &r, int64_t capacity, int64_t round, int64_t P_min,
+                             int64_t P_max, int64_t *plan, hipStream_t s);
 hipError_t launch_empty_result(const SpaddOut &out, int64_t *info, hipStream_t s);
 
 // ---- measurement aids: kernels of known traffic (streaming read, copy, independent gathers) ----

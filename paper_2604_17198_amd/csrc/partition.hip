@@ -533,6 +533,10 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                  ClearWords clear)
 {
     clear.run((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+    if (ops.dyn_plan) {                      // sizes left on the device by earlier kernels of the call
+        P = ops.dyn_plan[0];
+        total_unscaled = ops.dyn_plan[2];
+    }
     const int64_t b0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE) * kGroup;
     if (b0 > P) return;                      // whole wavefront leaves together
     const int lane = lane_id();
@@ -601,12 +605,13 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
             const bool end = (b != 0);
             if (lane == 0) {
                 for (int m = 0; m < d; ++m) cb[m] = 0;
-                if (end) cb[0] = (int32_t)ops.lvl[0][0].extent;
+                if (end) cb[0] = (int32_t)level0_extent(ops);
                 for (int t = 0; t < k; ++t)
                     for (int m = 0; m < d; ++m) {
                         const DevLevel &L = ops.lvl[t][m];
                         int32_t at = 0;
                         if (end) at = (L.kind == NACHO_DENSE) ? (int32_t)L.extent : (int32_t)L.count;
+                        if (end && ops.dyn_head) at = m == 0 ? (int32_t)level0_extent(ops) : (int32_t)last_count(ops, t);
                         pb[t * d + m] = at;
                     }
                 cost[b] = end ? total_scaled : 0;

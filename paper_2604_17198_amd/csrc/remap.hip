@@ -179,18 +179,17 @@ struct RemapOut {
     __device__ void finish(int, int total) const { head[0] = total; }
 };
 
-// Rows of the remapped result that hold an entry
+// Rows of the remapped result that hold an entry (the first head[0] rows exist)
 struct KeepIn {
     const int32_t *pos_full;
-    __device__ int load(int, int64_t i) const { return pos_full[i + 1] > pos_full[i] ? 1 : 0; }
+    const int32_t *head;
+    __device__ int load(int, int64_t i) const { return i < head[0] && pos_full[i + 1] > pos_full[i] ? 1 : 0; }
 };
 
 struct CompactOut {
     const int32_t *rows, *pos_full;
     const int64_t *counts_in;      // {rows, nnz} of the remapped result
     SpaddOut out;
-    int64_t info_vals[3];
-    int64_t *info;
     __device__ void store(int, int64_t i, int before, int keep) const
     {
         if (keep && before < out.cap_rows) {
@@ -207,9 +206,27 @@ struct CompactOut {
         else *out.status = NACHO_ERR_CAPACITY;
         out.counts[0] = total;
         out.counts[1] = nnz;
-        for (int i = 0; i < 3; ++i) info[i] = info_vals[i];
     }
 };
+
+// What the kernels after the row loop need to know, left where they can read it: the number of
+// partitions of the remapped nest (the rule of the fused calls: enough partitions that one fits a
+// workgroup, a whole number of rounds of resident workgroups, at least what the caller asked for),
+// the number of intersected rows and the remapped total cost.
+__global__ void remap_plan_kernel(const int32_t *__restrict__ head, int k, int64_t capacity, int64_t round,
+                                  int64_t P_min, int64_t P_max, int64_t *__restrict__ plan)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int64_t total = 0;
+    for (int t = 0; t < k; ++t) total += head[1 + t];
+    int64_t need = total > 0 ? (total + capacity - 1) / capacity : 1;
+    if (P_min == 0 && need > round) need = (need + round - 1) / round * round;
+    int64_t P = P_min > need ? P_min : need;
+    if (P > P_max) P = P_max;
+    plan[0] = P;
+    plan[1] = head[0];
+    plan[2] = total;
+}
 
 __global__ void empty_result_kernel(SpaddOut out, int64_t *info)
 {
@@ -284,20 +301,25 @@ hipError_t launch_remap_costs(int k, const RemapArrays &r, int32_t *tsum, hipStr
     return scan(in, out, r.stride, k, tsum, s);
 }
 
-hipError_t launch_compact_rows(int64_t M, const RemapArrays &r, const int32_t *pos_full,
-                               const int64_t *counts_in, const SpaddOut &out, const int64_t *info_vals,
-                               int64_t *info, int32_t *tsum, hipStream_t s)
+hipError_t launch_compact_rows(const RemapArrays &r, const int32_t *pos_full,
+                               const int64_t *counts_in, const SpaddOut &out, int32_t *tsum, hipStream_t s)
 {
     KeepIn in;
     in.pos_full = pos_full;
+    in.head = r.head;
     CompactOut o;
     o.rows = r.rows;
     o.pos_full = pos_full;
     o.counts_in = counts_in;
     o.out = out;
-    for (int i = 0; i < 3; ++i) o.info_vals[i] = info_vals[i];
-    o.info = info;
-    return scan(in, o, M, 1, tsum, s);
+    return scan(in, o, r.stride, 1, tsum, s);       // (over the upper bound of the rows; those past head[0] count as empty)
+}
+
+hipError_t launch_remap_plan(int k, const RemapArrays &r, int64_t capacity, int64_t round, int64_t P_min,
+                             int64_t P_max, int64_t *plan, hipStream_t s)
+{
+    hipLaunchKernelGGL(remap_plan_kernel, dim3(1), dim3(64), 0, s, r.head, k, capacity, round, P_min, P_max, plan);
+    return hipGetLastError();
 }
 
 hipError_t launch_empty_result(const SpaddOut &out, int64_t *info, hipStream_t s)

@@ -230,6 +230,12 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              unsigned long long *__restrict__ tile_state, SpaddOut out, WaveLog wlog)
 {
     const WaveStamp stamp = wave_begin();
+    if (kMapped && ops.dyn_plan) {
+        // the number of partitions is a result of earlier kernels of the call: the launch is sized for
+        // an upper bound and the workgroups past the last partition have nothing to do
+        P = ops.dyn_plan[0];
+        if ((int64_t)blockIdx.x >= P) return;
+    }
     typedef typename KeyOf<FMT>::type KeyT;
     typedef Shape<KeyT, T> S;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
@@ -733,13 +739,13 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 // totals, tails and the capacity verdict (the only writer of these words)
                 const long long total_nnz = b_nnz + t_nnz;
                 const long long total_rows = FMT == SPADD_DCSR ? b_rows + t_rows
-                                                               : (FMT == SPADD_CSR ? ops.lvl[0][0].extent : 1);
+                                                               : (FMT == SPADD_CSR ? level0_extent(ops) : 1);
                 out.counts[0] = total_rows;
                 out.counts[1] = total_nnz;
                 const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
                 if (!fits) atomicMin(out.status, (int32_t)NACHO_ERR_CAPACITY);
                 if (FMT == SPADD_VECTOR || kCoo) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
-                if (FMT == SPADD_CSR) out.pos1[ops.lvl[0][0].extent] = (int32_t)total_nnz;
+                if (FMT == SPADD_CSR) out.pos1[level0_extent(ops)] = (int32_t)total_nnz;
                 if (FMT == SPADD_DCSR) {
                     out.pos0[0] = 0;
                     out.pos0[1] = (int32_t)total_rows;

@@ -202,6 +202,34 @@ def test_workspace_too_small_and_reuse():
         assert np.array_equal(out.crd1.cpu().numpy()[:ref["crd1"].shape[0]], ref["crd1"])
 
 
+def test_the_call_only_enqueues():
+    """The sizes of the remapped space stay on the device: the call comes back while the stream is
+    still busy with work queued before it, and the result is right once the stream has drained."""
+    cfg = workloads.config(4, scale=0.05)
+    mats = [{kk: m[kk] for kk in ("pos0", "crd0", "pos1", "crd1", "val")} for m in cfg["ops"]]
+    shape = (cfg["n_rows"], cfg["n_cols"])
+    ops = [nb.dcsr(dev(m["pos0"]), dev(m["crd0"]), dev(m["pos1"]), dev(m["crd1"]), shape[0], shape[1],
+                   dev(m["val"])) for m in mats]
+    out = nb.SparseOut("dcsr", min(len(m["crd0"]) for m in mats), min(len(m["crd1"]) for m in mats),
+                       torch.float32, "cuda")
+    ws = torch.empty(nb.workspace_bytes(nb.OP_SPMUL, ops, nb.F32), dtype=torch.uint8, device="cuda")
+    a = torch.randn(8192, 8192, device="cuda")
+    torch.cuda.synchronize()
+    print("spmul dcsr behind a busy stream", flush=True)
+    for _ in range(12):
+        a = (a @ a) * 1e-4                      # tens of milliseconds of work ahead of the call
+    nb.nacho_spmul_k(ops, out, ws=ws)
+    done = torch.cuda.Event()
+    done.record()
+    assert not done.query(), "the call waited for the stream"
+    torch.cuda.synchronize()
+    ref = oracle.spmul_dcsr(mats)
+    assert out.counts.cpu().numpy().tolist() == [ref["crd0"].shape[0], ref["crd1"].shape[0]]
+    assert int(out.status.cpu().numpy()[0]) == 0
+    assert np.array_equal(out.crd1.cpu().numpy()[:ref["crd1"].shape[0]], ref["crd1"])
+    assert np.array_equal(out.crd0.cpu().numpy()[:ref["crd0"].shape[0]], ref["crd0"])
+
+
 def test_config4_operands_full_size():
     """The two DCSR matrices of configuration 4 multiplied: half of each operand's rows are skipped."""
     cfg = workloads.config(4)
