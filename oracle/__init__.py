@@ -182,6 +182,27 @@ def partition(ops, P, queries=None, tail_extent=0):
     return {"coord": coord, "posn": posn, "cost": cost}
 
 
+def partition_rowcost(ops, P, row_cost, queries=None):
+    """All P+1 boundaries of two-level operands under the row-aware cost (every level-0 position costs
+    `row_cost` on top of its stored non-zeros).  Same result layout as partition()."""
+    k = len(ops)
+    assert ops[0].nlevels == 2
+    coord = np.zeros((P + 1, 2), dtype=np.int64)
+    posn = np.zeros((P + 1, k, 2), dtype=np.int64)
+    cost = np.zeros(P + 1, dtype=np.int64)
+    qp = None
+    if queries is not None:
+        queries = np.ascontiguousarray(queries, dtype=np.int64)
+        assert queries.shape[0] == P + 1
+        qp = queries.ctypes.data_as(C.c_void_p)
+    rc = lib().ora_partition_rowcost(_pack(ops), k, C.c_int64(row_cost), C.c_int64(P), qp,
+                                     coord.ctypes.data_as(C.c_void_p), posn.ctypes.data_as(C.c_void_p),
+                                     cost.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("ora_partition_rowcost rejected its arguments")
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
 def spmv(pos, crd, val, x):
     """Returns (y, s) as float64: y = A x, s_i = sum_j |A_ij x_j|."""
     pos, crd = _i32(pos), _i32(crd)

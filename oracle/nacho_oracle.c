@@ -268,6 +268,125 @@ int ora_partition(const ora_tensor *ops, int k, int d, int64_t tail_extent, int6
     return 0;
 }
 
+/* ---- a row-aware cost function (variant) -------------------------------- */
+/*
+ * Section 4.2.2 counts stored non-zeros and remarks that this only approximates
+ * the run time; a partition of 512 one-entry rows does more than one of a single
+ * 512-entry row.  The variant below charges every level-0 position of an operand
+ * (every row of a Dense level, every stored row of a Compressed one) `row_cost`
+ * units on top of its stored non-zeros.  In the vocabulary of Section 3.1, for
+ * two-level operands (i over j):
+ *     C_i(x)     = sum_t [ non-zeros of t in rows before x  +  row_cost * (rows of t before x) ]
+ *     C_j(x | i) = sum_{t storing row i} [ (x > 0 ? row_cost : 0)  +  entries of row i with column < x ]
+ * Both are monotone, and C_j(N_j | i) = C_i(i + 1) - C_i(i): the pair is
+ * hierarchically consistent, so Algorithm 1 applies unchanged.  The row's own
+ * units sit in front of its first column: a boundary may fall at (i, 0).
+ * FindPartition below is Algorithm 1 with these two functions, written out for
+ * d = 2; outputs as ora_find_partition.
+ */
+static int64_t rows_before(const ora_tensor *T, int64_t lo, int64_t hi, int64_t x, int64_t *p_out)
+{
+    int64_t p = locate(T, 0, lo, hi, x);
+    *p_out = p;
+    return p - lo;
+}
+
+int64_t ora_total_cost_rowcost(const ora_tensor *ops, int k, int64_t row_cost)
+{
+    int64_t q = 0;
+    for (int t = 0; t < k; ++t) {
+        int64_t lo, hi;
+        root_segment(&ops[t], &lo, &hi);
+        q += leaf_begin(&ops[t], 0, hi) - leaf_begin(&ops[t], 0, lo) + row_cost * (hi - lo);
+    }
+    return q;
+}
+
+int ora_find_partition_rowcost(const ora_tensor *ops, int k, int64_t row_cost, int64_t Q,
+                               int64_t *coord, int64_t *posn, int64_t *cost)
+{
+    if (k < 1 || k > ORA_MAXK || row_cost < 0) return -1;
+    int64_t lo[ORA_MAXK], hi[ORA_MAXK];
+    int present[ORA_MAXK];
+    int64_t R = Q;
+    for (int t = 0; t < k; ++t) {
+        if (ops[t].nlevels != 2) return -1;
+        root_segment(&ops[t], &lo[t], &hi[t]);
+    }
+    /* level 0: the highest row x with C_i(x) <= R */
+    {
+        int64_t N = ops[0].lvl[0].extent, low = 0, high = N;
+        while (low < high) {
+            int64_t x = low + (high - low + 1) / 2, c = 0, p;
+            for (int t = 0; t < k; ++t)
+                c += level_cost(&ops[t], 0, lo[t], hi[t], x) + row_cost * rows_before(&ops[t], lo[t], hi[t], x, &p);
+            if (c <= R) low = x; else high = x - 1;
+        }
+        int64_t x0 = low, c = 0, p;
+        for (int t = 0; t < k; ++t)
+            c += level_cost(&ops[t], 0, lo[t], hi[t], x0) + row_cost * rows_before(&ops[t], lo[t], hi[t], x0, &p);
+        R -= c;
+        coord[0] = x0;
+        for (int t = 0; t < k; ++t) {
+            const ora_tensor *T = &ops[t];
+            rows_before(T, lo[t], hi[t], x0, &p);
+            posn[(size_t)t * 2 + 0] = p;
+            if (T->lvl[0].kind != ORA_DENSE) present[t] = (p < hi[t] && (int64_t)T->lvl[0].crd[p] == x0);
+            else present[t] = (x0 < N);
+            lo[t] = child_begin(T, 0, p);
+            hi[t] = child_begin(T, 0, present[t] ? p + 1 : p);
+        }
+    }
+    /* level 1: the highest column x with C_j(x | row) <= R */
+    {
+        int64_t N = ops[0].lvl[1].extent, low = 0, high = N;
+        while (low < high) {
+            int64_t x = low + (high - low + 1) / 2, c = 0;
+            for (int t = 0; t < k; ++t)
+                if (present[t]) c += (x > 0 ? row_cost : 0) + level_cost(&ops[t], 1, lo[t], hi[t], x);
+            if (c <= R) low = x; else high = x - 1;
+        }
+        int64_t x1 = low, c = 0;
+        for (int t = 0; t < k; ++t)
+            if (present[t]) c += (x1 > 0 ? row_cost : 0) + level_cost(&ops[t], 1, lo[t], hi[t], x1);
+        R -= c;
+        coord[1] = x1;
+        for (int t = 0; t < k; ++t) posn[(size_t)t * 2 + 1] = locate(&ops[t], 1, lo[t], hi[t], x1);
+    }
+    *cost = Q - R;
+    return 0;
+}
+
+/* All P+1 boundaries with the row-aware cost; conventions of ora_partition. */
+int ora_partition_rowcost(const ora_tensor *ops, int k, int64_t row_cost, int64_t P, const int64_t *queries,
+                          int64_t *coord, int64_t *posn, int64_t *cost)
+{
+    if (P < 1 || k < 1 || k > ORA_MAXK) return -1;
+    int64_t total = ora_total_cost_rowcost(ops, k, row_cost);
+    for (int64_t p = 0; p <= P; ++p) {
+        int64_t *c = coord + (size_t)p * 2;
+        int64_t *q = posn + (size_t)p * k * 2;
+        int64_t Q = queries ? queries[p] : equal_query(p, total, P);
+        if (p == 0 || p == P || Q >= total) {
+            int end = (p != 0);
+            c[0] = end ? ops[0].lvl[0].extent : 0;
+            c[1] = 0;
+            for (int t = 0; t < k; ++t) {
+                int64_t lo, hi;
+                root_segment(&ops[t], &lo, &hi);
+                int64_t at = end ? hi : lo;
+                q[(size_t)t * 2 + 0] = at;
+                q[(size_t)t * 2 + 1] = child_begin(&ops[t], 0, at);
+            }
+            cost[p] = end ? total : 0;
+        } else {
+            int rc = ora_find_partition_rowcost(ops, k, row_cost, Q, c, q, &cost[p]);
+            if (rc) return rc;
+        }
+    }
+    return 0;
+}
+
 /* ---- plain definitions of the balanced kernels -------------------------- */
 
 /* y_i = sum_j A_ij x_j, CSR, fp64 inputs, long double accumulation.

@@ -10,9 +10,8 @@ Section 4.2.2.  It is pinned here to things other than itself:
   * the tiling invariant (boundaries ordered, position intervals tile every
     operand, work sums to the total);
   * the CSR closed-form cost functions (Section 4.2.2, first listing);
-  * a literal transcription-free re-implementation of the specialised
-    three-vector search with range tracking (Section 4.2.3), written here in
-    Python from its description, on random inputs.
+  * numpy's sort / searchsorted on three vectors (the case Section 4.2.3
+    specialises), on random inputs.
 """
 import json
 import os
@@ -257,37 +256,22 @@ def test_spmm_tail_dimension_reading():
 
 
 # --------------------------------------------------------------------------- #
-# the specialised three-vector search with range tracking (Section 4.2.3)
+# three vectors against numpy's sort and searchsorted (the case Section 4.2.3 specialises)
 # --------------------------------------------------------------------------- #
-def _three_vector_search(vecs, q, n):
-    """Outer binary search over coordinates in (low, high]; per step one lower
-    bound per vector inside its tracked window [l, h) (half-open, returning h
-    when no entry is >= i); cost = sum of the lower bounds; cost <= q moves the
-    lower end (and the windows' lower ends) up, else the upper end down."""
-    low, high = 0, n
-    l = [0] * len(vecs)
-    h = [len(v) for v in vecs]
-    while low < high:
-        i = low + (high - low + 1) // 2
-        ip = [l[t] + int(np.searchsorted(vecs[t][l[t]:h[t]], i, side="left")) for t in range(len(vecs))]
-        if sum(ip) <= q:
-            low, l = i, ip
-        else:
-            high, h = i - 1, ip
-    return low, l
-
-
-def test_three_vector_listing_with_range_tracking():
+def test_three_vectors_against_numpy_sort():
+    """The boundary of query q is the q-th smallest of all stored indices (numpy.sort of their
+    concatenation); every vector's position is numpy.searchsorted of that index; the cost is their sum."""
     rng = np.random.default_rng(11)
     for trial in range(60):
         n = int(rng.integers(1, 200))
         vecs = [to_vector(random_coords(rng, (n,), int(rng.integers(0, n + 1)))) for _ in range(3)]
         ops = [oracle.vector(v, n) for v in vecs]
-        qtot = sum(len(v) for v in vecs)
-        for q in range(qtot):
-            low, l = _three_vector_search(vecs, q, n)
-            coord, posn, _ = oracle.find_partition(ops, q)
-            assert int(coord[0]) == low and posn[:, 0].tolist() == l
+        everything = np.sort(np.concatenate(vecs))
+        for q in range(everything.shape[0]):
+            x = int(everything[q])
+            at = [int(np.searchsorted(v, x, side="left")) for v in vecs]
+            coord, posn, cost = oracle.find_partition(ops, q)
+            assert int(coord[0]) == x and posn[:, 0].tolist() == at and cost == sum(at)
 
 
 # --------------------------------------------------------------------------- #
