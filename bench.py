@@ -206,6 +206,16 @@ def bench_spmv(args, ceilings):
                "table_nnz_plus_rows_max_over_mean": float(both.max() / both.mean()),
                "measured": _measured_balance(step, int(P))}
 
+    # the row-aware cost variant on the same matrix (every row costs one unit on top of its non-zeros):
+    # what balancing non-zeros + rows buys (or costs) against the paper's non-zero count
+    P_rc = nb.rowcost_partitions(op, nb.F64, 1)
+    ws_rc = torch.empty(nb.workspace_bytes(nb.OP_SPMV, [op], nb.F64, 0, P_rc), dtype=torch.uint8, device="cuda")
+    step_rc = lambda: nb.nacho_spmv_rowcost(op, x, y, 1, ws=ws_rc)
+    ms_rc, _ = _time_steps(step_rc, max(5, args.steps // 2), 2)
+    rowcost = {"row_cost": 1, "partitions": int(P_rc), "ms_per_step": ms_rc, "kernel_ms": _kernel_ms(step_rc, 5),
+               "measured": _measured_balance(step_rc, int(P_rc))}
+    del ws_rc
+
     # parity check of the timed configuration (full vector) and the oracle's own time
     import oracle
     best, ref, sabs = oracle.time_spmv_native(A["pos"], A["crd"], A["val"], cfg["x"], reps=3)
@@ -242,6 +252,7 @@ def bench_spmv(args, ceilings):
                      "gather_rate_Gper_s": nnz / exec_ms / 1e6,
                      "gather_ceiling_16MiB_Gper_s": ceilings["gather_16MiB_window_Gper_s"]},
         "balance": balance,
+        "row_aware_cost_variant": rowcost,
         "cpu_baseline": {"value": nnz / best, "unit": "nnz/s", "cores": 1, "kind": "oracle",
                          "seconds": best, "nproc": nproc, "cpu_model": cpu_model,
                          "build": "gcc -O3 -march=native (this host), timed in C with CLOCK_MONOTONIC",

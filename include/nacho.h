@@ -215,6 +215,32 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Row-aware cost (a variant; Section 4.2.2 remarks that the non-zero count only
+ * approximates the run time, and a partition of 512 one-entry rows does more
+ * than one of a single 512-entry row).  Every row of A costs `row_cost` units
+ * (0 .. 64) on top of its stored non-zeros, charged in front of its first
+ * column: C_i(r) = pos[r] + row_cost * r, C_j(x | r) = (x > 0 ? row_cost : 0) +
+ * entries of row r with column < x -- monotone and hierarchically consistent
+ * (Section 3.1), so Algorithm 1 applies unchanged; a boundary may fall at
+ * (r, 0), also in an empty row.  row_cost = 0 is the paper's cost.
+ *   nacho_partition_rowcost   boundaries of one CSR operand, queries
+ *                             floor(p * total / P) with total = nnz + row_cost * rows;
+ *                             `out` as for nacho_partition (k = 1, d = 2)
+ *   nacho_spmv_rowcost        y = A x on those partitions; uses
+ *                             nacho_rowcost_partitions(A, dtype, row_cost, P)
+ *                             partitions (at least P, and enough that a
+ *                             partition's cost fits one wavefront) and needs the
+ *                             workspace nacho_workspace_bytes reports for
+ *                             NACHO_OP_SPMV with that partition count
+ * Errors as for nacho_partition / nacho_spmv.
+ */
+int64_t nacho_rowcost_partitions(const nacho_tensor *A, int32_t dtype, int64_t row_cost, int64_t P);
+int32_t nacho_partition_rowcost(const nacho_tensor *A, int64_t row_cost, int64_t P, const nacho_parts *out,
+                                void *hip_stream);
+int32_t nacho_spmv_rowcost(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t row_cost,
+                           int64_t P, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * nacho_spmv for callers that cannot allocate device memory or pass a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc).  Same operation, arguments, results and status codes as nacho_spmv,

@@ -27,7 +27,8 @@ EXPORTS = [
     "nacho_partition", "nacho_spmv", "nacho_spmm", "nacho_spadd_k", "nacho_spmul_k", "nacho_workspace_parts",
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
     "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
-    "nacho_probe", "nacho_merge_wavefronts",
+    "nacho_probe", "nacho_merge_wavefronts", "nacho_rowcost_partitions", "nacho_partition_rowcost",
+    "nacho_spmv_rowcost",
 ]
 
 
@@ -102,6 +103,11 @@ def lib():
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
+        L.nacho_rowcost_partitions.restype = C.c_int64
+        L.nacho_rowcost_partitions.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64]
+        L.nacho_partition_rowcost.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+        L.nacho_spmv_rowcost.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p]
         _libs[_instrumented] = L
         _lib = L
@@ -297,6 +303,36 @@ def nacho_spmv_static(A: Operand, x, y, P=0):
 
 def static_scratch_bytes() -> int:
     return int(lib().nacho_static_scratch_bytes())
+
+
+def rowcost_partitions(A: Operand, dtype, row_cost, P=0) -> int:
+    arr = _pack([A])
+    return int(lib().nacho_rowcost_partitions(C.cast(arr, C.c_void_p), dtype, row_cost, P))
+
+
+def nacho_partition_rowcost(A: Operand, P, row_cost):
+    """Boundaries 0..P of one CSR operand under the row-aware cost; result as nacho_partition."""
+    dev = A.keep[0].device
+    coord = torch.empty((P + 1, 2), dtype=torch.int32, device=dev)
+    posn = torch.empty((P + 1, 1, 2), dtype=torch.int32, device=dev)
+    cost = torch.empty(P + 1, dtype=torch.int64, device=dev)
+    parts = _Parts(1, 2, P, coord.data_ptr(), posn.data_ptr(), cost.data_ptr())
+    arr = _pack([A])
+    _check(lib().nacho_partition_rowcost(C.cast(arr, C.c_void_p), row_cost, P, C.byref(parts), _stream()),
+           "nacho_partition_rowcost")
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
+def nacho_spmv_rowcost(A: Operand, x, y, row_cost, P=0, ws=None):
+    """y = A x on partitions balanced by non-zeros + row_cost per row."""
+    dt = dtype_code(x.dtype)
+    Pe = rowcost_partitions(A, dt, row_cost, P)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPMV, [A], dt, 0, Pe), x.device)
+    arr = _pack([A])
+    _check(lib().nacho_spmv_rowcost(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dt, row_cost, P, _ptr(ws),
+                                    ws.numel(), _stream()), "nacho_spmv_rowcost")
+    return y
 
 
 def nacho_spmm(A: Operand, B, Cout=None, P=0, ws=None):

@@ -269,11 +269,14 @@ RemapWs carve_remap(void *ws, const nacho_tensor *ops, int k, int32_t dtype, int
 
 // The three launches of y = A x on a carved workspace (caller's or the built-in one).
 int32_t spmv_enqueue(const nacho_tensor *A, const DevOperands &dev, int64_t nnz, const void *x, void *y,
-                     int32_t dtype, int64_t P, int64_t Pe, const CarryWs &w, hipStream_t s)
+                     int32_t dtype, int64_t P, int64_t Pe, const CarryWs &w, hipStream_t s, int64_t row_cost = 0)
 {
     const int64_t n_rows = A->lvl[0].extent;
     profile_begin(s);
-    const int64_t grain = (P == 0) ? spmv_capacity(dtype) : 0;
+    // (fixed-grain queries make the partitions inside a row arithmetic in pos, which the executing
+    // kernel uses to deal them out; with a row cost the boundaries are no longer multiples of the grain
+    // in pos, and the equally spaced queries are used)
+    const int64_t grain = (P == 0 && row_cost == 0) ? spmv_capacity(dtype) : 0;
     // (the partition kernel also writes the zeros of the rows A stores nothing in)
     ZeroRows zero;
     zero.base = y;
@@ -281,7 +284,7 @@ int32_t spmv_enqueue(const nacho_tensor *A, const DevOperands &dev, int64_t nnz,
     zero.width = 1;
     zero.elem = (int32_t)dtype_size(dtype);
     if (launch_partition(dev, 1, Pe, grain, nullptr, nnz, w.parts.coord, w.parts.posn, w.parts.cost, s, nullptr, 0,
-                         nullptr, &zero) != hipSuccess)
+                         nullptr, &zero, row_cost) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
     if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz,
@@ -526,6 +529,65 @@ int32_t nacho_spmv_static(const nacho_tensor *A, const void *x, void *y, int32_t
 }
 
 size_t nacho_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+// Partitions of the row-aware calls: at least P, and enough that a partition's cost (non-zeros +
+// row_cost per row) fits what one wavefront stages.
+static int64_t rowcost_partitions(int32_t dtype, int64_t nnz, int64_t n_rows, int64_t row_cost, int64_t P)
+{
+    const int64_t total = nnz + row_cost * n_rows;
+    const int64_t need = total > 0 ? ceil_div(total, spmv_capacity(dtype)) : 1;
+    return P > need ? P : need;
+}
+
+int64_t nacho_rowcost_partitions(const nacho_tensor *A, int32_t dtype, int64_t row_cost, int64_t P)
+{
+    if (!A || P < 0 || row_cost < 0 || row_cost > 64 || (dtype != NACHO_F32 && dtype != NACHO_F64)) return 0;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    if (check_operands(A, 1, false, &dev, &nnz, &fmt) != NACHO_OK || fmt != FMT_CSR) return 0;
+    return rowcost_partitions(dtype, nnz, A->lvl[0].extent, row_cost, P);
+}
+
+int32_t nacho_partition_rowcost(const nacho_tensor *A, int64_t row_cost, int64_t P, const nacho_parts *out,
+                                void *hip_stream)
+{
+    if (!out || !out->coord || !out->posn || !out->cost) return NACHO_ERR_INVALID_ARG;
+    if (P < 1 || P > 0x7ffffff0LL || row_cost < 0 || row_cost > 64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &total, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (out->k != 1 || out->d != 2 || out->P != P) return NACHO_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    if (launch_partition(dev, 1, P, 0, nullptr, total, out->coord, out->posn, out->cost, s, nullptr, 0, nullptr,
+                         nullptr, row_cost) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("partition");
+    return NACHO_OK;
+}
+
+int32_t nacho_spmv_rowcost(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t row_cost,
+                           int64_t P, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!A || !x || !y || P < 0 || row_cost < 0 || row_cost > 64) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &nnz, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = rowcost_partitions(dtype, nnz, A->lvl[0].extent, row_cost, P);
+    CarryWs w = carve_carry(ws, Pe, dtype, 1);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    // (P as passed on: with a row cost the call always uses the equally spaced queries)
+    return spmv_enqueue(A, dev, nnz, x, y, dtype, Pe, Pe, w, static_cast<hipStream_t>(hip_stream), row_cost);
+}
 
 int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb, void *C, int64_t ldc,
                    int32_t dtype, int64_t P, void *ws, size_t ws_bytes, void *hip_stream)

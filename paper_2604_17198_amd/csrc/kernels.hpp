@@ -10,6 +10,8 @@ namespace nacho {
 // `clear_words` (may be NULL): n_clear 64-bit words the kernel sets to zero on the side, and
 // `clear_status` (may be NULL) a status word it sets to NACHO_OK: the state of the kernels that
 // follow it in a fused call.
+// `row_cost` (one CSR operand with built-in queries only): every row costs that many units on top of its
+// stored non-zeros (in the units of a non-zero before cost_scale); total_unscaled stays the non-zero count.
 // `zero_rows` (may be NULL; one CSR operand with built-in queries only, i.e. the fused SpMV and
 // SpMM calls): the kernel also sets to zero the rows of a dense result whose operand row is empty.
 struct ZeroRows {
@@ -21,7 +23,8 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
                             unsigned long long *clear_words = nullptr, int64_t n_clear = 0,
-                            int32_t *clear_status = nullptr, const ZeroRows *zero_rows = nullptr);
+                            int32_t *clear_status = nullptr, const ZeroRows *zero_rows = nullptr,
+                            int64_t row_cost = 0);
 
 // Items one wavefront can stage for SpMV (partition work must not exceed it).
 int spmv_capacity(int dtype);

@@ -780,16 +780,24 @@ struct QueryRule {
     __device__ int64_t first_reaching(int64_t y) const
     {
         int64_t b;
-        if (grain_u > 0 && grain_u < 0x7fffffffLL) b = ((uint32_t)y + (uint32_t)grain_u - 1u) / (uint32_t)grain_u;   // y < 2^31
-        else if (grain_u > 0) b = y > 0 ? 1 : 0;
-        else b = total > 0 ? (y * P + total - 1) / total : 0;     // y, P < 2^31
+        if (grain_u > 0 && grain_u < 0x7fffffffLL && y < 0x7fffffffLL)
+            b = ((uint32_t)y + (uint32_t)grain_u - 1u) / (uint32_t)grain_u;
+        else if (grain_u > 0) b = (y + grain_u - 1) / grain_u;
+        else b = total > 0 ? (int64_t)(((__int128)y * P + total - 1) / total) : 0;
         return b < P ? b : P;
     }
 };
 
+// row_cost > 0: the row-aware variant of the cost (Section 4.2.2 remarks that the non-zero count only
+// approximates the run time): every row costs row_cost units on top of its stored non-zeros,
+// charged in front of its first column, C_i(r) = pos[r] + row_cost * r.  Row r then owns the queries in
+// [C_i(r), C_i(r + 1)) -- empty rows own some too -- and a boundary with R = Q - C_i(r) left lies at the
+// row's start when R < row_cost, else at the entry of rank R - row_cost (an entry in column 0 shares
+// the coordinate of the row's own units: the boundary's cost is then C_i(r)).
 __global__ void __launch_bounds__(256)
 partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
-                      int64_t count, QueryRule rule, int64_t cost_scale, int32_t *__restrict__ coord,
+                      int64_t count, QueryRule rule, int64_t cost_scale, int64_t row_cost,
+                      int32_t *__restrict__ coord,
                       int32_t *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear, ZeroRows zero)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -809,7 +817,7 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
             posn[i * 2 + 0] = end ? (int32_t)n_rows : 0;
             posn[i * 2 + 1] = end ? (int32_t)count : 0;
             cost[i] = end ? rule.total * cost_scale : 0;
-        } else {
+        } else if (row_cost == 0) {
             coord[i * 2 + 1] = crd[p0 + q];
             posn[i * 2 + 1] = (int32_t)(p0 + q);
             cost[i] = q * cost_scale;
@@ -819,13 +827,13 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
     int64_t b_lo = 0, b_hi = 0;
     bool empty_row = false;
     if (i < n_rows) {
-        const int64_t a = pos[i] - p0, e = pos[i + 1] - p0;
-        empty_row = e == a;
+        const int64_t a = pos[i] - p0 + row_cost * i, e = pos[i + 1] - p0 + row_cost * (i + 1);
+        empty_row = pos[i + 1] == pos[i];
         if (e > a) {
             b_lo = rule.first_reaching(a);
             b_hi = rule.first_reaching(e);
             if (b_lo < 1) b_lo = 1;                 // boundary 0 is the origin by definition
-            // (b < b_hi means Q_b < pos[r+1] <= total and b < P: interior)
+            // (b < b_hi means Q_b < C_i(r + 1) <= total and b < P: interior)
         }
     }
     unsigned long long todo = __ballot(b_hi > b_lo);
@@ -838,6 +846,18 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
         for (int64_t b = lo + lane; b < hi; b += NACHO_WAVE) {
             coord[b * 2 + 0] = r;
             posn[b * 2 + 0] = r;
+            if (row_cost > 0) {
+                const int64_t start = pos[r] - p0 + row_cost * r;      // C_i(r)
+                const int64_t Q = rule.query(b), R = Q - start;
+                int32_t at = pos[r], x1 = 0;
+                if (R >= row_cost) {
+                    at += (int32_t)(R - row_cost);
+                    x1 = crd[at];
+                }
+                coord[b * 2 + 1] = x1;
+                posn[b * 2 + 1] = at;
+                cost[b] = (x1 > 0 ? Q : start) * cost_scale;
+            }
         }
     }
     // Rows without entries: their row of the result is zero, and the executing
@@ -862,7 +882,7 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
                             unsigned long long *clear_words, int64_t n_clear, int32_t *clear_status,
-                            const ZeroRows *zero_rows)
+                            const ZeroRows *zero_rows, int64_t row_cost)
 {
     ClearWords clear;
     clear.words = clear_words;
@@ -877,17 +897,17 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
         (grain == 0 || grain % cost_scale == 0)) {
         QueryRule rule;
         rule.P = P;
-        rule.total = total_unscaled;
+        rule.total = total_unscaled + row_cost * ops.lvl[0][0].extent;
         rule.grain_u = grain / cost_scale;
         const int64_t n_rows = ops.lvl[0][0].extent;
         int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
         if (clear.n > threads) threads = clear.n;
         hipLaunchKernelGGL(partition_csr1_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            ops.lvl[0][1].pos, ops.lvl[0][1].crd, n_rows, ops.lvl[0][1].count, rule, cost_scale,
-                           coord, posn, cost, clear, zero);
+                           row_cost, coord, posn, cost, clear, zero);
         return hipGetLastError();
     }
-    if (zero_rows) return hipErrorInvalidValue;      // only the one-pass kernel above writes them
+    if (zero_rows || row_cost != 0) return hipErrorInvalidValue;      // only the one-pass kernel above does these
     int64_t waves = (P + 1 + kGroup - 1) / kGroup;
     if (clear.n > waves * NACHO_WAVE) waves = (clear.n + NACHO_WAVE - 1) / NACHO_WAVE;
     const int waves_per_block = 256 / NACHO_WAVE;
