@@ -303,6 +303,34 @@ def spadd_dcsr(mats):
             "crd1": o_c1[:nz].copy(), "val": o_v[:nz].copy(), "abs": o_a[:nz].copy()}
 
 
+def spadd_csf3(tens):
+    """Union add of k third-order CSF tensors given as dicts(pos0, crd0, pos1, crd1, pos2, crd2, val).
+    Returns dict(pos0, crd0, pos1, crd1, pos2, crd2 int32; val, abs float64)."""
+    k = len(tens)
+    arr = {n: [_i32(t[n]) for t in tens] for n in ("pos0", "crd0", "pos1", "crd1", "pos2", "crd2")}
+    vals, is64 = _vals([t["val"] for t in tens])
+    cap = [sum(c.shape[0] for c in arr[n]) for n in ("crd0", "crd1", "crd2")]
+    o_p0 = np.zeros(2, dtype=np.int32)
+    o_c0 = np.empty(cap[0], dtype=np.int32)
+    o_p1 = np.empty(cap[0] + 1, dtype=np.int32)
+    o_c1 = np.empty(cap[1], dtype=np.int32)
+    o_p2 = np.empty(cap[1] + 1, dtype=np.int32)
+    o_c2 = np.empty(cap[2], dtype=np.int32)
+    o_v = np.empty(cap[2], dtype=np.float64)
+    o_a = np.empty(cap[2], dtype=np.float64)
+    counts = np.zeros(3, dtype=np.int64)
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    rc = lib().ora_spadd_csf3(k, _ptr_array(arr["pos0"]), _ptr_array(arr["crd0"]), _ptr_array(arr["pos1"]),
+                              _ptr_array(arr["crd1"]), _ptr_array(arr["pos2"]), _ptr_array(arr["crd2"]),
+                              _ptr_array(vals), is64, p(o_p0), p(o_c0), p(o_p1), p(o_c1), p(o_p2), p(o_c2),
+                              p(o_v), p(o_a), p(counts))
+    if rc:
+        raise ValueError("ora_spadd_csf3 rejected its arguments")
+    n0, n1, n2 = (int(v) for v in counts)
+    return {"pos0": o_p0, "crd0": o_c0[:n0].copy(), "pos1": o_p1[:n0 + 1].copy(), "crd1": o_c1[:n1].copy(),
+            "pos2": o_p2[:n1 + 1].copy(), "crd2": o_c2[:n2].copy(), "val": o_v[:n2].copy(), "abs": o_a[:n2].copy()}
+
+
 def spadd_csr(mats):
     """Union add of k CSR matrices given as dicts(pos, crd, val).
     Returns dict(pos, crd int32; val, abs float64)."""

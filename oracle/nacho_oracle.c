@@ -896,6 +896,92 @@ int64_t ora_spmul_coo(int k, const int32_t *const *rows, const int32_t *const *c
     return coo_merge(1, k, rows, cols, val, nnz, is_f64, out_row, out_col, out_val, out_abs);
 }
 
+/* ---- union addition of third-order tensors (three compressed levels, CSF) ---- */
+/*
+ * Z_ijk = sum_t T^t_ijk over the union of the operands' stored coordinates: the
+ * coiteration nest of Section 2.2 one level deeper.  At every level the fingers of
+ * the operands that store the prefix walk their segments; the smallest coordinate
+ * under a finger is emitted ("any operand matches"), and the operands that hold it
+ * descend into their child segments.  Values of coinciding entries are added in
+ * operand order.  The result is CSF as well: crd0 / pos1 / crd1 / pos2 / crd2 / val.
+ */
+typedef struct {
+    int k, is_f64;
+    const int32_t *const *pos[3];
+    const int32_t *const *crd[3];
+    const void *const *val;
+    int32_t *ocrd[3];
+    int32_t *opos[3];        /* opos[m][c] = first child (level m) of output entry c of level m - 1 */
+    double *oval, *oabs;
+    int64_t n[3];
+} csf3_ctx;
+
+static void csf3_coiterate(csf3_ctx *c, int m, const int64_t *lo, const int64_t *hi)
+{
+    int64_t f[ORA_MAXK], clo[ORA_MAXK], chi[ORA_MAXK];
+    for (int t = 0; t < c->k; ++t) f[t] = lo[t];
+    for (;;) {
+        int64_t x = INT64_MAX;
+        for (int t = 0; t < c->k; ++t)
+            if (f[t] < hi[t] && (int64_t)c->crd[m][t][f[t]] < x) x = c->crd[m][t][f[t]];
+        if (x == INT64_MAX) break;
+        c->ocrd[m][c->n[m]] = (int32_t)x;
+        if (m < 2) {
+            c->opos[m + 1][c->n[m]] = (int32_t)c->n[m + 1];
+            for (int t = 0; t < c->k; ++t) {
+                if (f[t] < hi[t] && (int64_t)c->crd[m][t][f[t]] == x) {
+                    clo[t] = c->pos[m + 1][t][f[t]];
+                    chi[t] = c->pos[m + 1][t][f[t] + 1];
+                    ++f[t];
+                } else {
+                    clo[t] = chi[t] = 0;
+                }
+            }
+            ++c->n[m];
+            csf3_coiterate(c, m + 1, clo, chi);
+        } else {
+            double sum = 0.0, sabs = 0.0;
+            for (int t = 0; t < c->k; ++t)
+                if (f[t] < hi[t] && (int64_t)c->crd[m][t][f[t]] == x) {
+                    double v = load_value(c->val[t], c->is_f64, f[t]);
+                    sum += v;
+                    sabs += fabs(v);
+                    ++f[t];
+                }
+            c->oval[c->n[2]] = sum;
+            c->oabs[c->n[2]] = sabs;
+            ++c->n[2];
+        }
+    }
+}
+
+/* counts[3] = stored coordinates of the result at levels 0, 1, 2 */
+int ora_spadd_csf3(int k, const int32_t *const *pos0, const int32_t *const *crd0, const int32_t *const *pos1,
+                   const int32_t *const *crd1, const int32_t *const *pos2, const int32_t *const *crd2,
+                   const void *const *val, int is_f64, int32_t *opos0, int32_t *ocrd0, int32_t *opos1,
+                   int32_t *ocrd1, int32_t *opos2, int32_t *ocrd2, double *oval, double *oabs, int64_t *counts)
+{
+    if (k < 1 || k > ORA_MAXK) return -1;
+    csf3_ctx c;
+    c.k = k; c.is_f64 = is_f64;
+    c.pos[0] = pos0; c.pos[1] = pos1; c.pos[2] = pos2;
+    c.crd[0] = crd0; c.crd[1] = crd1; c.crd[2] = crd2;
+    c.val = val;
+    c.ocrd[0] = ocrd0; c.ocrd[1] = ocrd1; c.ocrd[2] = ocrd2;
+    c.opos[0] = opos0; c.opos[1] = opos1; c.opos[2] = opos2;
+    c.oval = oval; c.oabs = oabs;
+    c.n[0] = c.n[1] = c.n[2] = 0;
+    int64_t lo[ORA_MAXK], hi[ORA_MAXK];
+    for (int t = 0; t < k; ++t) { lo[t] = pos0[t][0]; hi[t] = pos0[t][1]; }
+    csf3_coiterate(&c, 0, lo, hi);
+    opos0[0] = 0;
+    opos0[1] = (int32_t)c.n[0];
+    opos1[c.n[0]] = (int32_t)c.n[1];
+    opos2[c.n[1]] = (int32_t)c.n[2];
+    counts[0] = c.n[0]; counts[1] = c.n[1]; counts[2] = c.n[2];
+    return 0;
+}
+
 /* Timing aid for benchmarks (no arithmetic of its own): runs ora_spmv_f64 `reps`
  * times and returns the shortest duration in seconds, measured with the
  * monotonic clock around the call. */
