@@ -319,7 +319,7 @@ def bench_others(steps, warmup, only=None, ceilings=None):
         fn = lambda: nb.nacho_spadd_k(ops, out, ws=ws)
         fn()
         torch.cuda.synchronize()
-        n_rows_out, n_out = (int(v) for v in out.counts.cpu().numpy())
+        n_rows_out, n_out = (int(v) for v in out.counts.cpu().numpy()[:2])
         nbytes = tot * 8 + n_out * 8 + (rows * 8 + n_rows_out * 8 if fmt == "dcsr" else 0)
         what = ("C3: 3 sparse vectors (10M + 1M + 100k nnz, index space 2^30), fp32 union add" if c == 3 else
                 "C4: DCSR + DCSR, 1,000,000 x 1,000,000, ~20M nnz each, fp32 union add")
@@ -342,7 +342,7 @@ def bench_others(steps, warmup, only=None, ceilings=None):
             fm = lambda: nb.nacho_spmul_k(ops, outm, ws=wsm)
             fm()
             torch.cuda.synchronize()
-            r_mul, n_mul = (int(v) for v in outm.counts.cpu().numpy())
+            r_mul, n_mul = (int(v) for v in outm.counts.cpu().numpy()[:2])
             tab = nb.workspace_parts(nb.OP_SPMUL, ops, nb.F32, wsm)
             work = int(tab["cost"][-1])                 # entries in the rows both operands store
             m_rows = int(tab["coord"][-1, 0])

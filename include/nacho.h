@@ -93,7 +93,7 @@ typedef struct {
  *   CSR            nlevels = 2  {DENSE, COMPRESSED}
  *   DCSR           nlevels = 2  {COMPRESSED, COMPRESSED}
  *   CSF            nlevels = 3  {COMPRESSED, COMPRESSED, COMPRESSED}: third-order
- *                  tensors (nacho_partition only)
+ *                  tensors (nacho_partition and nacho_spadd_k)
  *   COO            nlevels = 2  {NONUNIQUE, SINGLETON}: entries sorted by (row,
  *                  column), no pair twice (nacho_partition, nacho_spadd_k,
  *                  nacho_spmul_k)
@@ -127,8 +127,13 @@ typedef struct {
  *   DCSR:   pos0[2] = {0, rows}, crd0[cap_rows], pos1[cap_rows+1], crd1, val
  *   COO:    crd0[cap_nnz] (rows), crd1[cap_nnz] (columns), val[cap_nnz];
  *           pos1[2] = {0, nnz}; cap_rows is not used
+ *   CSF (third order, three compressed levels): pos0[2] = {0, slices},
+ *           crd0[cap_rows] (i), pos1[cap_rows+1], crd1[cap_fibres] (j),
+ *           pos2[cap_fibres+1], crd2[cap_nnz] (k), val[cap_nnz]
  * counts[0] = stored rows (DCSR; n_rows for CSR; 1 for a vector), counts[1] =
- * nnz.  *status is set to NACHO_OK, or to NACHO_ERR_CAPACITY when cap_rows or
+ * nnz; for CSF counts = {slices, fibres, nnz}.  counts always has room for
+ * three words.  pos2, crd2 and cap_fibres are read for CSF only.  *status is
+ * set to NACHO_OK, or to NACHO_ERR_CAPACITY when cap_rows, cap_fibres or
  * cap_nnz is too small (then nothing is written beyond the capacities; counts
  * still hold the required sizes).  The sums of the operands' counts are always
  * sufficient capacities. */
@@ -139,8 +144,11 @@ typedef struct {
     int32_t *crd1;
     void *val;
     int64_t cap_rows, cap_nnz;
-    int64_t *counts; /* device, [2] */
+    int64_t *counts; /* device, [3] */
     int32_t *status; /* device, [1] */
+    int32_t *pos2;   /* CSF only */
+    int32_t *crd2;   /* CSF only */
+    int64_t cap_fibres;
 } nacho_sparse_out;
 
 /* Library version (major*10000 + minor*100 + patch) and a static string for a status. */

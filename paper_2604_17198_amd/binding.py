@@ -55,7 +55,8 @@ class _Parts(C.Structure):
 class _SparseOut(C.Structure):
     _fields_ = [("pos0", C.c_void_p), ("crd0", C.c_void_p), ("pos1", C.c_void_p),
                 ("crd1", C.c_void_p), ("val", C.c_void_p), ("cap_rows", C.c_int64),
-                ("cap_nnz", C.c_int64), ("counts", C.c_void_p), ("status", C.c_void_p)]
+                ("cap_nnz", C.c_int64), ("counts", C.c_void_p), ("status", C.c_void_p),
+                ("pos2", C.c_void_p), ("crd2", C.c_void_p), ("cap_fibres", C.c_int64)]
 
 
 _lib = None
@@ -352,23 +353,27 @@ def nacho_spmm(A: Operand, B, Cout=None, P=0, ws=None):
 class SparseOut:
     """Caller-allocated result arrays of nacho_spadd_k."""
 
-    def __init__(self, fmt, cap_rows, cap_nnz, dtype, device, n_rows=0):
+    def __init__(self, fmt, cap_rows, cap_nnz, dtype, device, n_rows=0, cap_fibres=0):
+        """fmt "csf3": cap_rows is the capacity in slices, cap_fibres in fibres."""
         i32 = dict(dtype=torch.int32, device=device)
         self.fmt = fmt
-        self.pos0 = torch.zeros(2, **i32) if fmt == "dcsr" else None
+        self.pos0 = torch.zeros(2, **i32) if fmt in ("dcsr", "csf3") else None
         self.crd0 = None
-        if fmt == "dcsr":
+        if fmt in ("dcsr", "csf3"):
             self.crd0 = torch.empty(max(cap_rows, 1), **i32)
         elif fmt == "coo":
             self.crd0 = torch.empty(max(cap_nnz, 1), **i32)      # the rows of the result's entries
-        n_pos1 = {"vector": 2, "coo": 2, "csr": n_rows + 1, "dcsr": cap_rows + 1}[fmt]
+        n_pos1 = {"vector": 2, "coo": 2, "csr": n_rows + 1, "dcsr": cap_rows + 1, "csf3": cap_rows + 1}[fmt]
         self.pos1 = torch.zeros(n_pos1, **i32)
-        self.crd1 = torch.empty(max(cap_nnz, 1), **i32)
+        self.crd1 = torch.empty(max(cap_fibres if fmt == "csf3" else cap_nnz, 1), **i32)
+        self.pos2 = torch.zeros(cap_fibres + 1, **i32) if fmt == "csf3" else None
+        self.crd2 = torch.empty(max(cap_nnz, 1), **i32) if fmt == "csf3" else None
         self.val = torch.empty(max(cap_nnz, 1), dtype=dtype, device=device)
-        self.counts = torch.zeros(2, dtype=torch.int64, device=device)
+        self.counts = torch.zeros(3, dtype=torch.int64, device=device)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.c = _SparseOut(_ptr(self.pos0), _ptr(self.crd0), _ptr(self.pos1), _ptr(self.crd1),
-                            _ptr(self.val), cap_rows, cap_nnz, _ptr(self.counts), _ptr(self.status))
+                            _ptr(self.val), cap_rows, cap_nnz, _ptr(self.counts), _ptr(self.status),
+                            _ptr(self.pos2), _ptr(self.crd2), cap_fibres)
 
 
 def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):

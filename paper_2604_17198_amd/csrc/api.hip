@@ -210,6 +210,7 @@ struct RemapWs {
 
 int spadd_fmt(Format f)
 {
+    if (f == FMT_CSF3) return SPADD_CSF3;
     return f == FMT_VECTOR ? SPADD_VECTOR : (f == FMT_CSR ? SPADD_CSR : (f == FMT_COO ? SPADD_COO : SPADD_DCSR));
 }
 
@@ -361,7 +362,7 @@ int64_t nacho_num_partitions(int32_t op, const nacho_tensor *ops, int32_t k, int
         return fused_partitions(op, fmt, dtype, k, total, P);
     case NACHO_OP_SPADD:
     case NACHO_OP_SPMUL:      // (a DCSR product: an upper bound, the count depends on the intersected rows)
-        if (fmt == FMT_CSF3) return 0;
+        if (fmt == FMT_CSF3 && op == NACHO_OP_SPMUL) return 0;
         return fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     default: return 0;
     }
@@ -387,13 +388,13 @@ int32_t nacho_workspace_bytes(int32_t op, const nacho_tensor *ops, int32_t k, in
         return NACHO_OK;
     }
     case NACHO_OP_SPMUL:
+        if (fmt == FMT_CSF3) return NACHO_ERR_UNSUPPORTED;
         if (fmt == FMT_DCSR && k > 1) {
             *bytes = carve_remap(nullptr, ops, k, dtype, total, P).bytes;
             return NACHO_OK;
         }
         /* fall through: the pipeline of the union */
     case NACHO_OP_SPADD: {
-        if (fmt == FMT_CSF3) return NACHO_ERR_UNSUPPORTED;
         const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
         *bytes = carve_spadd(nullptr, Pe, k, dev.d).bytes;
         return NACHO_OK;
@@ -726,7 +727,7 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     Format fmt;
     int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
     if (rc != NACHO_OK) return rc;
-    if (fmt == FMT_CSF3) return NACHO_ERR_UNSUPPORTED;          // third-order tensors: partition only
+    if (fmt == FMT_CSF3 && multiply) return NACHO_ERR_UNSUPPORTED;      // third-order tensors: partition and union
     // (the product of one operand is the operand: the union's pipeline copies it)
     if (multiply && fmt == FMT_DCSR && k == 1) multiply = false;
     SpaddValues vals;
@@ -738,9 +739,12 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     }
     if (!out->counts || !out->status || !out->pos1 || out->cap_nnz < 0 || out->cap_rows < 0)
         return NACHO_ERR_INVALID_ARG;
-    if (out->cap_nnz > 0 && (!out->crd1 || !out->val)) return NACHO_ERR_INVALID_ARG;
+    if (out->cap_nnz > 0 && ((fmt != FMT_CSF3 && !out->crd1) || !out->val)) return NACHO_ERR_INVALID_ARG;
     if (fmt == FMT_DCSR && (!out->pos0 || (out->cap_rows > 0 && !out->crd0))) return NACHO_ERR_INVALID_ARG;
     if (fmt == FMT_COO && out->cap_nnz > 0 && !out->crd0) return NACHO_ERR_INVALID_ARG;
+    if (fmt == FMT_CSF3 && (!out->pos0 || !out->pos2 || out->cap_fibres < 0 || (out->cap_rows > 0 && !out->crd0) ||
+                            (out->cap_fibres > 0 && !out->crd1) || (out->cap_nnz > 0 && !out->crd2)))
+        return NACHO_ERR_INVALID_ARG;
     const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
     SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
     const bool recursive = multiply && fmt == FMT_DCSR && k > 1;    // (its own workspace layout)
@@ -748,6 +752,9 @@ static int32_t sparse_combine(bool multiply, const nacho_tensor *ops, int32_t k,
     SpaddOut o;
     o.pos0 = out->pos0; o.crd0 = out->crd0; o.pos1 = out->pos1; o.crd1 = out->crd1; o.val = out->val;
     o.cap_rows = out->cap_rows; o.cap_nnz = out->cap_nnz; o.counts = out->counts; o.status = out->status;
+    o.pos2 = fmt == FMT_CSF3 ? out->pos2 : nullptr;
+    o.crd2 = fmt == FMT_CSF3 ? out->crd2 : nullptr;
+    o.cap_fibres = fmt == FMT_CSF3 ? out->cap_fibres : 0;
     const int f = spadd_fmt(fmt);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // a product of DCSR operands intersects the OUTER level

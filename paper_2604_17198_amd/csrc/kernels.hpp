@@ -48,13 +48,15 @@ hipError_t launch_spmm_fixup(int dtype, void *C, int64_t ldc, int n, int64_t P, 
                              const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream);
 
 // ---- k-way union addition ---------------------------------------------------
-enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2, SPADD_COO = 3 };
+enum { SPADD_VECTOR = 0, SPADD_CSR = 1, SPADD_DCSR = 2, SPADD_COO = 3, SPADD_CSF3 = 4 };
 
 struct SpaddValues { const void *v[NACHO_MAX_OPERANDS]; };
 struct SpaddOut {
     int32_t *pos0, *crd0, *pos1, *crd1;
     void *val;
     int64_t cap_rows, cap_nnz;
+    int32_t *pos2, *crd2;        // third-order tensors: the innermost level (crd1 / pos2: the fibres)
+    int64_t cap_fibres;
     int64_t *counts;
     int32_t *status;
 };

@@ -52,8 +52,26 @@ namespace nacho {
 
 namespace {
 
+// Key of a third-order tensor's entry: (i, j) above k, compared lexicographically.
+struct alignas(16) Key3 {
+    uint64_t hi, lo;                                   // i << 32 | j,  k
+    __device__ bool operator==(const Key3 &o) const { return hi == o.hi && lo == o.lo; }
+    __device__ bool operator!=(const Key3 &o) const { return hi != o.hi || lo != o.lo; }
+    __device__ bool operator<(const Key3 &o) const { return hi < o.hi || (hi == o.hi && lo < o.lo); }
+    __device__ bool operator<=(const Key3 &o) const { return hi < o.hi || (hi == o.hi && lo <= o.lo); }
+};
+// c ? a : b, member by member (a conditional over the whole struct goes through memory)
+template <typename KeyT> __device__ inline KeyT pick(bool c, const KeyT &a, const KeyT &b) { return c ? a : b; }
+template <> __device__ inline Key3 pick<Key3>(bool c, const Key3 &a, const Key3 &b)
+{
+    return Key3{c ? a.hi : b.hi, c ? a.lo : b.lo};
+}
 template <int FMT> struct KeyOf { typedef uint64_t type; };
 template <> struct KeyOf<SPADD_VECTOR> { typedef uint32_t type; };
+template <> struct KeyOf<SPADD_CSF3> { typedef Key3 type; };
+// The key no entry reaches (coordinates stay below 2^31).
+template <typename KeyT> __device__ constexpr KeyT key_sentinel() { return ~KeyT(0); }
+template <> __device__ constexpr Key3 key_sentinel<Key3>() { return Key3{~0ull, ~0ull}; }
 
 #ifndef NACHO_MERGE_WAVES
 #define NACHO_MERGE_WAVES 8
@@ -71,7 +89,7 @@ constexpr int kSlack = 4 * kMaxRuns;               // sentinels, gaps left by me
 // over all banks.  Chosen so that three workgroups fit the LDS of a compute unit (the
 // scalar registers of the kernel allow no more than three anyway).
 template <typename KeyT, typename T> struct Shape {
-    static constexpr int kIpt = (sizeof(KeyT) + sizeof(T) <= 8) ? 11 : 7;
+    static constexpr int kIpt = (sizeof(KeyT) + sizeof(T) <= 8) ? 11 : (sizeof(KeyT) > 8 ? 5 : 7);
     static constexpr int kTile = kThreads * kIpt;
     // entries a partition may hold: every round of pairwise merges hands out whole threads per pair
     // (at most kMaxRuns / 2 pairs), and all of them must fit the workgroup
@@ -99,7 +117,11 @@ __device__ inline unsigned long long pack_counts(long long rows, long long nnz)
     return ((unsigned long long)rows << 31) | (unsigned long long)nnz;
 }
 
+// Level-0 coordinate and innermost coordinate of a key.
 template <typename KeyT> __device__ inline uint32_t row_of(KeyT k) { return (uint32_t)((uint64_t)k >> 32); }
+__device__ inline uint32_t row_of(const Key3 &k) { return (uint32_t)(k.hi >> 32); }
+template <typename KeyT> __device__ inline uint32_t col_of(KeyT k) { return (uint32_t)k; }
+__device__ inline uint32_t col_of(const Key3 &k) { return (uint32_t)k.lo; }
 
 // Pointers into the operands' and the result's arrays are global-memory pointers (the loads and
 // stores below then need no address-space check).
@@ -126,14 +148,17 @@ struct Tile {
     unsigned long long blk_emit[TILE / NACHO_WAVE];    // per block of 64 merged places: which are emitted
     uint32_t blk_cnt[TILE / NACHO_WAVE];  // emitted entries of the block | rows it starts << 16
     uint32_t blk_loc[TILE / NACHO_WAVE];  // emitted entries | rows started, before the block inside the partition
+    uint32_t blk_cnt2[TILE / NACHO_WAVE]; // third-order tensors: slices (level-0 coordinates) the block starts
+    uint32_t blk_loc2[TILE / NACHO_WAVE]; // ... and those started before the block inside the partition
     unsigned long long scrd[kMaxRuns];    // address of crd of run t, biased so that [c] is entry c of the partition
     unsigned long long sval[kMaxRuns];    // the same for the values
     unsigned long long sstart[kMaxRuns];  // remapped operands: address of start[t]; coordinate lists: of the rows
     unsigned long long spos[kMaxRuns];    // remapped operands: address of pos of run t
     int32_t soff[kMaxRuns + 1];           // start of run t among the partition's entries
     uint32_t wave_x[kWaves];              // per-wavefront partial of a scan across the workgroup
-    long long base_nnz, base_rows;        // output offsets of the partition (known after the prefix sum)
+    long long base_nnz, base_rows, base_slices;    // output offsets of the partition (known after the prefix sum)
     uint32_t tile_cnt;                    // emitted entries | rows started of the partition
+    uint32_t tile_cnt2;                   // slices started (third-order tensors)
     uint32_t early_hits;                  // early count: entries found to repeat a key (union) / found everywhere (product)
     int32_t gave_up;
 };
@@ -157,6 +182,32 @@ __device__ inline bool row_continues(const DevOperands &ops, const int32_t *coor
         if (present && q > ops.lvl[t][1].pos[i0]) cont = true;
     }
     return cont;
+}
+
+// Byte offset of a value in `vals` from the byte offset of its key in `keys` (the two arrays hold
+// entry c at index c).
+template <int KB, int VB> __device__ inline int value_offset(int src)
+{
+    if constexpr (KB == VB) return src;
+    else if constexpr (KB > VB) return (int)((unsigned)src / (unsigned)(KB / VB));
+    else return src * (VB / KB);
+}
+
+// Third-order tensors: does boundary b fall strictly inside a fibre (i, j) / inside a slice i, i.e. does
+// some operand hold an entry of the boundary's fibre / slice before the boundary?
+__device__ inline void csf3_continues(const DevOperands &ops, const int32_t *coord, const int32_t *posn, int64_t b,
+                                      bool &fibre, bool &slice)
+{
+    const int k = ops.k;
+    const int x0 = coord[b * 3], x1 = coord[b * 3 + 1];
+    fibre = slice = false;
+    for (int t = 0; t < k; ++t) {
+        const int i0 = posn[(b * k + t) * 3 + 0], f0 = posn[(b * k + t) * 3 + 1], q = posn[(b * k + t) * 3 + 2];
+        if ((int64_t)i0 >= ops.lvl[t][0].count || ops.lvl[t][0].crd[i0] != x0) continue;
+        const int32_t *pos1 = ops.lvl[t][1].pos, *pos2 = ops.lvl[t][2].pos;
+        if (q > pos2[pos1[i0]]) slice = true;
+        if (f0 < pos1[i0 + 1] && ops.lvl[t][1].crd[f0] == x1 && q > pos2[f0]) fibre = true;
+    }
 }
 
 // One thread's share of the stable merge of the sorted runs X = keys[sx, sx + nx)
@@ -191,14 +242,14 @@ __device__ inline void merge_share(const char *kb, const char *vb, int sx, int n
     for (int j = 0; j < IPT; ++j) {
         const bool tx = xk <= yk;              // (an exhausted run shows its sentinel)
         const int src = tx ? xi : yi;
-        ok[j] = tx ? xk : yk;
-        const int vsrc = sizeof(T) == sizeof(KeyT) ? src : (sizeof(T) < sizeof(KeyT) ? src >> 1 : src << 1);
+        ok[j] = pick<KeyT>(tx, xk, yk);
+        const int vsrc = value_offset<KB, (int)sizeof(T)>(src);
         ov[j] = *reinterpret_cast<const T *>(vb + vsrc);
         const KeyT nk = *reinterpret_cast<const KeyT *>(kb + src + KB);
         xi += tx ? KB : 0;
         yi += tx ? 0 : KB;
-        xk = tx ? nk : xk;
-        yk = tx ? yk : nk;
+        xk = pick<KeyT>(tx, nk, xk);
+        yk = pick<KeyT>(tx, yk, nk);
     }
 }
 
@@ -215,6 +266,67 @@ __device__ inline int run_lower_bound(const KeyT *keys, int s, int n, int bits, 
         pos = keys[s + at - 1] < key ? at : pos;
     }
     return pos;
+}
+
+// Prefix look-up, first level: the 14-bit fields of the words of workgroups c0 .. c0 + m - 1 (m <= kChunk)
+// summed over the wavefront, once every one of them is published.  `early` holds the words as they were
+// when the wavefront asked for them ahead of time (kUseEarly), else the first round loads them too.
+// Returns false when the wavefront gives up waiting.
+template <bool kUseEarly>
+__device__ inline bool sum_words(const unsigned int *words, int64_t c0, int m, const unsigned (&early)[kChunk / NACHO_WAVE],
+                                 int lane, long long &lo14, long long &hi14)
+{
+    int spins = 0;
+    for (bool first = true;; first = false) {
+        unsigned v[kChunk / NACHO_WAVE];
+        bool missing = false;
+#pragma unroll
+        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+            const int j = i * NACHO_WAVE + lane;
+            v[i] = (first && kUseEarly) ? early[i] : kWordValid;
+            if (!(first && kUseEarly) && i * NACHO_WAVE < m && j < m)
+                v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        int l_lo = 0, l_hi = 0;
+#pragma unroll
+        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+            missing = missing || !(v[i] & kWordValid);
+            l_lo += (int)(v[i] & 0x3fffu);
+            l_hi += (int)((v[i] >> 14) & 0x3fffu);
+        }
+        if (__ballot(missing)) {                   // a predecessor has not published yet
+            if (++spins > kSpinLimit) return false;
+            __builtin_amdgcn_s_sleep(16);
+            continue;
+        }
+        lo14 = wave_sum<int>(l_lo);
+        hi14 = wave_sum<int>(l_hi);
+        return true;
+    }
+}
+
+// Second level: the two 31-bit fields of the totals of chunks 0 .. chunk - 1, summed, once published.
+__device__ inline bool sum_totals(const unsigned long long *totals, int64_t chunk, int lane, long long &lo31,
+                                  long long &hi31)
+{
+    int spins = 0;
+    long long c_lo = 0, c_hi = 0;
+    for (int64_t first = 0; first < chunk; ) {
+        const int64_t j = first + lane;
+        unsigned long long s = kTotalValid;
+        if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__ballot(!(s & kTotalValid))) {
+            if (++spins > kSpinLimit) return false;
+            __builtin_amdgcn_s_sleep(16);
+            continue;
+        }
+        c_lo += wave_sum<long long>((long long)(s & 0x7fffffffull));
+        c_hi += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
+        first += NACHO_WAVE;
+    }
+    lo31 = c_lo;
+    hi31 = c_hi;
+    return true;
 }
 
 // kMul: the k-way intersection with products (an entry is emitted when all k
@@ -238,12 +350,14 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     }
     typedef typename KeyOf<FMT>::type KeyT;
     typedef Shape<KeyT, T> S;
-    constexpr int D = FMT == SPADD_VECTOR ? 1 : 2;
+    constexpr int D = FMT == SPADD_VECTOR ? 1 : (FMT == SPADD_CSF3 ? 3 : 2);
+    constexpr bool kCsf = FMT == SPADD_CSF3;   // third-order tensors: three compressed levels
     constexpr bool kCoo = FMT == SPADD_COO;    // coordinate lists: the row of an entry is stored with it
     constexpr int R = S::kIpt;
     constexpr int NB = S::kBlocks;
     constexpr int NR = K <= 2 ? 2 : (K <= 4 ? 4 : 8);     // runs of the merge tree (a power of two)
-    constexpr KeyT kSentinel = ~KeyT(0);       // coordinates stay below 2^31: no key reaches it
+    constexpr KeyT kSentinel = key_sentinel<KeyT>();
+    static_assert(!kCsf || R <= 5, "the slice bits of a thread's places start at bit 27");
     constexpr int kDummy = S::kTile + kSlack;  // word of keys / vals nobody reads
     __shared__ Tile<KeyT, T, S::kTile> w;
 
@@ -293,6 +407,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                     w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.start[t] : nullptr);
                     w.spos[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].pos : nullptr);
                 }
+                if (kCsf) w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].crd : nullptr);
             }
         }
     }
@@ -303,7 +418,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // to the dummy word: no branches around the loads.
     int tr[R], col[R];
     T val[R];
-    uint32_t row[D == 2 ? R : 1];
+    uint32_t row[D >= 2 ? R : 1];              // level-0 coordinate of every entry (matrices, tensors)
+    uint32_t mid[D == 3 ? R : 1];              // level-1 coordinate (third-order tensors)
     const int last = n - 1;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -315,7 +431,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         tr[r] = t;
         col[r] = 0;
         val[r] = T(0);
-        if (D == 2) row[r] = 0;
+        if (D >= 2) row[r] = 0;
+        if (D == 3) mid[r] = 0;
     }
     if (n > 0) {
 #pragma unroll
@@ -331,84 +448,99 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         }
     }
 
-    if (D == 2 && !kCoo) {
-        // rows overlapping [q_lo, q_hi) of every run: mark each row's first entry
-        // (word of the entry in marks), then hand every entry the latest marker
-        // at or before it.  The first entry of every run carries a marker, so no
-        // row leaks from one run into the next.
-        for (int i = tid; i < S::kTile; i += kThreads) w.marks[i] = 0;
-        __syncthreads();
-#pragma unroll
-        for (int t = 0; t < K; ++t) {
-            if (t >= k) break;
-            const int nt = off[t + 1] - off[t];
-            if (nt == 0) continue;
-            const int32_t *pos1 = ops.lvl[t][1].pos;
-            const int32_t *crd0 = ops.lvl[t][0].crd;
-            const int ql = q_lo[t], qh = ql + nt;
-            const int i_lo = posn[(p * k + t) * 2 + 0];
-            int i_hi = posn[((p + 1) * k + t) * 2 + 0] + 1;
-            const int i_max = FMT == SPADD_CSR ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
-            if (i_hi > i_max) i_hi = i_max;
-            for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
-                int a[4], b[4], rw[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * kThreads;
-                    if (i < i_hi) {
-                        a[u] = pos1[i];
-                        b[u] = pos1[i + 1];
-                        rw[u] = FMT == SPADD_CSR ? i : crd0[i];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * kThreads;
-                    if (i < i_hi) {
-                        const int s = a[u] > ql ? a[u] : ql;
-                        if (b[u] > s && s < qh) w.marks[off[t] + s - ql] = (uint32_t)(rw[u] + 1);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        {
-            // latest marker at or before every word; a thread owns R consecutive words
-            uint32_t v[R], cur = 0;
-            const int at = tid * R;
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                v[j] = w.marks[at + j];
-                cur = v[j] ? v[j] : cur;
-            }
-            uint32_t incl = cur;                      // latest marker up to the end of this thread's words
-#pragma unroll
-            for (int o = 1; o < NACHO_WAVE; o <<= 1) {
-                const uint32_t left = __shfl_up(incl, o, NACHO_WAVE);
-                if (lane >= o && incl == 0) incl = left;
-            }
-            if (lane == NACHO_WAVE - 1) w.wave_x[wave] = incl;
+    if constexpr (D >= 2 && !kCoo) {
+        // Segments of an upper level overlapping [q_lo, q_hi) of every run: mark each segment's
+        // first entry (word of the entry in marks) with a value, then hand every entry the latest
+        // marker at or before it.  The first entry of every run carries a marker, so nothing leaks
+        // from one run into the next.  Matrices: the segments are the rows, the value the row's
+        // coordinate.  Third-order tensors, two passes: the fibres (value: the fibre's position,
+        // whose coordinate j is then read from the level-1 coordinates), then the slices (value: i).
+        auto parents = [&](const int lv, uint32_t (&res)[R]) {
+            for (int i = tid; i < S::kTile; i += kThreads) w.marks[i] = 0;
             __syncthreads();
-            uint32_t carry = 0;                       // latest marker of the earlier wavefronts
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww)
-                if (ww < wave && w.wave_x[ww]) carry = w.wave_x[ww];
-            cur = __shfl_up(incl, 1, NACHO_WAVE);
-            if (lane == 0) cur = 0;
-            if (cur == 0) cur = carry;
+            for (int t = 0; t < K; ++t) {
+                if (t >= k) break;
+                const int nt = off[t + 1] - off[t];
+                if (nt == 0) continue;
+                const int32_t *pos_a = ops.lvl[t][1].pos;                       // children of level 0
+                const int32_t *pos_b = D == 3 ? ops.lvl[t][2].pos : nullptr;    // children of level 1
+                const int32_t *crd0 = ops.lvl[t][0].crd;
+                const int ql = q_lo[t], qh = ql + nt;
+                const int i_lo = posn[(p * k + t) * D + lv];
+                int i_hi = posn[((p + 1) * k + t) * D + lv] + 1;
+                const int i_max = (FMT == SPADD_CSR) ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][lv].count;
+                if (i_hi > i_max) i_hi = i_max;
+                for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
+                    int a[4], b[4], rw[4];
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                cur = v[j] ? v[j] : cur;
-                w.marks[at + j] = cur;
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * kThreads;
+                        if (i < i_hi) {
+                            if (D == 2) { a[u] = pos_a[i]; b[u] = pos_a[i + 1]; }
+                            else if (lv == 1) { a[u] = pos_b[i]; b[u] = pos_b[i + 1]; }
+                            else { a[u] = pos_b[pos_a[i]]; b[u] = pos_b[pos_a[i + 1]]; }
+                            rw[u] = (FMT == SPADD_CSR || lv == 1) ? i : crd0[i];
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * kThreads;
+                        if (i < i_hi) {
+                            const int s = a[u] > ql ? a[u] : ql;
+                            if (b[u] > s && s < qh) w.marks[off[t] + s - ql] = (uint32_t)(rw[u] + 1);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            {
+                // latest marker at or before every word; a thread owns R consecutive words
+                uint32_t v[R], cur = 0;
+                const int at = tid * R;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    v[j] = w.marks[at + j];
+                    cur = v[j] ? v[j] : cur;
+                }
+                uint32_t incl = cur;                      // latest marker up to the end of this thread's words
+#pragma unroll
+                for (int o = 1; o < NACHO_WAVE; o <<= 1) {
+                    const uint32_t left = __shfl_up(incl, o, NACHO_WAVE);
+                    if (lane >= o && incl == 0) incl = left;
+                }
+                if (lane == NACHO_WAVE - 1) w.wave_x[wave] = incl;
+                __syncthreads();
+                uint32_t carry = 0;                       // latest marker of the earlier wavefronts
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww)
+                    if (ww < wave && w.wave_x[ww]) carry = w.wave_x[ww];
+                cur = __shfl_up(incl, 1, NACHO_WAVE);
+                if (lane == 0) cur = 0;
+                if (cur == 0) cur = carry;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    cur = v[j] ? v[j] : cur;
+                    w.marks[at + j] = cur;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int c = r * kThreads + tid;
+                res[r] = w.marks[c < last ? c : (last > 0 ? last : 0)] - 1u;
+            }
+            __syncthreads();                       // markers are read: the next pass / the values may overwrite them
+        };
+        if constexpr (D == 3) {
+            uint32_t fibre[R];
+            parents(1, fibre);
+            if (n > 0) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) mid[D == 3 ? r : 0] = (uint32_t)global_ptr<int32_t>(w.sstart[tr[r]])[fibre[r]];
             }
         }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int c = r * kThreads + tid;
-            row[r] = w.marks[c < last ? c : (last > 0 ? last : 0)] - 1u;
-        }
-        __syncthreads();                           // markers are read: the values may overwrite them
+        parents(0, row);
     }
     if (kMapped && n > 0) {
         // storage position - counted position of every entry, then its column and value
@@ -431,14 +563,17 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     for (int r = 0; r < R; ++r) {
         const int c = r * kThreads + tid;
         const int slot = c < n ? c + tr[r] + 1 : kDummy;
-        if (D == 1) keys[slot] = (KeyT)(uint32_t)col[r];
-        else keys[slot] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
+        if constexpr (D == 1) keys[slot] = (KeyT)(uint32_t)col[r];
+        else if constexpr (D == 2) keys[slot] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
+        else keys[slot] = Key3{((uint64_t)row[r] << 32) | (uint64_t)mid[r], (uint64_t)(uint32_t)col[r]};
         w.vals[slot] = val[r];
     }
     if (tid < K) keys[w.soff[tid + 1] + tid + 1] = kSentinel;
     if (tid == K) keys[0] = kSentinel;
-    bool cont = false;                     // the partition starts inside a row whose head is elsewhere
+    bool cont = false;                     // the partition starts inside a row (fibre) whose head is elsewhere
+    bool cont_slice = false;               // third-order tensors: ... inside a slice whose head is elsewhere
     if (D == 2 && !kCoo) cont = row_continues<FMT>(ops, coord, posn, p);
+    if (kCsf) csf3_continues(ops, coord, posn, p, cont, cont_slice);
     if (tid == 0) w.early_hits = 0;
     __syncthreads();
 
@@ -450,7 +585,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // binary search per other run; done only when that is at most two searches per thread (one
     // operand dominates the partition), otherwise the count is published after the assembly.
     bool published = false;                // (uniform)
-    if (FMT != SPADD_DCSR) {
+    if (FMT != SPADD_DCSR && !kCsf) {
         int cost_fwd = 0, cost_bwd = 0, n_min = n, t_min = 0;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
@@ -590,8 +725,10 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     KeyT hk[R];                                // key of the place
     T hv[R];                                   // its value with the equal keys after it folded in
     unsigned long long em[R];                  // (uniform) the emitted places of the thread's block
-    unsigned long long rm[FMT == SPADD_DCSR ? R : 1];      // (uniform) the places that start a row
-    uint32_t mine = 0;                         // bit j: place j is emitted; bit 16 + j: it starts a row
+    unsigned long long rm[(FMT == SPADD_DCSR || kCsf) ? R : 1];      // (uniform) the places that start a row / fibre
+    unsigned long long sm[kCsf ? R : 1];       // (uniform) third-order tensors: the places that start a slice
+    uint32_t mine = 0;                         // bit j: place j is emitted; bit 16 + j: it starts a row (fibre);
+                                               // bit 27 + j: it starts a slice
     uint32_t logged_items = 0, logged_rows = 0;    // (instrumented build) places / row heads this wavefront walked
     {
         const KeyT *mk = keys + mb + tid;      // (all reads below stay inside the arrays: the slack)
@@ -632,6 +769,16 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                 cnt |= (uint32_t)__popcll(rm[j]) << 16;
                 if (kInstrument) logged_rows += (uint32_t)__popcll(rm[j]);
             }
+            if constexpr (kCsf) {
+                const bool fhead = emit && (m == 0 ? !cont : k0.hi != kp.hi);
+                const bool shead = emit && (m == 0 ? !cont_slice : row_of(k0) != row_of(kp));
+                rm[j] = __ballot(fhead);
+                sm[j] = __ballot(shead);
+                mine |= (fhead ? 0x10000u << j : 0u) | (shead ? 0x8000000u << j : 0u);
+                cnt |= (uint32_t)__popcll(rm[j]) << 16;
+                if (lane == 0) w.blk_cnt2[j * kWaves + wave] = (uint32_t)__popcll(sm[j]);
+                if (kInstrument) logged_rows += (uint32_t)__popcll(rm[j]);
+            }
             hk[j] = k0;
             hv[j] = sum;
             // (the folded value is formed here and now: left to the compiler, the additions sink to
@@ -662,71 +809,53 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         if (b0 < NB) w.blk_loc[b0] = excl;
         if (b1 < NB) w.blk_loc[b1] = excl + c0v;
         const long long t_nnz = (long long)(tile_cnt & 0xffffu), t_rows = (long long)(tile_cnt >> 16);
-        unsigned long long *totals = tile_state;                                        // one per chunk
-        unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);   // one per workgroup
+        long long t_slices = 0;
+        if (kCsf) {
+            const uint32_t s0v = b0 < NB ? w.blk_cnt2[b0 < NB ? b0 : 0] : 0u;
+            const uint32_t s1v = b1 < NB ? w.blk_cnt2[b1 < NB ? b1 : 0] : 0u;
+            const int incl2 = wave_inclusive_scan((int)(s0v + s1v));
+            if (b0 < NB) w.blk_loc2[b0] = (uint32_t)incl2 - (s0v + s1v);
+            if (b1 < NB) w.blk_loc2[b1] = (uint32_t)incl2 - s1v;
+            t_slices = (long long)__shfl(incl2, NACHO_WAVE - 1, NACHO_WAVE);
+        }
+        // state of the call: one total per chunk, one 32-bit word per workgroup; third-order tensors keep
+        // a second such pair behind the first for the slices
+        const int64_t state_half = n_chunks + (P + 1) / 2;
+        unsigned long long *totals = tile_state;
+        unsigned int *words = reinterpret_cast<unsigned int *>(tile_state + n_chunks);
+        unsigned long long *totals2 = tile_state + state_half;
+        unsigned int *words2 = reinterpret_cast<unsigned int *>(tile_state + state_half + n_chunks);
         if (lane == 0 && !published)
             __hip_atomic_store(&words[p], kWordValid | ((unsigned)t_rows << 14) | (unsigned)t_nnz, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        long long b_rows = 0, b_nnz = 0;
-        bool gave_up = false;
+        if (kCsf && lane == 0)
+            __hip_atomic_store(&words2[p], kWordValid | (unsigned)t_slices, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        long long b_rows = 0, b_nnz = 0, b_slices = 0, unused = 0;
         const int64_t chunk = p / kChunk, c0 = chunk * kChunk;
-        {
-            // words of the workgroups before this one in its chunk, all loads in flight together
-            const int m = (int)(p - c0);
-            int spins = 0;
-            for (bool first = true;; first = false) {
-                unsigned v[kChunk / NACHO_WAVE];
-                bool missing = false;
-#pragma unroll
-                for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
-                    const int j = i * NACHO_WAVE + lane;
-                    v[i] = first ? early[i] : kWordValid;
-                    if (!first && i * NACHO_WAVE < m && j < m)
-                        v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                int l_nnz = 0, l_rows = 0;
-#pragma unroll
-                for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
-                    missing = missing || !(v[i] & kWordValid);
-                    l_nnz += (int)(v[i] & 0x3fffu);
-                    l_rows += (int)((v[i] >> 14) & 0x3fffu);
-                }
-                if (__ballot(missing)) {                   // a predecessor has not published yet
-                    if (++spins > kSpinLimit) { gave_up = true; break; }
-                    __builtin_amdgcn_s_sleep(16);
-                    continue;
-                }
-                b_nnz = wave_sum<int>(l_nnz);
-                b_rows = wave_sum<int>(l_rows);
-                break;
-            }
-        }
-        if (!gave_up && (p == c0 + kChunk - 1 || p == P - 1) && lane == 0)
+        // words of the workgroups before this one in its chunk, all loads in flight together
+        bool ok = sum_words<true>(words, c0, (int)(p - c0), early, lane, b_nnz, b_rows);
+        if (kCsf && ok) ok = sum_words<false>(words2, c0, (int)(p - c0), early, lane, b_slices, unused);
+        if (ok && (p == c0 + kChunk - 1 || p == P - 1) && lane == 0) {
             __hip_atomic_store(&totals[chunk], kTotalValid | pack_counts(b_rows + t_rows, b_nnz + t_nnz),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (!gave_up && chunk > 0) {
+            if (kCsf)
+                __hip_atomic_store(&totals2[chunk], kTotalValid | pack_counts(0, b_slices + t_slices),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (ok && chunk > 0) {
             // totals of the chunks before this one
-            int spins = 0;
-            long long c_nnz = 0, c_rows = 0;
-            for (int64_t first = 0; first < chunk && !gave_up; ) {
-                const int64_t j = first + lane;
-                unsigned long long s = kTotalValid;
-                if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (__ballot(!(s & kTotalValid))) {
-                    if (++spins > kSpinLimit) { gave_up = true; break; }
-                    __builtin_amdgcn_s_sleep(16);
-                    continue;
-                }
-                c_nnz += wave_sum<long long>((long long)(s & 0x7fffffffull));
-                c_rows += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
-                first += NACHO_WAVE;
-            }
+            long long c_nnz = 0, c_rows = 0, c_slices = 0;
+            ok = sum_totals(totals, chunk, lane, c_nnz, c_rows);
+            if (kCsf && ok) ok = sum_totals(totals2, chunk, lane, c_slices, unused);
             b_nnz += c_nnz;
             b_rows += c_rows;
+            b_slices += c_slices;
         }
+        const bool gave_up = !ok;
         if (lane == 0) {
             w.base_nnz = b_nnz;
             w.base_rows = b_rows;
+            w.base_slices = b_slices;
             w.tile_cnt = tile_cnt;
             // a status once set to an error stays: the errors are ordered, the gravest wins
             if (gave_up) {
@@ -738,11 +867,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             if (p == P - 1 && !gave_up) {
                 // totals, tails and the capacity verdict (the only writer of these words)
                 const long long total_nnz = b_nnz + t_nnz;
-                const long long total_rows = FMT == SPADD_DCSR ? b_rows + t_rows
+                const long long total_rows = (FMT == SPADD_DCSR || kCsf) ? b_rows + t_rows
                                                                : (FMT == SPADD_CSR ? level0_extent(ops) : 1);
-                out.counts[0] = total_rows;
-                out.counts[1] = total_nnz;
-                const bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
+                const long long total_slices = b_slices + t_slices;
+                bool fits = total_nnz <= out.cap_nnz && (FMT != SPADD_DCSR || total_rows <= out.cap_rows);
+                if (kCsf) {
+                    // third-order tensors: {slices, fibres, entries}; the tails of the three pos arrays
+                    out.counts[0] = total_slices;
+                    out.counts[1] = total_rows;
+                    out.counts[2] = total_nnz;
+                    fits = fits && total_slices <= out.cap_rows && total_rows <= out.cap_fibres;
+                    out.pos0[0] = 0;
+                    out.pos0[1] = (int32_t)total_slices;
+                    if (total_slices <= out.cap_rows) out.pos1[total_slices] = (int32_t)total_rows;
+                    if (total_rows <= out.cap_fibres) out.pos2[total_rows] = (int32_t)total_nnz;
+                } else {
+                    out.counts[0] = total_rows;
+                    out.counts[1] = total_nnz;
+                }
                 if (!fits) atomicMin(out.status, (int32_t)NACHO_ERR_CAPACITY);
                 if (FMT == SPADD_VECTOR || kCoo) { out.pos1[0] = 0; out.pos1[1] = (int32_t)total_nnz; }
                 if (FMT == SPADD_CSR) out.pos1[level0_extent(ops)] = (int32_t)total_nnz;
@@ -787,16 +929,24 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             out.pos1[rr] = (int32_t)(base_nnz + at);
         }
     }
-    NACHO_GLOBAL int32_t *crd_out = global_out(out.crd1) + base_nnz;
+    NACHO_GLOBAL int32_t *crd_out = global_out(kCsf ? out.crd2 : out.crd1) + base_nnz;
     NACHO_GLOBAL T *val_out = global_out(static_cast<T *>(out.val)) + base_nnz;
     NACHO_GLOBAL int32_t *row_out = kCoo ? global_out(out.crd0) + base_nnz : nullptr;
     long long base_rows = 0;
     int room_rows = 0;
-    if (FMT == SPADD_DCSR) {
+    if (FMT == SPADD_DCSR || kCsf) {
         base_rows = ((long long)__builtin_amdgcn_readfirstlane((int)(w.base_rows >> 32)) << 32) |
                     (unsigned)__builtin_amdgcn_readfirstlane((int)(w.base_rows & 0xffffffffll));
-        const long long rr_ll = out.cap_rows - base_rows;
+        const long long rr_ll = (kCsf ? out.cap_fibres : out.cap_rows) - base_rows;
         room_rows = rr_ll < 0 ? 0 : (rr_ll > 0x7fffffffll ? 0x7fffffff : (int)rr_ll);
+    }
+    long long base_slices = 0;
+    int room_slices = 0;
+    if (kCsf) {
+        base_slices = ((long long)__builtin_amdgcn_readfirstlane((int)(w.base_slices >> 32)) << 32) |
+                      (unsigned)__builtin_amdgcn_readfirstlane((int)(w.base_slices & 0xffffffffll));
+        const long long ss_ll = out.cap_rows - base_slices;
+        room_slices = ss_ll < 0 ? 0 : (ss_ll > 0x7fffffffll ? 0x7fffffff : (int)ss_ll);
     }
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -806,7 +956,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                         (int)__builtin_amdgcn_mbcnt_hi((unsigned)(em[j] >> 32),
                                                        __builtin_amdgcn_mbcnt_lo((unsigned)em[j], 0u));
         if ((mine >> j & 1u) && loc < room) {
-            crd_out[loc] = (int32_t)(uint32_t)hk[j];
+            crd_out[loc] = (int32_t)col_of(hk[j]);
             if (kCoo) row_out[loc] = (int32_t)row_of(hk[j]);
             val_out[loc] = hv[j];
         }
@@ -817,6 +967,23 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             if ((mine >> (16 + j) & 1u) && rloc < room_rows) {
                 global_out(out.crd0)[base_rows + rloc] = (int32_t)row_of(hk[j]);
                 global_out(out.pos1)[base_rows + rloc] = (int32_t)(base_nnz + loc);
+            }
+        }
+        if constexpr (kCsf) {
+            // a fibre head writes its j and where its entries start; a slice head its i and where its fibres start
+            const int floc = (int)(loc_b >> 16) +
+                             (int)__builtin_amdgcn_mbcnt_hi((unsigned)(rm[j] >> 32),
+                                                            __builtin_amdgcn_mbcnt_lo((unsigned)rm[j], 0u));
+            if ((mine >> (16 + j) & 1u) && floc < room_rows) {
+                global_out(out.crd1)[base_rows + floc] = (int32_t)(uint32_t)hk[j].hi;
+                global_out(out.pos2)[base_rows + floc] = (int32_t)(base_nnz + loc);
+            }
+            const int sloc = (int)w.blk_loc2[j * kWaves + wave] +
+                             (int)__builtin_amdgcn_mbcnt_hi((unsigned)(sm[j] >> 32),
+                                                            __builtin_amdgcn_mbcnt_lo((unsigned)sm[j], 0u));
+            if ((mine >> (27 + j) & 1u) && sloc < room_slices) {
+                global_out(out.crd0)[base_slices + sloc] = (int32_t)row_of(hk[j]);
+                global_out(out.pos1)[base_slices + sloc] = (int32_t)(base_rows + floc);
             }
         }
     }
@@ -856,11 +1023,14 @@ int spadd_capacity(int fmt, int dtype)
 {
     if (fmt == SPADD_VECTOR)
         return dtype == NACHO_F64 ? Shape<uint32_t, double>::kCapacity : Shape<uint32_t, float>::kCapacity;
+    if (fmt == SPADD_CSF3)
+        return dtype == NACHO_F64 ? Shape<Key3, double>::kCapacity : Shape<Key3, float>::kCapacity;
     return dtype == NACHO_F64 ? Shape<uint64_t, double>::kCapacity : Shape<uint64_t, float>::kCapacity;
 }
 
-// 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup
-int64_t spadd_state_words(int64_t P) { return chunks_of(P) + (P + 1) / 2; }
+// 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup -- twice (third-order
+// tensors count slices in the second set)
+int64_t spadd_state_words(int64_t P) { return 2 * (chunks_of(P) + (P + 1) / 2); }
 
 hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,
                         int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
@@ -877,6 +1047,7 @@ hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &op
     NACHO_SPADD_CASE(SPADD_VECTOR, true)
     NACHO_SPADD_CASE(SPADD_COO, false)
     NACHO_SPADD_CASE(SPADD_COO, true)
+    NACHO_SPADD_CASE(SPADD_CSF3, false)
     if (fmt == SPADD_CSR && multiply && ops.start[0]) {       // remapped operands of a DCSR product
         if (dtype == NACHO_F64)
             return launch_one<SPADD_CSR, double, true, true>(ops, vals, P, coord, posn, tile_state, out, s);

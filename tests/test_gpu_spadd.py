@@ -18,7 +18,7 @@ TOL = {np.float32: 1e-5, np.float64: 1e-12}
 
 def _finish(out):
     torch.cuda.synchronize()
-    rows, nnz = (int(v) for v in out.counts.cpu().numpy())
+    rows, nnz = (int(v) for v in out.counts.cpu().numpy()[:2])
     return rows, nnz, int(out.status.cpu().numpy()[0])
 
 

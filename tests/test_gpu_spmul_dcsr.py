@@ -42,7 +42,7 @@ def run(mats, shape, P, tag, cap_rows=None, cap_nnz=None, check_parts=True):
     ws = torch.empty(nb.workspace_bytes(nb.OP_SPMUL, ops, dt, 0, P), dtype=torch.uint8, device="cuda")
     nb.nacho_spmul_k(ops, out, P=P, ws=ws)
     torch.cuda.synchronize()
-    rows, nnz = (int(v) for v in out.counts.cpu().numpy())
+    rows, nnz = (int(v) for v in out.counts.cpu().numpy()[:2])
     status = int(out.status.cpu().numpy()[0])
     ref = oracle.spmul_dcsr(mats)
     parts = None
@@ -198,7 +198,7 @@ def test_workspace_too_small_and_reuse():
     for rep in range(2):
         nb.nacho_spmul_k(ops, out, ws=ws)
         torch.cuda.synchronize()
-        assert out.counts.cpu().numpy().tolist() == [ref["crd0"].shape[0], ref["crd1"].shape[0]]
+        assert out.counts.cpu().numpy()[:2].tolist() == [ref["crd0"].shape[0], ref["crd1"].shape[0]]
         assert np.array_equal(out.crd1.cpu().numpy()[:ref["crd1"].shape[0]], ref["crd1"])
 
 
@@ -224,7 +224,7 @@ def test_the_call_only_enqueues():
     assert not done.query(), "the call waited for the stream"
     torch.cuda.synchronize()
     ref = oracle.spmul_dcsr(mats)
-    assert out.counts.cpu().numpy().tolist() == [ref["crd0"].shape[0], ref["crd1"].shape[0]]
+    assert out.counts.cpu().numpy()[:2].tolist() == [ref["crd0"].shape[0], ref["crd1"].shape[0]]
     assert int(out.status.cpu().numpy()[0]) == 0
     assert np.array_equal(out.crd1.cpu().numpy()[:ref["crd1"].shape[0]], ref["crd1"])
     assert np.array_equal(out.crd0.cpu().numpy()[:ref["crd0"].shape[0]], ref["crd0"])
