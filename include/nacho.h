@@ -278,9 +278,23 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
                    void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
- * Z = sum_t ops[t]: the union of k sparse vectors, CSR or DCSR matrices with
- * sorted output coordinates; coinciding values are added in operand order.
- * Pipeline: partition -> count -> exclusive scan -> fill.
+ * Z = sum_t ops[t]: the union of k sparse vectors, CSR, DCSR or COO matrices
+ * or third-order CSF tensors with sorted output coordinates; coinciding values
+ * are added in operand order.  Two kernels: the partition search, then one
+ * merge kernel whose workgroup p stages, merges, assembles and writes
+ * partition p.
+ *
+ * Where workgroup p writes depends on what the workgroups before it emit, and
+ * it learns that inside the kernel: every workgroup publishes its counts in
+ * the workspace and reads those of its predecessors, polling a bounded number
+ * of times for the ones not there yet.  This relies on the GPU starting the
+ * workgroups of a launch in the order of their indices, so that a workgroup
+ * only ever waits for workgroups that are already running or done; HIP does
+ * not promise that order, every AMD GPU so far keeps it.  Should a wait run
+ * out all the same (about 2^14 polls of a few hundred nanoseconds each), the
+ * workgroup writes nothing and *status becomes NACHO_ERR_HIP: the output is
+ * then incomplete and the call must be repeated.  Among several conditions the
+ * gravest (lowest) status wins.
  */
 int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream);

@@ -245,18 +245,15 @@ __device__ inline void windows_init(const DevOperands &ops, int m, const int *se
 // boundary coordinate x in operand t lies in [l_t, h_t], and so does the
 // position of x + 1.  With that, clamping any coordinate's lower bounds into
 // the windows preserves "cost <= R  <=>  coordinate <= x".
-//   narrow_only: shrink the windows around the whole query range while that
-//                pays (used once for a group of neighbouring boundaries) and
-//                return; the result is in W.
-//   otherwise:   R_lo == R_hi; runs until the boundary is found.
+// Runs until the boundary of query R is found.
 template <bool kLast, int K, class Acc = PlainCoords, bool kDeep = false>
-__device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R_lo64, int64_t R_hi64,
-                                      Windows<K> &W, bool narrow_only, int *p, const int *sh)
+__device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, int m, int64_t R64, Windows<K> &W,
+                                                      int *p, const int *sh)
 {
     typedef typename Acc::type CoordT;
     // costs, positions and coordinates all fit 32 bits (the operands hold fewer than
     // 2^31 entries together; INT32_MAX is no coordinate)
-    const int R_lo = (int)R_lo64, R_hi = (int)R_hi64;
+    const int R_lo = (int)R64, R_hi = (int)R64;      // (the bounds below are written for a range of queries)
     const int lane = lane_id();
     const int k = ops.k;
     int base[K], l[K], h[K], cl[K], ch[K];
@@ -284,12 +281,11 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             total += w[t];
             if (w[t] > NACHO_WAVE) all_small = false;
         }
-        if (narrow_only && (all_small || total > prev_total / 4)) break;   // no longer pays
         if (!all_small && total >= prev_total) {
             int64_t c0 = 0;
 #pragma unroll
             for (int t = 0; t < K; ++t) c0 += cl[t];
-            return tracked_search<kLast, K, Acc, kDeep>(ops, m, R_lo64, base, l, h, c0, p, sh);
+            return tracked_search<kLast, K, Acc, kDeep>(ops, m, R64, base, l, h, c0, p, sh);
         }
         prev_total = total;
 #pragma unroll
@@ -426,7 +422,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             }
             l[u] = nl; cl[u] = ncl; h[u] = nh; ch[u] = nch;
         }
-        if (all_small && !narrow_only) {
+        if (all_small) {
             if (vminus < 0) {                           // cannot happen for an interior query
                 int64_t c0 = 0;
 #pragma unroll
@@ -434,7 +430,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
                     l[t] = W.l[t]; h[t] = W.h[t];
                     c0 += W.cl[t];
                 }
-                return tracked_search<kLast, K, Acc, kDeep>(ops, m, R_lo64, base, l, h, c0, p, sh);
+                return tracked_search<kLast, K, Acc, kDeep>(ops, m, R64, base, l, h, c0, p, sh);
             }
             r.x = vminus;
 #pragma unroll
@@ -445,11 +441,6 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             return r;
         }
     }
-#pragma unroll
-    for (int t = 0; t < K; ++t) {
-        W.l[t] = l[t]; W.h[t] = h[t]; W.cl[t] = cl[t]; W.ch[t] = ch[t];
-    }
-    return r;
 }
 
 // One level of Algorithm 1 for one query, starting from windows that bracket the
@@ -500,7 +491,7 @@ __device__ __forceinline__ LevelResult compressed_level(const DevOperands &ops, 
         for (int t = 0; t < K; ++t) c0 += W.cl[t];
         return tracked_search<kLast, K, Acc, kDeep>(ops, m, R, W.base, W.l, W.h, c0, p, sh);
     }
-    return sampled_search<kLast, K, Acc, kDeep>(ops, m, R, R, W, false, p, sh);
+    return sampled_search<kLast, K, Acc, kDeep>(ops, m, R, W, p, sh);
 }
 
 template <bool kLast, int K>
@@ -516,13 +507,9 @@ __device__ inline int64_t level_total(const DevOperands &ops, int m, const int *
     return total;
 }
 
-constexpr int kGroup = 1;   // neighbouring boundaries one wavefront searches
-
 }  // namespace
 
-// One wavefront searches kGroup neighbouring boundaries: their searches share
-// the first rounds (the windows are narrowed once around the whole group), then
-// every boundary is finished on its own from the shared windows.
+// One wavefront searches one boundary.
 // kMode: 0 = vectors, CSR, DCSR; 1 = coordinate lists; 2 = three compressed levels (CSF).  The
 // last two are instantiations of their own: the other formats keep their register budget.
 template <int K, int kMode>
@@ -537,8 +524,8 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
         P = ops.dyn_plan[0];
         total_unscaled = ops.dyn_plan[2];
     }
-    const int64_t b0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE) * kGroup;
-    if (b0 > P) return;                      // whole wavefront leaves together
+    const int64_t b = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / NACHO_WAVE;
+    if (b > P) return;                       // whole wavefront leaves together
     const int lane = lane_id();
     const int k = ops.k, d = ops.d;
     const int64_t total_scaled = total_unscaled * cost_scale;
@@ -546,28 +533,15 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
     constexpr bool pairs = kMode == 1;                              // coordinate lists (COO), d == 2
     constexpr bool csf3 = kMode == 2;                               // three compressed levels, d == 3
 
-    int64_t Qu[kGroup];
-    bool interior[kGroup];
-    int64_t q_first = -1, q_last = -1;
-#pragma unroll
-    for (int g = 0; g < kGroup; ++g) {
-        const int64_t b = b0 + g;
-        int64_t Q = 0;
-        if (b <= P) {
-            if (queries) Q = queries[b];
-            else if (grain > 0) Q = b * grain < total_scaled ? b * grain : total_scaled;
-            else Q = equal_query(b, total_scaled, P);
-        }
-        if (Q < 0) Q = 0;
-        Qu[g] = Q / cost_scale;
-        interior[g] = b > 0 && b < P && Qu[g] < total_unscaled;
-        if (interior[g]) {
-            if (q_first < 0 || Qu[g] < q_first) q_first = Qu[g];
-            if (Qu[g] > q_last) q_last = Qu[g];
-        }
-    }
+    int64_t Q = 0;
+    if (queries) Q = queries[b];
+    else if (grain > 0) Q = b * grain < total_scaled ? b * grain : total_scaled;
+    else Q = equal_query(b, total_scaled, P);
+    if (Q < 0) Q = 0;
+    const int64_t Qu = Q / cost_scale;
+    const bool interior = b > 0 && b < P && Qu < total_unscaled;
 
-    // level-0 segments and, for a compressed level 0, windows shared by the group
+    // level-0 segments and, for a compressed level 0, the windows the search starts from
     int seg0_lo[K], seg0_hi[K];
 #pragma unroll
     for (int t = 0; t < K; ++t) {
@@ -581,27 +555,17 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
 #pragma unroll
     for (int t = 0; t < K; ++t) no_shift[t] = 0;
     Windows<K> W0;
-    if (!dense0 && q_first >= 0) {
-        int dummy[K];
-        if (pairs) {
-            windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
-        } else if (csf3) {
-            windows_init<false, K, true>(ops, 0, seg0_lo, seg0_hi, W0);
-        } else if (d == 1) {
-            windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
-            if (q_last > q_first) sampled_search<true, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
-        } else {
-            windows_init<false, K>(ops, 0, seg0_lo, seg0_hi, W0);
-            if (q_last > q_first) sampled_search<false, K>(ops, 0, q_first, q_last, W0, true, dummy, no_shift);
-        }
+    if (!dense0 && interior) {
+        if (pairs) windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
+        else if (csf3) windows_init<false, K, true>(ops, 0, seg0_lo, seg0_hi, W0);
+        else if (d == 1) windows_init<true, K>(ops, 0, seg0_lo, seg0_hi, W0);
+        else windows_init<false, K>(ops, 0, seg0_lo, seg0_hi, W0);
     }
 
-    for (int g = 0; g < kGroup; ++g) {
-        const int64_t b = b0 + g;
-        if (b > P) break;
+    {
         int32_t *cb = coord + b * d;
         int32_t *pb = posn + b * (int64_t)k * d;
-        if (!interior[g]) {
+        if (!interior) {
             const bool end = (b != 0);
             if (lane == 0) {
                 for (int m = 0; m < d; ++m) cb[m] = 0;
@@ -616,10 +580,10 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                     }
                 cost[b] = end ? total_scaled : 0;
             }
-            continue;
+            return;
         }
         int seg_lo[K], seg_hi[K], p[K];
-        int64_t R = Qu[g];
+        int64_t R = Qu;
         if (pairs) {
             // one search over the (row, column) pairs; the row-level position of an operand is
             // that of its first entry in the boundary's row
@@ -752,7 +716,7 @@ partition_kernel(DevOperands ops, int64_t cost_scale, int64_t P, int64_t grain,
                     }
             }
         }
-        if (lane == 0) cost[b] = (Qu[g] - R) * cost_scale;
+        if (lane == 0) cost[b] = (Qu - R) * cost_scale;
     }
 }
 
@@ -908,7 +872,7 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
         return hipGetLastError();
     }
     if (zero_rows || row_cost != 0) return hipErrorInvalidValue;      // only the one-pass kernel above does these
-    int64_t waves = (P + 1 + kGroup - 1) / kGroup;
+    int64_t waves = P + 1;
     if (clear.n > waves * NACHO_WAVE) waves = (clear.n + NACHO_WAVE - 1) / NACHO_WAVE;
     const int waves_per_block = 256 / NACHO_WAVE;
     const unsigned grid = (unsigned)((waves + waves_per_block - 1) / waves_per_block);
