@@ -411,6 +411,24 @@ def bench_others(steps, warmup, only=None, ceilings=None):
             record("F2_csr2", f"CSR Hadamard product of the same two matrices, {tot} input nnz, {n_mul} output nnz",
                    fm, tot, tot * 8 + n_mul * 8 + 3 * (cfg["n_rows"] + 1) * 4)
         del ops, out, ws, cfg
+    if want("F4_csf3"):
+        cfg = workloads.csf3_add_config()
+        names = ("pos0", "crd0", "pos1", "crd1", "pos2", "crd2")
+        ops = [nb.csf3(*[dev(t[n]) for n in names], cfg["shape"], dev(t["val"])) for t in cfg["ops"]]
+        tot = sum(int(t["crd2"].shape[0]) for t in cfg["ops"])
+        fib = sum(int(t["crd1"].shape[0]) for t in cfg["ops"])
+        sl = sum(int(t["crd0"].shape[0]) for t in cfg["ops"])
+        out = nb.SparseOut("csf3", sl, tot, torch.float32, "cuda", cap_fibres=fib)
+        ws = torch.empty(nb.workspace_bytes(nb.OP_SPADD, ops, nb.F32), dtype=torch.uint8, device="cuda")
+        fn = lambda: nb.nacho_spadd_k(ops, out, ws=ws)
+        fn()
+        torch.cuda.synchronize()
+        s_out, f_out, n_out = (int(v) for v in out.counts.cpu().numpy())
+        nbytes = (tot + n_out) * 8 + (fib + f_out) * 8 + (sl + s_out) * 8
+        record("F4_csf3", f"CSF + CSF, third-order tensors {cfg['shape']}, fp32 union add, {tot} input nnz in {fib} "
+               f"fibres, {n_out} output nnz in {f_out} fibres and {s_out} slices", fn, tot, nbytes,
+               table=lambda: nb.workspace_parts(nb.OP_SPADD, ops, nb.F32, ws), main_kernel="spadd_merge")
+        del ops, out, ws, cfg
     if not want("C5"):
         return res
     cfg = workloads.config(5)
@@ -438,7 +456,7 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="time configuration 2 only (skip the other configurations)")
     ap.add_argument("--only", default=None,
-                    help="comma-separated workload tags (C3, C4, C5, F1_k2, F1_k3, F1_k8): time only these, "
+                    help="comma-separated workload tags (C3, C4, C5, F1_k2, F1_k3, F4_csf3, F1_k8): time only these, "
                          "print their records and skip the headline (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run two device-to-device copies of 256 MiB (a kernel of known "

@@ -181,6 +181,45 @@ def sparse_vector(n, extent, seed, dtype, share_from=None, share_frac=0.0):
             "v": _uniform_values(rng, idx.shape[0], dtype)}
 
 
+def csf3_tensor(shape, nnz, seed, dtype, share_from=None, share_frac=0.0):
+    """Third-order tensor with three compressed levels (CSF): `nnz` distinct coordinates uniform over
+    `shape`, a fraction `share_frac` of them taken from the linearised coordinates `share_from` of
+    another tensor.  Returns the six level arrays (int32), the values and `lin`, the sorted linearised
+    coordinates (i * J + j) * K + k."""
+    rng = np.random.default_rng(seed)
+    I, J, K = (int(v) for v in shape)
+    parts, n_shared = [], 0
+    if share_from is not None and share_frac > 0 and share_from.shape[0] > 0:
+        n_shared = min(int(round(nnz * share_frac)), share_from.shape[0])
+        parts.append(share_from[rng.choice(share_from.shape[0], size=n_shared, replace=False)])
+    parts.append(_sorted_unique_indices(rng, nnz - n_shared, I * J * K))
+    lin = np.unique(np.concatenate(parts))
+    i, rest = np.divmod(lin, J * K)
+    j, k = np.divmod(rest, K)
+    n = lin.shape[0]
+    ij = i * J + j
+    fibre_first = np.flatnonzero(np.concatenate([[True], ij[1:] != ij[:-1]])) if n else np.zeros(0, np.int64)
+    fi = i[fibre_first]                                         # slice of every fibre
+    slice_first = np.flatnonzero(np.concatenate([[True], fi[1:] != fi[:-1]])) if n else np.zeros(0, np.int64)
+    i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+    return {"shape": (I, J, K), "lin": lin,
+            "pos0": i32([0, slice_first.shape[0]]), "crd0": i32(fi[slice_first]),
+            "pos1": i32(np.append(slice_first, fibre_first.shape[0])), "crd1": i32(j[fibre_first]),
+            "pos2": i32(np.append(fibre_first, n)), "crd2": i32(k),
+            "val": _uniform_values(rng, n, dtype)}
+
+
+def csf3_add_config(k=2, shape=(2000, 2000, 2000), nnz_each=8_000_000, seed=71, share_frac=0.2, dtype=np.float32):
+    """k third-order CSF tensors of one shape for the k-way tensor addition (the shape of the paper's
+    FROSTT-style operands: a few thousand coordinates per mode, millions of non-zeros; 20 % of the later
+    operands' coordinates coincide with the first one's)."""
+    a = csf3_tensor(shape, nnz_each, seed, dtype)
+    ops = [a]
+    for t in range(1, k):
+        ops.append(csf3_tensor(shape, nnz_each, seed + 7919 * t, dtype, share_from=a["lin"], share_frac=share_frac))
+    return {"kind": "spadd_csf3", "ops": ops, "shape": tuple(int(v) for v in shape)}
+
+
 # --------------------------------------------------------------------------- #
 # the five configurations (scale < 1 shrinks sizes for CPU-side tests)
 # --------------------------------------------------------------------------- #

@@ -100,3 +100,22 @@ def test_empty_operands_and_empty_result():
     one = _tensor(np.array([[2, 3, 4]]), np.array([0.5]))
     r = oracle.spadd_csf3([z, one, z])
     assert _expand(r) == [(2, 3, 4)] and r["val"].tolist() == [0.5]
+
+
+def test_generated_benchmark_tensors_are_valid_csf_and_add_up():
+    """The seeded CSF generator the benchmark uses: its level arrays equal those rebuilt from its own
+    coordinate list, and the oracle's sum of two of its tensors matches numpy.unique."""
+    from paper_2604_17198_amd import workloads
+    shape = (20, 30, 40)
+    cfg = workloads.csf3_add_config(k=2, shape=shape, nnz_each=3000, seed=5)
+    names = ("pos0", "crd0", "pos1", "crd1", "pos2", "crd2")
+    for t in cfg["ops"]:
+        coords = np.stack(np.unravel_index(t["lin"], shape), axis=1)
+        for n, a in zip(names, to_csf3(coords)):
+            assert np.array_equal(t[n], a), n
+    r = oracle.spadd_csf3(cfg["ops"])
+    union = np.unique(np.concatenate([t["lin"] for t in cfg["ops"]]))
+    got = np.array(_expand(r), dtype=np.int64)
+    assert np.array_equal((got[:, 0] * shape[1] + got[:, 1]) * shape[2] + got[:, 2], union)
+    shared = np.intersect1d(cfg["ops"][0]["lin"], cfg["ops"][1]["lin"]).shape[0]
+    assert shared >= 0.15 * 3000                       # the forced coincidences are there
