@@ -195,11 +195,15 @@ def test_third_order_csf_random(k):
             _compare(got, oracle.partition(o, P), (k, trial, P))
 
 
-def test_third_order_csf_is_partition_only():
+def test_third_order_csf_product_is_refused_and_its_sum_needs_three_output_levels():
     c = np.array([[0, 1, 2], [1, 0, 0]], dtype=np.int64)
     arrs = [dev(a) for a in to_csf3(c)]
     op = nb.csf3(*arrs, (2, 2, 3), dev(np.ones(2, np.float32)))
     out = nb.SparseOut("vector", 0, 4, torch.float32, "cuda")
     with pytest.raises(nb.NachoError) as e:
-        nb.nacho_spadd_k([op, op], out)
+        nb.nacho_spadd_k([op, op], out)                 # (an output without pos0 / pos2 / crd2)
+    assert e.value.status == -1
+    out3 = nb.SparseOut("csf3", 4, 4, torch.float32, "cuda", cap_fibres=4)
+    with pytest.raises(nb.NachoError) as e:
+        nb.nacho_spmul_k([op, op], out3)
     assert e.value.status == -2
