@@ -25,7 +25,9 @@ namespace {
 
 constexpr int kLongRow = 192;  // products per row above which the wavefront sums it together
 
-template <typename T, int G, int RBLK>
+// kDealt: the partitions come from fixed-grain queries (grain > 0) and are dealt out by XCD; the
+// instantiation without it serves arbitrary partition tables (caller's P, the row-aware cost).
+template <typename T, int G, int RBLK, bool kDealt>
 __global__ void __launch_bounds__(NACHO_WAVE)
 spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                  const T *__restrict__ val, const T *__restrict__ x, T *__restrict__ y,
@@ -49,7 +51,7 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     // partitions (stretches as long as there are such workgroups): a
     // permutation of first .. end - 1; everything else keeps its index.
     int p = blockIdx.x;
-    if (grain > 0) {
+    if (kDealt) {
         const int r = coord[2 * p];
         if (r < n_rows) {
             const int base = pos[0];
@@ -259,16 +261,18 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
                             const int32_t *coord, const int32_t *posn, int64_t P,
                             void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream)
 {
-    if (dtype == NACHO_F64)
-        hipLaunchKernelGGL((spmv_exec_kernel<double, kGrainF64, kRowsF64>), dim3((unsigned)P),
-                           dim3(NACHO_WAVE), 0, stream, pos, crd, (const double *)val,
-                           (const double *)x, (double *)y, (int)nnz, coord, posn,
-                           (double *)carry_val, carry_row, (int)n_rows, (int)grain, nacho_host::wave_log());
-    else
-        hipLaunchKernelGGL((spmv_exec_kernel<float, kGrainF32, kRowsF32>), dim3((unsigned)P),
-                           dim3(NACHO_WAVE), 0, stream, pos, crd, (const float *)val,
-                           (const float *)x, (float *)y, (int)nnz, coord, posn,
-                           (float *)carry_val, carry_row, (int)n_rows, (int)grain, nacho_host::wave_log());
+#define NACHO_SPMV_LAUNCH(T, G, R, DEALT)                                                               \
+    hipLaunchKernelGGL((spmv_exec_kernel<T, G, R, DEALT>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, stream, pos, \
+                       crd, (const T *)val, (const T *)x, (T *)y, (int)nnz, coord, posn, (T *)carry_val,       \
+                       carry_row, (int)n_rows, (int)grain, nacho_host::wave_log())
+    if (dtype == NACHO_F64) {
+        if (grain > 0) NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, true);
+        else NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, false);
+    } else {
+        if (grain > 0) NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, true);
+        else NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, false);
+    }
+#undef NACHO_SPMV_LAUNCH
     return hipGetLastError();
 }
 
