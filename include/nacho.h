@@ -271,7 +271,9 @@ size_t nacho_static_scratch_bytes(void);
  * C = A B with A in CSR and B, C dense row-major (loop order i -> j -> k, dense
  * k innermost; cost of a stored non-zero = n, the broadcast extent).
  *   B[n_cols(A) x n] leading dimension ldb,  C[n_rows(A) x n] leading dimension
- *   ldc (elements); 1 <= n <= 64 per call in this version.
+ *   ldc (elements); n >= 1.  The executing kernel covers 64 columns at a time:
+ *   a wider B goes through it in stretches of 64 columns over the same
+ *   partitions (A is then read once per stretch).
  */
 int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
                    void *C, int64_t ldc, int32_t dtype, int64_t P,

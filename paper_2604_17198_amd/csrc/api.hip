@@ -421,7 +421,7 @@ int32_t nacho_workspace_parts(int32_t op, const nacho_tensor *ops, int32_t k, in
     case NACHO_OP_SPMV:
     case NACHO_OP_SPMM: {
         if (k != 1 || fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
-        if (op == NACHO_OP_SPMM && (n_dense < 1 || n_dense > NACHO_WAVE)) return NACHO_ERR_INVALID_ARG;
+        if (op == NACHO_OP_SPMM && n_dense < 1) return NACHO_ERR_INVALID_ARG;
         Pe = fused_partitions(op, fmt, dtype, k, total, P);
         CarryWs c = carve_carry(ws, Pe, dtype, op == NACHO_OP_SPMM ? NACHO_WAVE : 1);
         w = c.parts;
@@ -596,7 +596,7 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
     if (!A || !B || !C || P < 0) return NACHO_ERR_INVALID_ARG;
     if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
     if (n < 1 || ldb < n || ldc < n) return NACHO_ERR_INVALID_ARG;
-    if (n > NACHO_WAVE) return NACHO_ERR_UNSUPPORTED;
+    if (n > (int64_t)1 << 20) return NACHO_ERR_UNSUPPORTED;     // (costs are n per non-zero: n * nnz stays far below 2^63)
     DevOperands dev;
     int64_t nnz = 0;
     Format fmt;
@@ -620,13 +620,24 @@ int32_t nacho_spmm(const nacho_tensor *A, const void *B, int64_t n, int64_t ldb,
                          nullptr, &zero) != hipSuccess)
         return NACHO_ERR_HIP;
     profile_mark("partition");
-    if (launch_spmm_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, B, (int)n, ldb, C, ldc,
-                         w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spmm_exec");
-    if (launch_spmm_fixup(dtype, C, ldc, (int)n, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain / n, s) != hipSuccess)
-        return NACHO_ERR_HIP;
-    profile_mark("spmm_fixup");
+    // The executing kernel gives every lane of a wavefront one column of B: wider operands go through it
+    // in stretches of 64 columns.  The partitions are the same for every stretch (the queries are multiples
+    // of n, so no boundary falls inside the dense loop), and so are the carry buffers, which the stretches
+    // use one after the other on the stream.
+    const size_t elem = dtype_size(dtype);
+    for (int64_t j0 = 0; j0 < n; j0 += NACHO_WAVE) {
+        const int width = (int)(n - j0 < NACHO_WAVE ? n - j0 : NACHO_WAVE);
+        const void *Bj = static_cast<const char *>(B) + (size_t)j0 * elem;
+        void *Cj = static_cast<char *>(C) + (size_t)j0 * elem;
+        if (launch_spmm_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, Bj, width, ldb, Cj, ldc,
+                             w.parts.coord, w.parts.posn, Pe, w.carry_val, w.carry_row, s) != hipSuccess)
+            return NACHO_ERR_HIP;
+        profile_mark("spmm_exec");
+        if (launch_spmm_fixup(dtype, Cj, ldc, width, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain / n, s) !=
+            hipSuccess)
+            return NACHO_ERR_HIP;
+        profile_mark("spmm_fixup");
+    }
     return NACHO_OK;
 }
 

@@ -103,9 +103,26 @@ def test_config5_full_size():
     _check(cfg["A"], cfg["B"], 0, "config5 full")
 
 
-def test_unsupported_width():
-    cfg = workloads.config(1)
-    B = torch.zeros((4096, 65), dtype=torch.float64, device="cuda")
-    with pytest.raises(nb.NachoError) as e:
-        nb.nacho_spmm(csr_operand(cfg["A"]), B)
-    assert e.value.status == -2
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_more_than_64_dense_columns(dtype):
+    """Wider operands go through the executing kernel in stretches of 64 columns (ragged last one)."""
+    rng = np.random.default_rng(33)
+    cfg = workloads.config(5, scale=0.01)
+    A = dict(cfg["A"])
+    A["val"] = A["val"].astype(dtype)
+    for n in (65, 100, 128, 200):
+        B = rng.uniform(-1, 1, (A["n_cols"], n)).astype(dtype)
+        for P in (0, 7):
+            _check(A, B, P, f"wide{n}")
+    # a leading dimension wider than n, and a row that spans many partitions
+    c = np.stack([np.full(3000, 5, np.int64), np.arange(3000)], 1)
+    pos, crd = to_csr(c, 9)
+    A1 = {"n_rows": 9, "n_cols": 3000, "pos": pos, "crd": crd, "val": rng.uniform(-1, 1, 3000).astype(dtype)}
+    Bfull = dev(rng.uniform(-1, 1, (3000, 160)).astype(dtype))
+    Cfull = torch.full((9, 170), float("nan"), dtype=Bfull.dtype, device="cuda")
+    nb.nacho_spmm(csr_operand(A1), Bfull[:, :150], Cfull[:, :150], P=40)
+    torch.cuda.synchronize()
+    ref, sabs = oracle.spmm(A1["pos"], A1["crd"], A1["val"], Bfull[:, :150].cpu().numpy())
+    got = Cfull.cpu().numpy()
+    assert tol_ok(got[:, :150], ref, sabs, TOL[dtype]).all()
+    assert np.isnan(got[:, 150:]).all(), "columns beyond n were written"
