@@ -193,6 +193,23 @@ int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, 
                         void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * nacho_partition for ONE CSR operand whose positions are 64-bit: operands of
+ * 2^31 stored non-zeros or more, which the int32 descriptors above cannot
+ * describe (Section 4.2.2's CSR cost functions, C_i(x) = pos[x] and the count
+ * of the row's entries before a column; equal-share queries
+ * Q_p = floor(p * nnz / P)).
+ *   pos     device int64[n_rows + 1], non-decreasing, pos[0] = 0, pos[n_rows] = nnz
+ *   crd     device int32[nnz], 16-byte aligned
+ *   coord   device int32[(P+1) * 2]   (row, column) of every boundary
+ *   posn    device int64[(P+1) * 2]   (row, position of the first entry not
+ *           before the boundary)
+ *   cost    device int64[P+1]
+ * Rows and columns stay below 2^31.  Enqueues only.  Errors: INVALID_ARG, HIP.
+ */
+int32_t nacho_partition_csr64(const int64_t *pos, const int32_t *crd, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                              int64_t P, int32_t *coord, int64_t *posn, int64_t *cost, void *hip_stream);
+
+/*
  * Where a fused call keeps its stored partitions (Section 4.2.3: the positions
  * found by the search are kept for the assembly and compute stages).  Fills
  * `parts` (host struct) with the number of partitions the fused call `op` uses

@@ -182,6 +182,59 @@ def partition(ops, P, queries=None, tail_extent=0):
     return {"coord": coord, "posn": posn, "cost": cost}
 
 
+def partition_csr64(pos, row_crd, n_cols, P):
+    """Algorithm 1 (Section 3.2) for ONE CSR operand whose positions do not fit 32 bits, in plain Python
+    integers (the C oracle above describes operands with int32 arrays).  Cost functions of Section 4.2.2:
+    C_i(x) = stored non-zeros in the rows before x = pos[x] (pos[0] = 0); C_j(c | x) = entries of row x in
+    columns before c.  `pos`: integer array [n_rows + 1]; `row_crd(r)`: the sorted column coordinates
+    of row r (only the rows that hold a boundary are asked for); queries Q_p = floor(p * Q_total / P).
+    Conventions as partition(): boundary 0 is the origin, boundary P (and any query that reaches
+    Q_total) the end; on a flat stretch of a cost function the highest coordinate is taken.
+    Returns dict(coord[P+1, 2], posn[P+1, 2], cost[P+1]) of int64 (k = 1: posn has no operand axis)."""
+    n_rows = len(pos) - 1
+    base = int(pos[0])
+    total = int(pos[n_rows]) - base
+    coord = np.zeros((P + 1, 2), dtype=np.int64)
+    posn = np.zeros((P + 1, 2), dtype=np.int64)
+    cost = np.zeros(P + 1, dtype=np.int64)
+    for p in range(P + 1):
+        Q = (p * total) // P
+        if p == 0:
+            posn[p] = (0, base)
+            continue
+        if p == P or Q >= total:
+            coord[p] = (n_rows, 0)
+            posn[p] = (n_rows, int(pos[n_rows]))
+            cost[p] = total
+            continue
+        # level 0: the highest row x in [0, n_rows] whose cost C_i(x) does not exceed the query
+        lo, hi = 0, n_rows
+        while lo < hi:
+            x = lo + (hi - lo + 1) // 2
+            if int(pos[x]) - base <= Q:
+                lo = x
+            else:
+                hi = x - 1
+        x0 = lo
+        R = Q - (int(pos[x0]) - base)
+        # level 1: the highest column c in [0, n_cols] with C_j(c | x0) <= the residual
+        crd = np.asarray(row_crd(x0))
+        before = lambda c: int(np.searchsorted(crd, c, side="left"))      # entries of the row in columns < c
+        lo, hi = 0, n_cols
+        while lo < hi:
+            c = lo + (hi - lo + 1) // 2
+            if before(c) <= R:
+                lo = c
+            else:
+                hi = c - 1
+        x1 = lo
+        R -= before(x1)
+        coord[p] = (x0, x1)
+        posn[p] = (x0, int(pos[x0]) + before(x1))
+        cost[p] = Q - R
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
 def partition_rowcost(ops, P, row_cost, queries=None):
     """All P+1 boundaries of two-level operands under the row-aware cost (every level-0 position costs
     `row_cost` on top of its stored non-zeros).  Same result layout as partition()."""

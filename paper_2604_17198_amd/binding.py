@@ -28,7 +28,7 @@ EXPORTS = [
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
     "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
     "nacho_probe", "nacho_merge_wavefronts", "nacho_rowcost_partitions", "nacho_partition_rowcost",
-    "nacho_spmv_rowcost",
+    "nacho_spmv_rowcost", "nacho_partition_csr64",
 ]
 
 
@@ -104,6 +104,8 @@ def lib():
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
+        L.nacho_partition_csr64.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_rowcost_partitions.restype = C.c_int64
         L.nacho_rowcost_partitions.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64]
         L.nacho_partition_rowcost.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
@@ -255,6 +257,20 @@ def nacho_partition(ops, P, queries=None, cost_scale=1):
         assert queries.dtype == torch.int64 and queries.numel() == P + 1
     _check(lib().nacho_partition(C.cast(arr, C.c_void_p), k, cost_scale, P, _ptr(queries),
                                  C.byref(parts), None, 0, _stream()), "nacho_partition")
+    return {"coord": coord, "posn": posn, "cost": cost}
+
+
+def nacho_partition_csr64(pos, crd, n_rows, n_cols, P):
+    """All P+1 boundaries of one CSR operand with 64-bit positions (pos: int64 device tensor).
+    Returns dict(coord int32 [P+1, 2], posn int64 [P+1, 2], cost int64 [P+1]); enqueues only."""
+    dev = pos.device
+    assert pos.dtype == torch.int64 and (crd is None or crd.dtype == torch.int32)
+    nnz = int((pos[-1] - pos[0]).item())
+    coord = torch.empty((P + 1, 2), dtype=torch.int32, device=dev)
+    posn = torch.empty((P + 1, 2), dtype=torch.int64, device=dev)
+    cost = torch.empty(P + 1, dtype=torch.int64, device=dev)
+    _check(lib().nacho_partition_csr64(_ptr(pos), _ptr(crd), n_rows, n_cols, nnz, P, _ptr(coord), _ptr(posn),
+                                       _ptr(cost), _stream()), "nacho_partition_csr64")
     return {"coord": coord, "posn": posn, "cost": cost}
 
 

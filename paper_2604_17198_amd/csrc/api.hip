@@ -487,6 +487,21 @@ int32_t nacho_partition(const nacho_tensor *ops, int32_t k, int64_t cost_scale, 
     return NACHO_OK;
 }
 
+int32_t nacho_partition_csr64(const int64_t *pos, const int32_t *crd, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                              int64_t P, int32_t *coord, int64_t *posn, int64_t *cost, void *hip_stream)
+{
+    if (!pos || !coord || !posn || !cost) return NACHO_ERR_INVALID_ARG;
+    if (n_rows < 0 || n_rows > 0x7ffffff0LL || n_cols < 0 || n_cols > 0x7ffffff0LL || nnz < 0) return NACHO_ERR_INVALID_ARG;
+    if (P < 1 || P > 0x7ffffff0LL) return NACHO_ERR_INVALID_ARG;
+    if (nnz > 0 && (!crd || !aligned16(crd))) return NACHO_ERR_INVALID_ARG;
+    if (nnz > ((int64_t)1 << 62) / P) return NACHO_ERR_INVALID_ARG;         // (p * nnz is formed in 128 bits, kept sane)
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    if (launch_partition_csr64(pos, crd, n_rows, nnz, P, coord, posn, cost, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("partition");
+    return NACHO_OK;
+}
+
 int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
                    void *ws, size_t ws_bytes, void *hip_stream)
 {

@@ -26,6 +26,9 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
                             int32_t *clear_status = nullptr, const ZeroRows *zero_rows = nullptr,
                             int64_t row_cost = 0);
 
+hipError_t launch_partition_csr64(const int64_t *pos, const int32_t *crd, int64_t n_rows, int64_t nnz, int64_t P,
+                                  int32_t *coord, int64_t *posn, int64_t *cost, hipStream_t stream);
+
 // Items one wavefront can stage for SpMV (partition work must not exceed it).
 int spmv_capacity(int dtype);
 // `grain` > 0: the partitions come from the fixed-grain queries Q_p = min(p * grain, nnz)

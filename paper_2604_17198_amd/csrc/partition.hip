@@ -758,17 +758,19 @@ struct QueryRule {
 // [C_i(r), C_i(r + 1)) -- empty rows own some too -- and a boundary with R = Q - C_i(r) left lies at the
 // row's start when R < row_cost, else at the entry of rank R - row_cost (an entry in column 0 shares
 // the coordinate of the row's own units: the boundary's cost is then C_i(r)).
+// PosT: type of the operand's positions and of the stored ones (int64_t: operands of 2^31 entries or more).
+template <typename PosT>
 __global__ void __launch_bounds__(256)
-partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
+partition_csr1_kernel(const PosT *__restrict__ pos, const int32_t *__restrict__ crd, int64_t n_rows,
                       int64_t count, QueryRule rule, int64_t cost_scale, int64_t row_cost,
                       int32_t *__restrict__ coord,
-                      int32_t *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear, ZeroRows zero)
+                      PosT *__restrict__ posn, int64_t *__restrict__ cost, ClearWords clear, ZeroRows zero)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     clear.run(i);
     const int lane = lane_id();
     const int64_t P = rule.P;
-    const int32_t p0 = pos[0];
+    const PosT p0 = pos[0];
     // As boundary i: everything that does not depend on the row.  Boundaries that
     // are not searched (the origin, the end, queries that reach past the work) are
     // complete here.
@@ -778,12 +780,12 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
             const bool end = i != 0;
             coord[i * 2 + 0] = end ? (int32_t)n_rows : 0;
             coord[i * 2 + 1] = 0;
-            posn[i * 2 + 0] = end ? (int32_t)n_rows : 0;
-            posn[i * 2 + 1] = end ? (int32_t)count : 0;
+            posn[i * 2 + 0] = end ? (PosT)n_rows : 0;
+            posn[i * 2 + 1] = end ? (PosT)count : 0;
             cost[i] = end ? rule.total * cost_scale : 0;
         } else if (row_cost == 0) {
             coord[i * 2 + 1] = crd[p0 + q];
-            posn[i * 2 + 1] = (int32_t)(p0 + q);
+            posn[i * 2 + 1] = (PosT)(p0 + q);
             cost[i] = q * cost_scale;
         }
     }
@@ -791,7 +793,7 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
     int64_t b_lo = 0, b_hi = 0;
     bool empty_row = false;
     if (i < n_rows) {
-        const int64_t a = pos[i] - p0 + row_cost * i, e = pos[i + 1] - p0 + row_cost * (i + 1);
+        const int64_t a = (int64_t)(pos[i] - p0) + row_cost * i, e = (int64_t)(pos[i + 1] - p0) + row_cost * (i + 1);
         empty_row = pos[i + 1] == pos[i];
         if (e > a) {
             b_lo = rule.first_reaching(a);
@@ -811,11 +813,12 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
             coord[b * 2 + 0] = r;
             posn[b * 2 + 0] = r;
             if (row_cost > 0) {
-                const int64_t start = pos[r] - p0 + row_cost * r;      // C_i(r)
+                const int64_t start = (int64_t)(pos[r] - p0) + row_cost * r;      // C_i(r)
                 const int64_t Q = rule.query(b), R = Q - start;
-                int32_t at = pos[r], x1 = 0;
+                PosT at = pos[r];
+                int32_t x1 = 0;
                 if (R >= row_cost) {
-                    at += (int32_t)(R - row_cost);
+                    at += (PosT)(R - row_cost);
                     x1 = crd[at];
                 }
                 coord[b * 2 + 1] = x1;
@@ -842,6 +845,28 @@ partition_csr1_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict
 
 }  // namespace
 
+// One CSR operand whose positions are 64-bit: the same one-pass kernel, equal-share queries.
+hipError_t launch_partition_csr64(const int64_t *pos, const int32_t *crd, int64_t n_rows, int64_t nnz, int64_t P,
+                                  int32_t *coord, int64_t *posn, int64_t *cost, hipStream_t stream)
+{
+    ClearWords clear;
+    clear.words = nullptr;
+    clear.n = 0;
+    clear.status = nullptr;
+    ZeroRows zero;
+    zero.base = nullptr;
+    zero.ld = 0;
+    zero.width = zero.elem = 0;
+    QueryRule rule;
+    rule.P = P;
+    rule.total = nnz;
+    rule.grain_u = 0;
+    const int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
+    hipLaunchKernelGGL(partition_csr1_kernel<int64_t>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                       pos, crd, n_rows, nnz, rule, (int64_t)1, (int64_t)0, coord, posn, cost, clear, zero);
+    return hipGetLastError();
+}
+
 hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                             const int64_t *queries, int64_t total_unscaled,
                             int32_t *coord, int32_t *posn, int64_t *cost, hipStream_t stream,
@@ -866,7 +891,7 @@ hipError_t launch_partition(const DevOperands &ops, int64_t cost_scale, int64_t 
         const int64_t n_rows = ops.lvl[0][0].extent;
         int64_t threads = n_rows > P + 1 ? n_rows : P + 1;
         if (clear.n > threads) threads = clear.n;
-        hipLaunchKernelGGL(partition_csr1_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+        hipLaunchKernelGGL(partition_csr1_kernel<int32_t>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            ops.lvl[0][1].pos, ops.lvl[0][1].crd, n_rows, ops.lvl[0][1].count, rule, cost_scale,
                            row_cost, coord, posn, cost, clear, zero);
         return hipGetLastError();
