@@ -747,7 +747,10 @@ struct QueryRule {
         if (grain_u > 0 && grain_u < 0x7fffffffLL && y < 0x7fffffffLL)
             b = ((uint32_t)y + (uint32_t)grain_u - 1u) / (uint32_t)grain_u;
         else if (grain_u > 0) b = (y + grain_u - 1) / grain_u;
-        else b = total > 0 ? (int64_t)(((__int128)y * P + total - 1) / total) : 0;
+        else if (total <= 0) b = 0;
+        else if (total < 0x7fffffffLL && P < 0x7fffffffLL)          // (the product fits 64 bits: no 128-bit division)
+            b = (int64_t)(((uint64_t)y * (uint64_t)P + (uint64_t)total - 1u) / (uint64_t)total);
+        else b = (int64_t)(((__int128)y * P + total - 1) / total);
         return b < P ? b : P;
     }
 };
@@ -802,30 +805,38 @@ partition_csr1_kernel(const PosT *__restrict__ pos, const int32_t *__restrict__ 
             // (b < b_hi means Q_b < C_i(r + 1) <= total and b < P: interior)
         }
     }
-    unsigned long long todo = __ballot(b_hi > b_lo);
+    // row r writes the row fields of boundary b
+    auto write_boundary = [&](int64_t b, int32_t r) {
+        coord[b * 2 + 0] = r;
+        posn[b * 2 + 0] = r;
+        if (row_cost > 0) {
+            const int64_t start = (int64_t)(pos[r] - p0) + row_cost * r;      // C_i(r)
+            const int64_t Q = rule.query(b), R = Q - start;
+            PosT at = pos[r];
+            int32_t x1 = 0;
+            if (R >= row_cost) {
+                at += (PosT)(R - row_cost);
+                x1 = crd[at];
+            }
+            coord[b * 2 + 1] = x1;
+            posn[b * 2 + 1] = at;
+            cost[b] = (x1 > 0 ? Q : start) * cost_scale;
+        }
+    };
+    // a row with a few boundaries writes them itself (all rows of the wavefront at once); a row with
+    // many is written by its whole wavefront
+    constexpr int kFew = 4;
+    const int64_t mine = b_hi - b_lo;
+    if (mine > 0 && mine <= kFew)
+        for (int64_t b = b_lo; b < b_hi; ++b) write_boundary(b, (int32_t)i);
+    unsigned long long todo = __ballot(mine > kFew);
     while (todo) {
         const int src = __ffsll((long long)todo) - 1;
         todo &= todo - 1;
         const int64_t lo = __shfl((long long)b_lo, src, NACHO_WAVE);
         const int64_t hi = __shfl((long long)b_hi, src, NACHO_WAVE);
         const int32_t r = (int32_t)(i - lane + src);
-        for (int64_t b = lo + lane; b < hi; b += NACHO_WAVE) {
-            coord[b * 2 + 0] = r;
-            posn[b * 2 + 0] = r;
-            if (row_cost > 0) {
-                const int64_t start = (int64_t)(pos[r] - p0) + row_cost * r;      // C_i(r)
-                const int64_t Q = rule.query(b), R = Q - start;
-                PosT at = pos[r];
-                int32_t x1 = 0;
-                if (R >= row_cost) {
-                    at += (PosT)(R - row_cost);
-                    x1 = crd[at];
-                }
-                coord[b * 2 + 1] = x1;
-                posn[b * 2 + 1] = at;
-                cost[b] = (x1 > 0 ? Q : start) * cost_scale;
-            }
-        }
+        for (int64_t b = lo + lane; b < hi; b += NACHO_WAVE) write_boundary(b, r);
     }
     // Rows without entries: their row of the result is zero, and the executing
     // wavefronts may then step over them however many there are.
