@@ -200,7 +200,7 @@ def dcsr(pos0, crd0, pos1, crd1, n_rows, n_cols, val=None):
 
 
 def csf3(pos0, crd0, pos1, crd1, pos2, crd2, shape, val=None):
-    """Third-order tensor, three compressed levels (nacho_partition only)."""
+    """Third-order tensor, three compressed levels (nacho_partition, nacho_spadd_k)."""
     return Operand([{"kind": "compressed", "extent": shape[0], "pos": pos0, "crd": crd0},
                     {"kind": "compressed", "extent": shape[1], "pos": pos1, "crd": crd1},
                     {"kind": "compressed", "extent": shape[2], "pos": pos2, "crd": crd2}], val)

@@ -22,8 +22,10 @@
 //   1. stages the operands' coordinate segments in LDS as k sorted runs of keys
 //      (vectors: the index; matrices: row<<32 | column, the row of every entry
 //      recovered from the pos array with a marker + latest-marker scan, or read
-//      from the stored rows of a coordinate list), every run followed by a
-//      sentinel, and the values beside them;
+//      from the stored rows of a coordinate list; third-order tensors: the
+//      16-byte key (i<<32 | j, k), fibre and slice of every entry recovered by
+//      two such passes), every run followed by a sentinel, and the values
+//      beside them;
 //   2. merges the runs pairwise, in place, values moving with their keys;
 //   3. assembly: walks the merged order, place m = j * 512 + thread; a place
 //      whose key differs from the one before it is the HEAD of its coordinate
@@ -34,9 +36,10 @@
 //      everything before the partition (two levels, see below);
 //   5. compute: every head writes coordinate and value at offset + heads before
 //      it -- consecutive lanes write consecutive words.  The hierarchical
-//      arrays (crd0/pos1 of a DCSR result, pos of a CSR result) are written for
-//      the rows whose first output entry the partition owns -- exactly one
-//      writer per row.
+//      arrays (crd0/pos1 of a DCSR result, pos of a CSR result, crd1/pos2 and
+//      crd0/pos1 of a third-order result) are written for the rows (fibres,
+//      slices) whose first output entry the partition owns -- exactly one
+//      writer each.
 // What differs from the paper's three kernels: the inputs are read once instead
 // of twice and there is no separate scan launch; the arithmetic is the same.
 //
