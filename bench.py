@@ -215,6 +215,10 @@ def bench_spmv(args, ceilings):
     rowcost = {"row_cost": 1, "partitions": int(P_rc), "ms_per_step": ms_rc, "kernel_ms": _kernel_ms(step_rc, 5),
                "measured": _measured_balance(step_rc, int(P_rc))}
     del ws_rc
+    # the same call without a partition pass: every executing wavefront searches its own boundaries
+    step_fu = lambda: nb.nacho_spmv_fused(op, x, y, ws=ws)
+    ms_fu, _ = _time_steps(step_fu, max(5, args.steps // 2), 2)
+    fused = {"ms_per_step": ms_fu, "kernel_ms": _kernel_ms(step_fu, 5)}
 
     # parity check of the timed configuration (full vector) and the oracle's own time
     import oracle
@@ -253,6 +257,7 @@ def bench_spmv(args, ceilings):
                      "gather_ceiling_16MiB_Gper_s": ceilings["gather_16MiB_window_Gper_s"]},
         "balance": balance,
         "row_aware_cost_variant": rowcost,
+        "fused_search_variant": fused,
         "cpu_baseline": {"value": nnz / best, "unit": "nnz/s", "cores": 1, "kind": "oracle",
                          "seconds": best, "nproc": nproc, "cpu_model": cpu_model,
                          "build": "gcc -O3 -march=native (this host), timed in C with CLOCK_MONOTONIC",

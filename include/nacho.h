@@ -266,6 +266,20 @@ int32_t nacho_spmv_rowcost(const nacho_tensor *A, const void *x, void *y, int32_
                            int64_t P, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * nacho_spmv without a partition pass (a P-free, fused search-in-execute form):
+ * there is no partition table; every wavefront of the executing kernel finds its
+ * own two boundaries -- Algorithm 1 for one CSR operand with the fixed-grain
+ * queries Q_b = min(b * G, nnz), G = one wavefront's capacity, i.e. the row with
+ * pos[r] <= Q_b < pos[r+1] by a 64-ary search over pos -- and y is cleared by a
+ * small fill kernel first.  Same partitions, same arithmetic and the same result
+ * as nacho_spmv with P = 0; it trades the partition kernel's one pass over pos
+ * for two searches per wavefront (a measured variant, not the default).
+ * Workspace: nacho_workspace_bytes(NACHO_OP_SPMV, ..., P = 0).
+ */
+int32_t nacho_spmv_fused(const nacho_tensor *A, const void *x, void *y, int32_t dtype, void *ws, size_t ws_bytes,
+                         void *hip_stream);
+
+/*
  * nacho_spmv for callers that cannot allocate device memory or pass a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc).  Same operation, arguments, results and status codes as nacho_spmv,

@@ -28,7 +28,7 @@ EXPORTS = [
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
     "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
     "nacho_probe", "nacho_merge_wavefronts", "nacho_rowcost_partitions", "nacho_partition_rowcost",
-    "nacho_spmv_rowcost", "nacho_partition_csr64",
+    "nacho_spmv_rowcost", "nacho_partition_csr64", "nacho_spmv_fused",
 ]
 
 
@@ -104,6 +104,8 @@ def lib():
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.nacho_validate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_instrument.argtypes = [C.c_void_p, C.c_int64]
+        L.nacho_spmv_fused.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
+                                       C.c_void_p]
         L.nacho_partition_csr64.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_rowcost_partitions.restype = C.c_int64
@@ -306,6 +308,17 @@ def nacho_spmv(A: Operand, x, y=None, P=0, ws=None):
     arr = _pack([A])
     _check(lib().nacho_spmv(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dt, P, _ptr(ws),
                             ws.numel(), _stream()), "nacho_spmv")
+    return y
+
+
+def nacho_spmv_fused(A: Operand, x, y, ws=None):
+    """y = A x without a partition pass: the executing wavefronts search their own boundaries."""
+    dt = dtype_code(x.dtype)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPMV, [A], dt, 0, 0), x.device)
+    arr = _pack([A])
+    _check(lib().nacho_spmv_fused(C.cast(arr, C.c_void_p), _ptr(x), _ptr(y), dt, _ptr(ws), ws.numel(), _stream()),
+           "nacho_spmv_fused")
     return y
 
 

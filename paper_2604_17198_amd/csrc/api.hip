@@ -520,6 +520,37 @@ int32_t nacho_spmv(const nacho_tensor *A, const void *x, void *y, int32_t dtype,
     return spmv_enqueue(A, dev, nnz, x, y, dtype, P, Pe, w, static_cast<hipStream_t>(hip_stream));
 }
 
+int32_t nacho_spmv_fused(const nacho_tensor *A, const void *x, void *y, int32_t dtype, void *ws, size_t ws_bytes,
+                         void *hip_stream)
+{
+    if (!A || !x || !y) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t nnz = 0;
+    Format fmt;
+    int32_t rc = check_operands(A, 1, true, &dev, &nnz, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_CSR) return NACHO_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!A->val || !aligned16(A->val))) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = fused_partitions(NACHO_OP_SPMV, fmt, dtype, 1, nnz, 0);
+    CarryWs w = carve_carry(ws, Pe, dtype, 1);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t n_rows = A->lvl[0].extent;
+    const int64_t grain = spmv_capacity(dtype);
+    profile_begin(s);
+    if (launch_zero_vector(dtype, y, n_rows, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("zero_y");
+    if (launch_spmv_exec(dtype, A->lvl[1].pos, A->lvl[1].crd, A->val, x, y, n_rows, nnz, nullptr, nullptr, Pe,
+                         w.carry_val, w.carry_row, grain, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_exec_fused");
+    if (launch_spmv_fixup(dtype, y, Pe, w.carry_val, w.carry_row, A->lvl[1].pos, grain, s) != hipSuccess)
+        return NACHO_ERR_HIP;
+    profile_mark("spmv_fixup");
+    return NACHO_OK;
+}
+
 int32_t nacho_spmv_static(const nacho_tensor *A, const void *x, void *y, int32_t dtype, int64_t P,
                           void *hip_stream)
 {

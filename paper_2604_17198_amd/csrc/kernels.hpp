@@ -37,6 +37,8 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
                             const void *x, void *y, int64_t n_rows, int64_t nnz,
                             const int32_t *coord, const int32_t *posn, int64_t P,
                             void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream);
+// (coord == nullptr with grain > 0: the fused form, every wavefront searches its own boundaries)
+hipError_t launch_zero_vector(int dtype, void *y, int64_t n, hipStream_t stream);
 hipError_t launch_spmv_fixup(int dtype, void *y, int64_t P, const void *carry_val,
                              const int32_t *carry_row, const int32_t *pos, int64_t grain, hipStream_t stream);
 

@@ -27,7 +27,10 @@ constexpr int kLongRow = 192;  // products per row above which the wavefront sum
 
 // kDealt: the partitions come from fixed-grain queries (grain > 0) and are dealt out by XCD; the
 // instantiation without it serves arbitrary partition tables (caller's P, the row-aware cost).
-template <typename T, int G, int RBLK, bool kDealt>
+// kFused (with kDealt): there is no partition table; the wavefront finds its own two boundaries, the
+// search of Algorithm 1 for one CSR operand (Section 4.2.2: the row with pos[r] <= Q < pos[r + 1], at
+// position Q) with the fixed-grain queries Q_b = min(b * grain, nnz), as a 64-ary search over pos.
+template <typename T, int G, int RBLK, bool kDealt, bool kFused = false>
 __global__ void __launch_bounds__(NACHO_WAVE)
 spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                  const T *__restrict__ val, const T *__restrict__ x, T *__restrict__ y,
@@ -51,8 +54,20 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
     // partitions (stretches as long as there are such workgroups): a
     // permutation of first .. end - 1; everything else keeps its index.
     int p = blockIdx.x;
+    // (fused search) boundary b: its row and its position
+    auto boundary = [&](int b, int from, int &r, int &n) {
+        const long long Q = (long long)b * grain;
+        if (b == 0) { r = 0; n = pos[0]; }
+        else if (Q >= nnz) { r = n_rows; n = pos[0] + nnz; }
+        else {
+            n = pos[0] + (int)Q;
+            r = pos[from + 1] > n ? from : first_row_past(pos, from, n_rows, n);
+        }
+    };
+    int r_own = 0, n_own = 0;
+    if (kFused) boundary(p, 0, r_own, n_own);
     if (kDealt) {
-        const int r = coord[2 * p];
+        const int r = kFused ? r_own : coord[2 * p];
         if (r < n_rows) {
             const int base = pos[0];
             const int first = ((pos[r] - base) + grain - 1) / grain;
@@ -72,8 +87,16 @@ spmv_exec_kernel(const int32_t *__restrict__ pos, const int32_t *__restrict__ cr
         }
     }
     // k = 1, d = 2: coord[b*2 + 0] = row, posn[b*2 + 1] = position in crd/val
-    const int r0 = coord[2 * p], r1 = coord[2 * p + 2];
-    const int n0 = posn[2 * p + 1], n1 = posn[2 * p + 3];
+    int r0, r1, n0, n1;
+    if (kFused) {
+        // (a dealt partition lies in the row of the one it was dealt for)
+        if (p == (int)blockIdx.x) { r0 = r_own; n0 = n_own; }
+        else boundary(p, r_own < n_rows ? r_own : 0, r0, n0);
+        boundary(p + 1, r0 < n_rows ? r0 : 0, r1, n1);
+    } else {
+        r0 = coord[2 * p]; r1 = coord[2 * p + 2];
+        n0 = posn[2 * p + 1]; n1 = posn[2 * p + 3];
+    }
     const int pr0 = pos[r0], pr1 = pos[r1];
     const bool has_head = n0 > pr0;                    // row r0 started in an earlier partition
     const int next_first = (n1 > pr1) ? r1 + 1 : r1;   // first row that starts after this partition
@@ -261,18 +284,40 @@ hipError_t launch_spmv_exec(int dtype, const int32_t *pos, const int32_t *crd, c
                             const int32_t *coord, const int32_t *posn, int64_t P,
                             void *carry_val, int32_t *carry_row, int64_t grain, hipStream_t stream)
 {
-#define NACHO_SPMV_LAUNCH(T, G, R, DEALT)                                                               \
-    hipLaunchKernelGGL((spmv_exec_kernel<T, G, R, DEALT>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, stream, pos, \
-                       crd, (const T *)val, (const T *)x, (T *)y, (int)nnz, coord, posn, (T *)carry_val,       \
+#define NACHO_SPMV_LAUNCH(T, G, R, DEALT, FUSED)                                                        \
+    hipLaunchKernelGGL((spmv_exec_kernel<T, G, R, DEALT, FUSED>), dim3((unsigned)P), dim3(NACHO_WAVE), 0, stream, \
+                       pos, crd, (const T *)val, (const T *)x, (T *)y, (int)nnz, coord, posn, (T *)carry_val,    \
                        carry_row, (int)n_rows, (int)grain, nacho_host::wave_log())
+    const bool fused = grain > 0 && coord == nullptr;       // no table: the wavefronts search their boundaries
     if (dtype == NACHO_F64) {
-        if (grain > 0) NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, true);
-        else NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, false);
+        if (fused) NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, true, true);
+        else if (grain > 0) NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, true, false);
+        else NACHO_SPMV_LAUNCH(double, kGrainF64, kRowsF64, false, false);
     } else {
-        if (grain > 0) NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, true);
-        else NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, false);
+        if (fused) NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, true, true);
+        else if (grain > 0) NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, true, false);
+        else NACHO_SPMV_LAUNCH(float, kGrainF32, kRowsF32, false, false);
     }
 #undef NACHO_SPMV_LAUNCH
+    return hipGetLastError();
+}
+
+namespace {
+__global__ void __launch_bounds__(256) zero_words_kernel(uint32_t *__restrict__ dst, int64_t n_words)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * blockDim.x)
+        dst[i] = 0u;
+}
+}  // namespace
+
+// y = 0 (the fused form has no partition kernel to write the zeros of the rows A stores nothing in)
+hipError_t launch_zero_vector(int dtype, void *y, int64_t n, hipStream_t stream)
+{
+    const int64_t words = n * (dtype == NACHO_F64 ? 2 : 1);
+    if (words == 0) return hipSuccess;
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint32_t *)y, words);
     return hipGetLastError();
 }
 

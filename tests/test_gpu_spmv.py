@@ -125,3 +125,45 @@ def test_errors_from_the_host():
         bad = nb.csr(A.keep[0], A.keep[1], 4096, 4096, A.val[1:])
         nb.nacho_spmv(bad, x, y)
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_fused_search_in_execute_variant(dtype):
+    """nacho_spmv_fused has no partition pass: every wavefront searches its own boundaries.  Same
+    partitions and arithmetic as nacho_spmv with P = 0, so the results agree bit for bit; and with
+    the oracle within the tolerance."""
+    rng = np.random.default_rng(8)
+    mats = []
+    for trial in range(6):
+        n_rows, n_cols = int(rng.integers(1, 4000)), int(rng.integers(1, 4000))
+        nnz = int(rng.integers(0, min(n_rows * n_cols, 40000) + 1))
+        c = random_coords(rng, (n_rows, n_cols), nnz)
+        if trial % 2:
+            c = c[c[:, 0] % 7 != 3]                   # runs of empty rows
+        pos, crd = to_csr(c, n_rows)
+        mats.append(({"n_rows": n_rows, "n_cols": n_cols, "pos": pos, "crd": crd,
+                      "val": rng.uniform(-1, 1, c.shape[0]).astype(dtype)},
+                     rng.uniform(-1, 1, n_cols).astype(dtype), f"random{trial}"))
+    # all-empty matrix, one row spanning many partitions among empty rows, the skewed configuration
+    pos, crd = to_csr(np.zeros((0, 2), np.int64), 300)
+    mats.append(({"n_rows": 300, "n_cols": 9, "pos": pos, "crd": crd, "val": np.zeros(0, dtype)},
+                 rng.uniform(-1, 1, 9).astype(dtype), "empty"))
+    c = np.stack([np.full(30000, 4321, np.int64), np.arange(30000)], 1)
+    pos, crd = to_csr(c, 9000)
+    mats.append(({"n_rows": 9000, "n_cols": 30000, "pos": pos, "crd": crd,
+                  "val": rng.uniform(-1, 1, 30000).astype(dtype)}, rng.uniform(-1, 1, 30000).astype(dtype), "heavy"))
+    cfg = workloads.config(2, scale=0.05)
+    mats.append((dict(cfg["A"], val=cfg["A"]["val"].astype(dtype)), cfg["x"].astype(dtype), "config2@0.05"))
+    for A, x, tag in mats:
+        print(f"spmv fused {tag} rows={A['n_rows']} nnz={int(A['pos'][-1])} {np.dtype(dtype).name}", flush=True)
+        op, xd = csr_operand(A), dev(x)
+        y = torch.full((A["n_rows"],), float("nan"), dtype=xd.dtype, device="cuda")
+        nb.nacho_spmv_fused(op, xd, y)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        ref, s = oracle.spmv(A["pos"], A["crd"], A["val"], x)
+        assert not np.any(np.isnan(got)), tag
+        assert tol_ok(got, ref, s, TOL[dtype]).all(), tag
+        assert np.all(got[np.diff(A["pos"]) == 0] == 0.0)
+        plain = _run(A, x, 0)
+        assert np.array_equal(got.view(np.uint8), plain.view(np.uint8)), tag
