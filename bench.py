@@ -3,7 +3,7 @@
 
 `python bench.py --gpus 1 --steps K --warmup W` prints ONE JSON line.  A step is
 one whole call of the hot path (partition search + partitioned execution +
-carry fix-up) on the headline workload: configuration 2 of the benchmark spec, the
+carry fix-up) on the headline workload: configuration 2 of the baseline workload list, the
 power-law CSR SpMV (2M x 2M, ~50M nnz, fp64), inputs resident in HBM.
 
 Extra objects on the line:
@@ -266,7 +266,7 @@ def bench_spmv(args, ceilings):
 
 
 def bench_others(steps, warmup, only=None, ceilings=None):
-    """Configurations 3, 4 and 5 of the benchmark spec, one fused call per step, same timing
+    """Configurations 3, 4 and 5 of the baseline workload list, one fused call per step, same timing
     protocol; algorithmic bytes = every input array once + every output array once."""
     import torch
     from paper_2604_17198_amd import binding as nb

@@ -38,7 +38,7 @@
  * sum of absolute terms is returned beside every value so that a test can use
  * the tolerance  |got - ref| <= tol * max(|ref|, sum|terms|).
  *
- * Readings of points the paper leaves open (each is listed in the design doc):
+ * Readings of points the paper leaves open:
  *   - search domain of a level is [0, N_m] (the 3-vector listing of Section
  *     4.2.3 searches (0, N]); for an interior query the result is < N_m;
  *   - the first boundary is the origin and the last is the end of the space,
