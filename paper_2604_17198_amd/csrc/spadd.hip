@@ -393,186 +393,221 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
 #pragma unroll
         for (int t = 0; t <= K; ++t) off[t] = 0;
     }
-    if (tid == 0) {
-        w.gave_up = 0;
+    // Vectors: key = the stored index and nothing else, so keys and values are copied as they are -- by
+    // the memory pipeline itself, global memory to LDS (one instruction moves 64 words of one run, no
+    // register in between, no address arithmetic per entry); the wavefronts share the stretches of
+    // 64 words of every run among them.
+    constexpr bool kDirect = D == 1 && !kMapped;
+    if constexpr (kDirect) {
+        typedef __attribute__((address_space(3))) uint32_t lds_word;
+        if (tid == 0) w.gave_up = 0;
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
+        constexpr int kValWords = (int)sizeof(T) / 4;
 #pragma unroll
-        for (int t = 0; t <= K; ++t) {
-            w.soff[t] = off[t];
-            if (t < K) {
-                const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
-                w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
-                w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
-                if (kCoo) {
-                    const int32_t *rows_t = t < k ? ops.lvl[t][0].crd : nullptr;
-                    w.sstart[t] = (unsigned long long)(uintptr_t)(rows_t + q_lo[t] - off[t]);
+        for (int t = 0; t < K; ++t) {
+            if (t >= k) break;
+            const int nt = off[t + 1] - off[t];
+            const int slot = off[t] + t + 1;
+            const NACHO_GLOBAL uint32_t *ksrc = global_ptr<uint32_t>((unsigned long long)(uintptr_t)(ops.lvl[t][0].crd + q_lo[t]));
+            const NACHO_GLOBAL uint32_t *vsrc =
+                global_ptr<uint32_t>((unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t]));
+            lds_word *kdst = (lds_word *)(keys + slot);
+            lds_word *vdst = (lds_word *)(w.vals + slot);
+            // (the wavefront that starts on a run rotates with the run: short runs do not all land on wavefront 0)
+            for (int c = ((wv + kWaves - (t & (kWaves - 1))) & (kWaves - 1)) * NACHO_WAVE; c < nt; c += kThreads)
+                if (c + lane < nt) __builtin_amdgcn_global_load_lds(ksrc + c + lane, kdst + c, 4, 0, 0);
+            const int nw = nt * kValWords;
+            for (int c = ((wv + kWaves - (t & (kWaves - 1))) & (kWaves - 1)) * NACHO_WAVE; c < nw; c += kThreads)
+                if (c + lane < nw) __builtin_amdgcn_global_load_lds(vsrc + c + lane, vdst + c, 4, 0, 0);
+        }
+        int sentinel_at = 0;
+#pragma unroll
+        for (int t = 0; t < K; ++t)
+            if (tid == t) sentinel_at = off[t + 1] + t + 1;
+        if (tid < K) keys[sentinel_at] = kSentinel;
+        if (tid == K) keys[0] = kSentinel;
+    } else {
+        if (tid == 0) {
+            w.gave_up = 0;
+    #pragma unroll
+            for (int t = 0; t <= K; ++t) {
+                w.soff[t] = off[t];
+                if (t < K) {
+                    const int32_t *crd_t = t < k ? ops.lvl[t][D - 1].crd : nullptr;
+                    w.scrd[t] = (unsigned long long)(uintptr_t)(crd_t + q_lo[t] - off[t]);
+                    w.sval[t] = (unsigned long long)(uintptr_t)(static_cast<const T *>(vals.v[t]) + q_lo[t] - off[t]);
+                    if (kCoo) {
+                        const int32_t *rows_t = t < k ? ops.lvl[t][0].crd : nullptr;
+                        w.sstart[t] = (unsigned long long)(uintptr_t)(rows_t + q_lo[t] - off[t]);
+                    }
+                    if (kMapped) {
+                        w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.start[t] : nullptr);
+                        w.spos[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].pos : nullptr);
+                    }
+                    if (kCsf) w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].crd : nullptr);
                 }
-                if (kMapped) {
-                    w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.start[t] : nullptr);
-                    w.spos[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].pos : nullptr);
-                }
-                if (kCsf) w.sstart[t] = (unsigned long long)(uintptr_t)(t < k ? ops.lvl[t][1].crd : nullptr);
             }
         }
-    }
-    __syncthreads();
+        __syncthreads();
 
-    // run and column of every entry this thread stages: entry c = r * kThreads + tid.  A thread
-    // without an entry (c >= n) goes through the motions on the partition's last entry and stores
-    // to the dummy word: no branches around the loads.
-    int tr[R], col[R];
-    T val[R];
-    uint32_t row[D >= 2 ? R : 1];              // level-0 coordinate of every entry (matrices, tensors)
-    uint32_t mid[D == 3 ? R : 1];              // level-1 coordinate (third-order tensors)
-    const int last = n - 1;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int c = r * kThreads + tid;
-        const int cc = c < last ? c : last;
-        int t = 0;
-#pragma unroll
-        for (int u = 1; u < K; ++u) t += cc >= off[u] ? 1 : 0;
-        tr[r] = t;
-        col[r] = 0;
-        val[r] = T(0);
-        if (D >= 2) row[r] = 0;
-        if (D == 3) mid[r] = 0;
-    }
-    if (n > 0) {
-#pragma unroll
+        // run and column of every entry this thread stages: entry c = r * kThreads + tid.  A thread
+        // without an entry (c >= n) goes through the motions on the partition's last entry and stores
+        // to the dummy word: no branches around the loads.
+        int tr[R], col[R];
+        T val[R];
+        uint32_t row[D >= 2 ? R : 1];              // level-0 coordinate of every entry (matrices, tensors)
+        uint32_t mid[D == 3 ? R : 1];              // level-1 coordinate (third-order tensors)
+        const int last = n - 1;
+    #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int c = r * kThreads + tid;
             const int cc = c < last ? c : last;
-            if (!kMapped) {
-                col[r] = global_ptr<int32_t>(w.scrd[tr[r]])[cc];
-                // the values: requested now, stored beside the keys once the markers are done with
-                val[r] = global_ptr<T>(w.sval[tr[r]])[cc];
-            }
-            if (kCoo) row[r] = (uint32_t)global_ptr<int32_t>(w.sstart[tr[r]])[cc];
+            int t = 0;
+    #pragma unroll
+            for (int u = 1; u < K; ++u) t += cc >= off[u] ? 1 : 0;
+            tr[r] = t;
+            col[r] = 0;
+            val[r] = T(0);
+            if (D >= 2) row[r] = 0;
+            if (D == 3) mid[r] = 0;
         }
-    }
-
-    if constexpr (D >= 2 && !kCoo) {
-        // Segments of an upper level overlapping [q_lo, q_hi) of every run: mark each segment's
-        // first entry (word of the entry in marks) with a value, then hand every entry the latest
-        // marker at or before it.  The first entry of every run carries a marker, so nothing leaks
-        // from one run into the next.  Matrices: the segments are the rows, the value the row's
-        // coordinate.  Third-order tensors, two passes: the fibres (value: the fibre's position,
-        // whose coordinate j is then read from the level-1 coordinates), then the slices (value: i).
-        auto parents = [&](const int lv, uint32_t (&res)[R]) {
-            for (int i = tid; i < S::kTile; i += kThreads) w.marks[i] = 0;
-            __syncthreads();
-#pragma unroll
-            for (int t = 0; t < K; ++t) {
-                if (t >= k) break;
-                const int nt = off[t + 1] - off[t];
-                if (nt == 0) continue;
-                const int32_t *pos_a = ops.lvl[t][1].pos;                       // children of level 0
-                const int32_t *pos_b = D == 3 ? ops.lvl[t][2].pos : nullptr;    // children of level 1
-                const int32_t *crd0 = ops.lvl[t][0].crd;
-                const int ql = q_lo[t], qh = ql + nt;
-                const int i_lo = posn[(p * k + t) * D + lv];
-                int i_hi = posn[((p + 1) * k + t) * D + lv] + 1;
-                const int i_max = (FMT == SPADD_CSR) ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][lv].count;
-                if (i_hi > i_max) i_hi = i_max;
-                for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
-                    int a[4], b[4], rw[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * kThreads;
-                        if (i < i_hi) {
-                            if (D == 2) { a[u] = pos_a[i]; b[u] = pos_a[i + 1]; }
-                            else if (lv == 1) { a[u] = pos_b[i]; b[u] = pos_b[i + 1]; }
-                            else { a[u] = pos_b[pos_a[i]]; b[u] = pos_b[pos_a[i + 1]]; }
-                            rw[u] = (FMT == SPADD_CSR || lv == 1) ? i : crd0[i];
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * kThreads;
-                        if (i < i_hi) {
-                            const int s = a[u] > ql ? a[u] : ql;
-                            if (b[u] > s && s < qh) w.marks[off[t] + s - ql] = (uint32_t)(rw[u] + 1);
-                        }
-                    }
-                }
-            }
-            __syncthreads();
-            {
-                // latest marker at or before every word; a thread owns R consecutive words
-                uint32_t v[R], cur = 0;
-                const int at = tid * R;
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    v[j] = w.marks[at + j];
-                    cur = v[j] ? v[j] : cur;
-                }
-                uint32_t incl = cur;                      // latest marker up to the end of this thread's words
-#pragma unroll
-                for (int o = 1; o < NACHO_WAVE; o <<= 1) {
-                    const uint32_t left = __shfl_up(incl, o, NACHO_WAVE);
-                    if (lane >= o && incl == 0) incl = left;
-                }
-                if (lane == NACHO_WAVE - 1) w.wave_x[wave] = incl;
-                __syncthreads();
-                uint32_t carry = 0;                       // latest marker of the earlier wavefronts
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww)
-                    if (ww < wave && w.wave_x[ww]) carry = w.wave_x[ww];
-                cur = __shfl_up(incl, 1, NACHO_WAVE);
-                if (lane == 0) cur = 0;
-                if (cur == 0) cur = carry;
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    cur = v[j] ? v[j] : cur;
-                    w.marks[at + j] = cur;
-                }
-            }
-            __syncthreads();
-#pragma unroll
+        if (n > 0) {
+    #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int c = r * kThreads + tid;
-                res[r] = w.marks[c < last ? c : (last > 0 ? last : 0)] - 1u;
-            }
-            __syncthreads();                       // markers are read: the next pass / the values may overwrite them
-        };
-        if constexpr (D == 3) {
-            uint32_t fibre[R];
-            parents(1, fibre);
-            if (n > 0) {
-#pragma unroll
-                for (int r = 0; r < R; ++r) mid[D == 3 ? r : 0] = (uint32_t)global_ptr<int32_t>(w.sstart[tr[r]])[fibre[r]];
+                const int cc = c < last ? c : last;
+                if (!kMapped) {
+                    col[r] = global_ptr<int32_t>(w.scrd[tr[r]])[cc];
+                    // the values: requested now, stored beside the keys once the markers are done with
+                    val[r] = global_ptr<T>(w.sval[tr[r]])[cc];
+                }
+                if (kCoo) row[r] = (uint32_t)global_ptr<int32_t>(w.sstart[tr[r]])[cc];
             }
         }
-        parents(0, row);
-    }
-    if (kMapped && n > 0) {
-        // storage position - counted position of every entry, then its column and value
-        int sh[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int32_t NACHO_GLOBAL *st = global_ptr<int32_t>(w.sstart[tr[r]]);
-            const int32_t NACHO_GLOBAL *ps = global_ptr<int32_t>(w.spos[tr[r]]);
-            sh[r] = st[row[D == 2 ? r : 0]] - ps[row[D == 2 ? r : 0]];
+
+        if constexpr (D >= 2 && !kCoo) {
+            // Segments of an upper level overlapping [q_lo, q_hi) of every run: mark each segment's
+            // first entry (word of the entry in marks) with a value, then hand every entry the latest
+            // marker at or before it.  The first entry of every run carries a marker, so nothing leaks
+            // from one run into the next.  Matrices: the segments are the rows, the value the row's
+            // coordinate.  Third-order tensors, two passes: the fibres (value: the fibre's position,
+            // whose coordinate j is then read from the level-1 coordinates), then the slices (value: i).
+            auto parents = [&](const int lv, uint32_t (&res)[R]) {
+                for (int i = tid; i < S::kTile; i += kThreads) w.marks[i] = 0;
+                __syncthreads();
+    #pragma unroll
+                for (int t = 0; t < K; ++t) {
+                    if (t >= k) break;
+                    const int nt = off[t + 1] - off[t];
+                    if (nt == 0) continue;
+                    const int32_t *pos_a = ops.lvl[t][1].pos;                       // children of level 0
+                    const int32_t *pos_b = D == 3 ? ops.lvl[t][2].pos : nullptr;    // children of level 1
+                    const int32_t *crd0 = ops.lvl[t][0].crd;
+                    const int ql = q_lo[t], qh = ql + nt;
+                    const int i_lo = posn[(p * k + t) * D + lv];
+                    int i_hi = posn[((p + 1) * k + t) * D + lv] + 1;
+                    const int i_max = (FMT == SPADD_CSR) ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][lv].count;
+                    if (i_hi > i_max) i_hi = i_max;
+                    for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
+                        int a[4], b[4], rw[4];
+    #pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int i = i0 + u * kThreads;
+                            if (i < i_hi) {
+                                if (D == 2) { a[u] = pos_a[i]; b[u] = pos_a[i + 1]; }
+                                else if (lv == 1) { a[u] = pos_b[i]; b[u] = pos_b[i + 1]; }
+                                else { a[u] = pos_b[pos_a[i]]; b[u] = pos_b[pos_a[i + 1]]; }
+                                rw[u] = (FMT == SPADD_CSR || lv == 1) ? i : crd0[i];
+                            }
+                        }
+    #pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int i = i0 + u * kThreads;
+                            if (i < i_hi) {
+                                const int s = a[u] > ql ? a[u] : ql;
+                                if (b[u] > s && s < qh) w.marks[off[t] + s - ql] = (uint32_t)(rw[u] + 1);
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+                {
+                    // latest marker at or before every word; a thread owns R consecutive words
+                    uint32_t v[R], cur = 0;
+                    const int at = tid * R;
+    #pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        v[j] = w.marks[at + j];
+                        cur = v[j] ? v[j] : cur;
+                    }
+                    uint32_t incl = cur;                      // latest marker up to the end of this thread's words
+    #pragma unroll
+                    for (int o = 1; o < NACHO_WAVE; o <<= 1) {
+                        const uint32_t left = __shfl_up(incl, o, NACHO_WAVE);
+                        if (lane >= o && incl == 0) incl = left;
+                    }
+                    if (lane == NACHO_WAVE - 1) w.wave_x[wave] = incl;
+                    __syncthreads();
+                    uint32_t carry = 0;                       // latest marker of the earlier wavefronts
+    #pragma unroll
+                    for (int ww = 0; ww < kWaves; ++ww)
+                        if (ww < wave && w.wave_x[ww]) carry = w.wave_x[ww];
+                    cur = __shfl_up(incl, 1, NACHO_WAVE);
+                    if (lane == 0) cur = 0;
+                    if (cur == 0) cur = carry;
+    #pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        cur = v[j] ? v[j] : cur;
+                        w.marks[at + j] = cur;
+                    }
+                }
+                __syncthreads();
+    #pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int c = r * kThreads + tid;
+                    res[r] = w.marks[c < last ? c : (last > 0 ? last : 0)] - 1u;
+                }
+                __syncthreads();                       // markers are read: the next pass / the values may overwrite them
+            };
+            if constexpr (D == 3) {
+                uint32_t fibre[R];
+                parents(1, fibre);
+                if (n > 0) {
+    #pragma unroll
+                    for (int r = 0; r < R; ++r) mid[D == 3 ? r : 0] = (uint32_t)global_ptr<int32_t>(w.sstart[tr[r]])[fibre[r]];
+                }
+            }
+            parents(0, row);
         }
-#pragma unroll
+        if (kMapped && n > 0) {
+            // storage position - counted position of every entry, then its column and value
+            int sh[R];
+    #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int32_t NACHO_GLOBAL *st = global_ptr<int32_t>(w.sstart[tr[r]]);
+                const int32_t NACHO_GLOBAL *ps = global_ptr<int32_t>(w.spos[tr[r]]);
+                sh[r] = st[row[D == 2 ? r : 0]] - ps[row[D == 2 ? r : 0]];
+            }
+    #pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int c = r * kThreads + tid;
+                const int cc = c < last ? c : last;
+                col[r] = global_ptr<int32_t>(w.scrd[tr[r]])[cc + sh[r]];
+                val[r] = global_ptr<T>(w.sval[tr[r]])[cc + sh[r]];
+            }
+        }
+    #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int c = r * kThreads + tid;
-            const int cc = c < last ? c : last;
-            col[r] = global_ptr<int32_t>(w.scrd[tr[r]])[cc + sh[r]];
-            val[r] = global_ptr<T>(w.sval[tr[r]])[cc + sh[r]];
+            const int slot = c < n ? c + tr[r] + 1 : kDummy;
+            if constexpr (D == 1) keys[slot] = (KeyT)(uint32_t)col[r];
+            else if constexpr (D == 2) keys[slot] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
+            else keys[slot] = Key3{((uint64_t)row[r] << 32) | (uint64_t)mid[r], (uint64_t)(uint32_t)col[r]};
+            w.vals[slot] = val[r];
         }
+        if (tid < K) keys[w.soff[tid + 1] + tid + 1] = kSentinel;
+        if (tid == K) keys[0] = kSentinel;
     }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int c = r * kThreads + tid;
-        const int slot = c < n ? c + tr[r] + 1 : kDummy;
-        if constexpr (D == 1) keys[slot] = (KeyT)(uint32_t)col[r];
-        else if constexpr (D == 2) keys[slot] = (KeyT)(((uint64_t)row[r] << 32) | (uint32_t)col[r]);
-        else keys[slot] = Key3{((uint64_t)row[r] << 32) | (uint64_t)mid[r], (uint64_t)(uint32_t)col[r]};
-        w.vals[slot] = val[r];
-    }
-    if (tid < K) keys[w.soff[tid + 1] + tid + 1] = kSentinel;
-    if (tid == K) keys[0] = kSentinel;
     bool cont = false;                     // the partition starts inside a row (fibre) whose head is elsewhere
     bool cont_slice = false;               // third-order tensors: ... inside a slice whose head is elsewhere
     if (D == 2 && !kCoo) cont = row_continues<FMT>(ops, coord, posn, p);
