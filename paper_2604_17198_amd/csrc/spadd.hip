@@ -109,7 +109,13 @@ template <typename KeyT, typename T> struct Shape {
 // anybody (a word) or after one such wait (a total).
 //   word:  bit 31 published, bits 14..27 rows, bits 0..13 nnz
 //   total: bit 63 published, bits 31..61 rows, bits 0..30 nnz
-constexpr int kChunk = 512;           // workgroups per chunk
+// Workgroups per chunk.  Vectors: a large chunk, so that few totals are read (their workgroups run
+// nearly in step and a total is there early).  Matrices and tensors: a small one; their partitions
+// take unequal time, the waiting wavefronts poll the words of their chunk, and hundreds of them on
+// the same 2 KB of words measured a sixth slower than on 256 bytes each.
+constexpr int kChunkVector = 512, kChunkOther = 64;
+constexpr int chunk_size(int fmt) { return fmt == SPADD_VECTOR ? kChunkVector : kChunkOther; }
+constexpr int word_loads(int chunk) { return (chunk + NACHO_WAVE - 1) / NACHO_WAVE; }   // words of a chunk a lane reads
 constexpr int kSpinLimit = 1 << 14;   // polls (each a sleep + one round trip to memory: tens of milliseconds in all)
 constexpr unsigned kWordValid = 0x80000000u;
 constexpr unsigned long long kTotalValid = 1ull << 63;
@@ -275,57 +281,70 @@ __device__ inline int run_lower_bound(const KeyT *keys, int s, int n, int bits, 
 // summed over the wavefront, once every one of them is published.  `early` holds the words as they were
 // when the wavefront asked for them ahead of time (kUseEarly), else the first round loads them too.
 // Returns false when the wavefront gives up waiting.
-template <bool kUseEarly>
-__device__ inline bool sum_words(const unsigned int *words, int64_t c0, int m, const unsigned (&early)[kChunk / NACHO_WAVE],
+template <bool kUseEarly, int kWordLoads>
+__device__ inline bool sum_words(const unsigned int *words, int64_t c0, int m, const unsigned (&early)[kWordLoads],
                                  int lane, long long &lo14, long long &hi14)
 {
-    int spins = 0;
-    for (bool first = true;; first = false) {
-        unsigned v[kChunk / NACHO_WAVE];
+    // (a word that has been seen published is not read again: a waiting wavefront only polls the words
+    // it still misses -- hundreds of waiting workgroups re-reading whole chunks would load the fabric
+    // that the publishing stores travel on)
+    unsigned v[kWordLoads];
+#pragma unroll
+    for (int i = 0; i < kWordLoads; ++i) {
+        const int j = i * NACHO_WAVE + lane;
+        const bool mine = i * NACHO_WAVE < m && j < m;
+        v[i] = mine ? 0u : kWordValid;
+        if (kUseEarly && mine) v[i] = early[i];
+    }
+    for (int spins = 0;; ++spins) {
         bool missing = false;
 #pragma unroll
-        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
-            const int j = i * NACHO_WAVE + lane;
-            v[i] = (first && kUseEarly) ? early[i] : kWordValid;
-            if (!(first && kUseEarly) && i * NACHO_WAVE < m && j < m)
-                v[i] = __hip_atomic_load(&words[c0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        int l_lo = 0, l_hi = 0;
-#pragma unroll
-        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+        for (int i = 0; i < kWordLoads; ++i) {
+            if (i * NACHO_WAVE < m && !(v[i] & kWordValid))
+                v[i] = __hip_atomic_load(&words[c0 + i * NACHO_WAVE + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             missing = missing || !(v[i] & kWordValid);
-            l_lo += (int)(v[i] & 0x3fffu);
-            l_hi += (int)((v[i] >> 14) & 0x3fffu);
         }
-        if (__ballot(missing)) {                   // a predecessor has not published yet
-            if (++spins > kSpinLimit) return false;
-            __builtin_amdgcn_s_sleep(16);
-            continue;
-        }
-        lo14 = wave_sum<int>(l_lo);
-        hi14 = wave_sum<int>(l_hi);
-        return true;
+        if (__ballot(missing) == 0ull) break;
+        if (spins > kSpinLimit) return false;      // a predecessor has not published yet
+        __builtin_amdgcn_s_sleep(16);
     }
+    int l_lo = 0, l_hi = 0;
+#pragma unroll
+    for (int i = 0; i < kWordLoads; ++i) {
+        l_lo += (int)(v[i] & 0x3fffu);
+        l_hi += (int)((v[i] >> 14) & 0x3fffu);
+    }
+    lo14 = wave_sum<int>(l_lo);
+    hi14 = wave_sum<int>(l_hi);
+    return true;
 }
 
 // Second level: the two 31-bit fields of the totals of chunks 0 .. chunk - 1, summed, once published.
-__device__ inline bool sum_totals(const unsigned long long *totals, int64_t chunk, int lane, long long &lo31,
-                                  long long &hi31)
+template <int kChunk>
+__device__ inline bool sum_totals(const unsigned long long *totals, const unsigned int *words, int64_t chunk, int lane,
+                                  long long &lo31, long long &hi31)
 {
-    int spins = 0;
+    // A total that its chunk's last workgroup has not published yet (that workgroup first has to get to
+    // its own prefix sum) is not waited for: the words of that chunk are summed here -- they may all be
+    // there long before, published early.
     long long c_lo = 0, c_hi = 0;
-    for (int64_t first = 0; first < chunk; ) {
+    const unsigned none[word_loads(kChunk)] = {};
+    for (int64_t first = 0; first < chunk; first += NACHO_WAVE) {
         const int64_t j = first + lane;
         unsigned long long s = kTotalValid;
         if (j < chunk) s = __hip_atomic_load(&totals[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (__ballot(!(s & kTotalValid))) {
-            if (++spins > kSpinLimit) return false;
-            __builtin_amdgcn_s_sleep(16);
-            continue;
+        const bool there = (s & kTotalValid) != 0;
+        c_lo += wave_sum<long long>(there ? (long long)(s & 0x7fffffffull) : 0ll);
+        c_hi += wave_sum<long long>(there ? (long long)((s >> 31) & 0x7fffffffull) : 0ll);
+        unsigned long long missing = __ballot(!there);
+        while (missing) {                          // (uniform)
+            const int64_t jm = first + (__ffsll((long long)missing) - 1);
+            missing &= missing - 1;
+            long long l = 0, h = 0;
+            if (!sum_words<false, word_loads(kChunk)>(words, jm * kChunk, kChunk, none, lane, l, h)) return false;
+            c_lo += l;
+            c_hi += h;
         }
-        c_lo += wave_sum<long long>((long long)(s & 0x7fffffffull));
-        c_hi += wave_sum<long long>((long long)((s >> 31) & 0x7fffffffull));
-        first += NACHO_WAVE;
     }
     lo31 = c_lo;
     hi31 = c_hi;
@@ -354,6 +373,7 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     typedef typename KeyOf<FMT>::type KeyT;
     typedef Shape<KeyT, T> S;
     constexpr int D = FMT == SPADD_VECTOR ? 1 : (FMT == SPADD_CSF3 ? 3 : 2);
+    constexpr int kChunk = chunk_size(FMT), kWordLoads = word_loads(kChunk);
     constexpr bool kCsf = FMT == SPADD_CSF3;   // third-order tensors: three compressed levels
     constexpr bool kCoo = FMT == SPADD_COO;    // coordinate lists: the row of an entry is stored with it
     constexpr int R = S::kIpt;
@@ -747,13 +767,13 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // place m = j * kThreads + tid; block b = m / 64 = j * kWaves + wave
     // Wavefront 0 asks for the counts of the workgroups before this one in its chunk already
     // now: they were published long ago as a rule, and the answer travels during the assembly.
-    unsigned early[kChunk / NACHO_WAVE];
+    unsigned early[kWordLoads];
     {
         const unsigned int *words = reinterpret_cast<const unsigned int *>(tile_state + n_chunks);
         const int64_t c0 = (p / kChunk) * kChunk;
         const int m = (int)(p - c0);
 #pragma unroll
-        for (int i = 0; i < kChunk / NACHO_WAVE; ++i) {
+        for (int i = 0; i < kWordLoads; ++i) {
             const int j = i * NACHO_WAVE + lane;
             early[i] = kWordValid;
             if (wave == 0 && i * NACHO_WAVE < m && j < m)
@@ -871,8 +891,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         long long b_rows = 0, b_nnz = 0, b_slices = 0, unused = 0;
         const int64_t chunk = p / kChunk, c0 = chunk * kChunk;
         // words of the workgroups before this one in its chunk, all loads in flight together
-        bool ok = sum_words<true>(words, c0, (int)(p - c0), early, lane, b_nnz, b_rows);
-        if (kCsf && ok) ok = sum_words<false>(words2, c0, (int)(p - c0), early, lane, b_slices, unused);
+        bool ok = sum_words<true, kWordLoads>(words, c0, (int)(p - c0), early, lane, b_nnz, b_rows);
+        if (kCsf && ok) ok = sum_words<false, kWordLoads>(words2, c0, (int)(p - c0), early, lane, b_slices, unused);
         if (ok && (p == c0 + kChunk - 1 || p == P - 1) && lane == 0) {
             __hip_atomic_store(&totals[chunk], kTotalValid | pack_counts(b_rows + t_rows, b_nnz + t_nnz),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -883,8 +903,8 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
         if (ok && chunk > 0) {
             // totals of the chunks before this one
             long long c_nnz = 0, c_rows = 0, c_slices = 0;
-            ok = sum_totals(totals, chunk, lane, c_nnz, c_rows);
-            if (kCsf && ok) ok = sum_totals(totals2, chunk, lane, c_slices, unused);
+            ok = sum_totals<kChunk>(totals, words, chunk, lane, c_nnz, c_rows);
+            if (kCsf && ok) ok = sum_totals<kChunk>(totals2, words2, chunk, lane, c_slices, unused);
             b_nnz += c_nnz;
             b_rows += c_rows;
             b_slices += c_slices;
@@ -1028,14 +1048,14 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     wave_end(wlog, (long long)p * kWaves + wave, stamp, logged_items, logged_rows);
 }
 
-int64_t chunks_of(int64_t P) { return (P + kChunk - 1) / kChunk; }
+int64_t chunks_of(int64_t P, int chunk) { return (P + chunk - 1) / chunk; }
 
 template <int FMT, typename T, int K, bool kMul, bool kMapped>
 hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const int32_t *coord,
                     const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
     hipLaunchKernelGGL((spadd_kernel<FMT, T, K, kMul, kMapped>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
-                       P, chunks_of(P), coord, posn, tile_state, out, nacho_host::wave_log());
+                       P, chunks_of(P, chunk_size(FMT)), coord, posn, tile_state, out, nacho_host::wave_log());
     return hipGetLastError();
 }
 
@@ -1067,8 +1087,8 @@ int spadd_capacity(int fmt, int dtype)
 }
 
 // 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup -- twice (third-order
-// tensors count slices in the second set)
-int64_t spadd_state_words(int64_t P) { return 2 * (chunks_of(P) + (P + 1) / 2); }
+// tensors count slices in the second set); sized for the smaller chunk, which covers both
+int64_t spadd_state_words(int64_t P) { return 2 * (chunks_of(P, kChunkOther) + (P + 1) / 2); }
 
 hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,
                         int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
