@@ -210,6 +210,32 @@ __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, in
     return r;
 }
 
+// The value lane `from` (a constant) holds, through a scalar register.
+__device__ inline int lane_value(int x, int from) { return __builtin_amdgcn_readlane(x, from); }
+__device__ inline long long lane_value(long long x, int from)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)x, from);
+    const int hi = __builtin_amdgcn_readlane((int)(x >> 32), from);
+    return ((long long)hi << 32) | (long long)lo;
+}
+
+// How many of the wavefront's 64 values xs -- ascending with the lane, lanes past the valid ones hold
+// the largest value there is -- are smaller than this lane's key.  An 8-ary search: the values of
+// lanes 7, 15, .. 55 pick the group of eight lanes, seven shuffles inside the group that do not depend
+// on each other count the rest (a binary search is a chain of seven dependent shuffles, and these
+// rank searches were half of a round's time).
+template <typename CoordT>
+__device__ inline int rank_among(CoordT xs, CoordT key)
+{
+    int group = 0;
+#pragma unroll
+    for (int g = 0; g < 7; ++g) group += lane_value(xs, 8 * g + 7) < key ? 1 : 0;
+    int n = group * 8 + (lane_value(xs, NACHO_WAVE - 1) < key ? 1 : 0);
+#pragma unroll
+    for (int i = 0; i < 7; ++i) n += __shfl(xs, group * 8 + i, NACHO_WAVE) < key ? 1 : 0;
+    return n;
+}
+
 // Search windows of one compressed level: for operand t the boundary's position
 // lies in [l, h]; cl/ch are the costs of the entries before l / before h,
 // relative to the segment start (base = cost offset of the segment start).
@@ -265,8 +291,10 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
     r.x = 0;
     r.c = 0;
     // position of sample j of a window (l, w): every entry when w <= 64, else 64 evenly spaced ones
+    // (j * w / 64 with w = 128 q + r is 2 j q + j r / 64: two 24-bit products, no 64-bit one)
     auto sample_pos = [](int lo, int w, int j) -> int {
-        return lo + (w <= NACHO_WAVE ? j : (int)(((int64_t)j * w) >> 6));
+        const int spread = 2 * __mul24(j, w >> 7) + (__mul24(j, w & 127) >> 6);
+        return lo + (w <= NACHO_WAVE ? j : spread);
     };
     int prev_total = INT32_MAX;
     for (;;) {
@@ -344,54 +372,14 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
                 vplus = cand < vplus ? cand : vplus;     // smallest sample after the last boundary
             }
         };
-        // rank of every sample of t among the samples of u: K*(K-1) binary searches over the lanes
-        if constexpr (K <= 3) {
-            // few operands: all searches advance in lockstep so that their shuffles overlap
-            int lo[K][K], hi[K][K];
+        // rank of every sample of t among the samples of u (lanes past mt[u] hold kNone, which is
+        // smaller than no key: a rank never exceeds mt[u]); one operand at a time, ranks and bounds
 #pragma unroll
-            for (int t = 0; t < K; ++t)
+        for (int t = 0; t < K; ++t) {
+            int lo_t[K];
 #pragma unroll
-                for (int u = 0; u < K; ++u) { lo[t][u] = 0; hi[t][u] = mt[u]; }
-#pragma unroll
-            for (int it = 0; it < 7; ++it) {
-#pragma unroll
-                for (int t = 0; t < K; ++t)
-#pragma unroll
-                    for (int u = 0; u < K; ++u) {
-                        if (u == t) continue;
-                        const int mid = (lo[t][u] + hi[t][u]) >> 1;
-                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
-                        const bool go = lo[t][u] < hi[t][u];
-                        const bool right = xs < v[t];
-                        lo[t][u] = (go && right) ? mid + 1 : lo[t][u];
-                        hi[t][u] = (go && !right) ? mid : hi[t][u];
-                    }
-            }
-#pragma unroll
-            for (int t = 0; t < K; ++t) bounds_of(t, lo[t]);
-        } else {
-            // many operands: one operand at a time, searches and bounds (the state of all
-            // K * K searches at once does not fit the registers)
-#pragma unroll
-            for (int t = 0; t < K; ++t) {
-                int lo_t[K], hi[K];
-#pragma unroll
-                for (int u = 0; u < K; ++u) { lo_t[u] = 0; hi[u] = mt[u]; }
-#pragma unroll
-                for (int it = 0; it < 7; ++it) {
-#pragma unroll
-                    for (int u = 0; u < K; ++u) {
-                        if (u == t) continue;
-                        const int mid = (lo_t[u] + hi[u]) >> 1;
-                        const CoordT xs = __shfl(v[u], mid & (NACHO_WAVE - 1), NACHO_WAVE);
-                        const bool go = lo_t[u] < hi[u];
-                        const bool right = xs < v[t];
-                        lo_t[u] = (go && right) ? mid + 1 : lo_t[u];
-                        hi[u] = (go && !right) ? mid : hi[u];
-                    }
-                }
-                bounds_of(t, lo_t);
-            }
+            for (int u = 0; u < K; ++u) lo_t[u] = u == t ? 0 : rank_among<CoordT>(v[u], v[t]);
+            bounds_of(t, lo_t);
         }
 
 #pragma unroll
