@@ -91,6 +91,15 @@ struct PairCoords {
     __device__ static int64_t extent(const DevOperands &ops, int) { return ops.lvl[0][0].extent << 32; }
 };
 
+// The value lane `from` holds (`from` the same in every lane), through a scalar register.
+__device__ inline int lane_value(int x, int from) { return __builtin_amdgcn_readlane(x, from); }
+__device__ inline long long lane_value(long long x, int from)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)x, from);
+    const int hi = __builtin_amdgcn_readlane((int)(x >> 32), from);
+    return ((long long)hi << 32) | (long long)lo;
+}
+
 // Least position in [lo, hi) of operand t whose coordinate is >= x; hi if there is none.
 template <class Acc>
 __device__ inline int lower_bound_level(const DevOperands &ops, int t, int m, int shift, int lo, int hi, int64_t x)
@@ -136,10 +145,10 @@ __device__ __forceinline__ LevelResult dense_search(const DevOperands &ops, int 
         const unsigned long long ok = __ballot(c <= R);   // a prefix of the lanes (monotone cost)
         const int n = __popcll(ok);
         if (n > 0) {
-            low = __shfl((long long)x, n - 1, NACHO_WAVE);
-            c_low = __shfl((long long)c, n - 1, NACHO_WAVE);
+            low = lane_value((long long)x, n - 1);
+            c_low = lane_value((long long)c, n - 1);
         }
-        if (n < NACHO_WAVE) high = __shfl((long long)x, n, NACHO_WAVE) - 1;
+        if (n < NACHO_WAVE) high = lane_value((long long)x, n) - 1;
     }
 #pragma unroll
     for (int t = 0; t < K; ++t) {
@@ -186,15 +195,15 @@ __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, in
         const unsigned long long ok = __ballot(c <= R);
         const int n = __popcll(ok);
         if (n > 0) {
-            low = __shfl((long long)x, n - 1, NACHO_WAVE);
-            c_low = __shfl((long long)c, n - 1, NACHO_WAVE);
+            low = lane_value((long long)x, n - 1);
+            c_low = lane_value((long long)c, n - 1);
         }
-        if (n < NACHO_WAVE) high = __shfl((long long)x, n, NACHO_WAVE) - 1;
+        if (n < NACHO_WAVE) high = lane_value((long long)x, n) - 1;
 #pragma unroll
         for (int t = 0; t < K; ++t) {
             if (t >= k) break;
-            const int lo_new = __shfl(ip[t], n > 0 ? n - 1 : 0, NACHO_WAVE);
-            const int hi_new = __shfl(ip[t], n < NACHO_WAVE ? n : NACHO_WAVE - 1, NACHO_WAVE);
+            const int lo_new = lane_value(ip[t], n > 0 ? n - 1 : 0);
+            const int hi_new = lane_value(ip[t], n < NACHO_WAVE ? n : NACHO_WAVE - 1);
             if (n > 0) wl[t] = lo_new;
             if (n < NACHO_WAVE) wh[t] = hi_new;
         }
@@ -208,15 +217,6 @@ __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, in
     r.x = low;
     r.c = c_low;
     return r;
-}
-
-// The value lane `from` (a constant) holds, through a scalar register.
-__device__ inline int lane_value(int x, int from) { return __builtin_amdgcn_readlane(x, from); }
-__device__ inline long long lane_value(long long x, int from)
-{
-    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)x, from);
-    const int hi = __builtin_amdgcn_readlane((int)(x >> 32), from);
-    return ((long long)hi << 32) | (long long)lo;
 }
 
 // How many of the wavefront's 64 values xs -- ascending with the lane, lanes past the valid ones hold
@@ -364,11 +364,11 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             const int n_le = __popcll(__ballot(valid && ghi <= R_lo));   // lanes 0 .. n_le - 1
             const int n_in = __popcll(__ballot(valid && glo <= R_hi));   // lanes n_in .. mt - 1 are after
             if (n_le > 0) {
-                const CoordT cand = __shfl(v[t], n_le - 1, NACHO_WAVE);
+                const CoordT cand = lane_value(v[t], n_le - 1);
                 vminus = cand > vminus ? cand : vminus;  // largest sample not after the first boundary
             }
             if (n_in < mt[t]) {
-                const CoordT cand = __shfl(v[t], n_in, NACHO_WAVE);
+                const CoordT cand = lane_value(v[t], n_in);
                 vplus = cand < vplus ? cand : vplus;     // smallest sample after the last boundary
             }
         };
@@ -394,8 +394,8 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
                 nl = eq ? sc : sp;
                 if (kLast) ncl = nl - base[u];
                 else {
-                    const int e = __shfl(cb[u], c & (NACHO_WAVE - 1), NACHO_WAVE);
-                    const int a = __shfl(ca[u], (c - 1) & (NACHO_WAVE - 1), NACHO_WAVE);
+                    const int e = lane_value(cb[u], c & (NACHO_WAVE - 1));
+                    const int a = lane_value(ca[u], (c - 1) & (NACHO_WAVE - 1));
                     ncl = eq ? e : (c == 0 ? cl[u] : a);
                 }
             }
@@ -404,7 +404,7 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
                 nh = c == mt[u] ? h[u] : sample_pos(l[u], w[u], c);
                 if (kLast) nch = nh - base[u];
                 else {
-                    const int e = __shfl(cb[u], c & (NACHO_WAVE - 1), NACHO_WAVE);
+                    const int e = lane_value(cb[u], c & (NACHO_WAVE - 1));
                     nch = c == mt[u] ? ch[u] : e;
                 }
             }
