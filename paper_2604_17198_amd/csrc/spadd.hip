@@ -505,6 +505,27 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
             }
         }
 
+        // Matrices: the first 512 rows of every run (as a rule all of them) are asked for together with
+        // the entries, one round trip to memory instead of two.
+        constexpr bool kRowsAhead = D == 2 && !kCoo && K <= 4;      // (with eight runs the registers for it cost a workgroup per CU)
+        int ahead_a[kRowsAhead ? K : 1], ahead_b[kRowsAhead ? K : 1], ahead_row[kRowsAhead ? K : 1];
+        if constexpr (kRowsAhead) {
+    #pragma unroll
+            for (int t = 0; t < K; ++t) {
+                ahead_a[t] = ahead_b[t] = ahead_row[t] = 0;
+                if (t >= k) continue;
+                const int i = posn[(p * k + t) * D] + tid;
+                int i_hi = posn[((p + 1) * k + t) * D] + 1;
+                const int i_max = (FMT == SPADD_CSR) ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][0].count;
+                if (i_hi > i_max) i_hi = i_max;
+                if (i < i_hi && off[t + 1] > off[t]) {
+                    ahead_a[t] = ops.lvl[t][1].pos[i];
+                    ahead_b[t] = ops.lvl[t][1].pos[i + 1];
+                    ahead_row[t] = (FMT == SPADD_CSR) ? i : ops.lvl[t][0].crd[i];
+                }
+            }
+        }
+
         if constexpr (D >= 2 && !kCoo) {
             // Segments of an upper level overlapping [q_lo, q_hi) of every run: mark each segment's
             // first entry (word of the entry in marks) with a value, then hand every entry the latest
@@ -528,7 +549,12 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
                     int i_hi = posn[((p + 1) * k + t) * D + lv] + 1;
                     const int i_max = (FMT == SPADD_CSR) ? (int)ops.lvl[t][0].extent : (int)ops.lvl[t][lv].count;
                     if (i_hi > i_max) i_hi = i_max;
-                    for (int i0 = i_lo + tid; i0 < i_hi; i0 += kThreads * 4) {
+                    if constexpr (kRowsAhead) {
+                        // (a thread without a row holds a = b = 0: no mark)
+                        const int s = ahead_a[t] > ql ? ahead_a[t] : ql;
+                        if (ahead_b[t] > s && s < qh) w.marks[off[t] + s - ql] = (uint32_t)(ahead_row[t] + 1);
+                    }
+                    for (int i0 = i_lo + tid + (kRowsAhead ? kThreads : 0); i0 < i_hi; i0 += kThreads * 4) {
                         int a[4], b[4], rw[4];
     #pragma unroll
                         for (int u = 0; u < 4; ++u) {
