@@ -732,7 +732,9 @@ struct QueryRule {
     __device__ int64_t first_reaching(int64_t y) const
     {
         int64_t b;
-        if (grain_u > 0 && grain_u < 0x7fffffffLL && y < 0x7fffffffLL)
+        if (grain_u > 0 && (grain_u & (grain_u - 1)) == 0)           // a power of two (the built-in grains are)
+            b = (y + grain_u - 1) >> (63 - __clzll((long long)grain_u));
+        else if (grain_u > 0 && grain_u < 0x7fffffffLL && y < 0x7fffffffLL)
             b = ((uint32_t)y + (uint32_t)grain_u - 1u) / (uint32_t)grain_u;
         else if (grain_u > 0) b = (y + grain_u - 1) / grain_u;
         else if (total <= 0) b = 0;

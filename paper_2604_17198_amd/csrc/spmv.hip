@@ -220,6 +220,9 @@ spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
     // a run that reaches the last lane may go on in the next wavefronts
     const int r_last = __shfl(r, NACHO_WAVE - 1, NACHO_WAVE);
     const bool last_owned = __shfl((int)owned, NACHO_WAVE - 1, NACHO_WAVE) != 0;
+    // (the writer's element of y is requested now, beside the loads of the tail)
+    const bool writer = r >= 0 && owned && lane == end;
+    const T y_old = writer ? y[r] : T(0);
     T tail = T(0);
     if (r_last >= 0 && last_owned && grain > 0) {
         // fixed-grain partitions: the carries of row r come from the partitions that
@@ -269,7 +272,7 @@ spmv_fixup_kernel(T *__restrict__ y, int P, const T *__restrict__ carry_val,
         walk(std::integral_constant<int, 2>());
         while (more) walk(std::integral_constant<int, 16>());
     }
-    if (r >= 0 && owned && lane == end) y[r] += v + (end == NACHO_WAVE - 1 ? tail : T(0));
+    if (writer) y[r] = y_old + (v + (end == NACHO_WAVE - 1 ? tail : T(0)));
 }
 
 constexpr int kGrainF64 = 512, kRowsF64 = 512;
