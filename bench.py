@@ -333,6 +333,15 @@ def bench_others(steps, warmup, only=None, ceilings=None):
                table=lambda: nb.workspace_parts(nb.OP_SPADD, ops, nb.F32, ws), main_kernel="spadd_merge",
                waves=P_add * nb.merge_wavefronts())
         if c == 3:
+            # the same sum with the boundary search fused into the merge kernel (no partition kernel)
+            ff = lambda: nb.nacho_spadd_fused(ops, out, ws=ws)
+            ff()
+            torch.cuda.synchronize()
+            ms_f, _ = _time_steps(ff, steps, warmup)
+            res["C3"]["fused_search_variant"] = {
+                "what": "nacho_spadd_fused: every workgroup of the merge kernel searches its own two boundaries",
+                "ms_per_step": ms_f, "kernel_ms": _kernel_ms(ff, 5),
+                "same_output_count": int(out.counts.cpu().numpy()[1]) == n_out}
             fm = lambda: nb.nacho_spmul_k(ops, out, ws=ws)
             fm()
             torch.cuda.synchronize()

@@ -280,6 +280,23 @@ int32_t nacho_spmv_fused(const nacho_tensor *A, const void *x, void *y, int32_t 
                          void *hip_stream);
 
 /*
+ * nacho_spadd_k on sparse vectors without a partition pass (the fused
+ * search-in-execute form of the merge path; the paper's partitions "computed in
+ * parallel" with the kernel they balance, Sections 1 and 2.1): every workgroup
+ * of the merge kernel searches its own two boundaries with Algorithm 1
+ * (Section 3.2; wavefront 0 the lower one, wavefront 1 the upper one, equal-share
+ * queries Q_p = floor(p Q* / P)) and stores them in the partition table of the
+ * workspace, which nacho_workspace_parts returns as after nacho_spadd_k; two
+ * small fill kernels clear the prefix-sum state and the status word first.  Same
+ * partitions, same result arrays, counts and status as nacho_spadd_k; other
+ * formats: NACHO_ERR_UNSUPPORTED.  A measured variant, not the default: a
+ * boundary search is as long as a workgroup's whole merge, and here every
+ * workgroup waits for two of them.  Workspace: nacho_workspace_bytes(NACHO_OP_SPADD, ...).
+ */
+int32_t nacho_spadd_fused(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P, const nacho_sparse_out *out,
+                          void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * nacho_spmv for callers that cannot allocate device memory or pass a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc).  Same operation, arguments, results and status codes as nacho_spmv,

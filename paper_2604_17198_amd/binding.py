@@ -28,7 +28,7 @@ EXPORTS = [
     "nacho_validate", "nacho_profile_enable", "nacho_profile_read", "nacho_spmv_static",
     "nacho_static_scratch_bytes", "nacho_instrument", "nacho_instrument_record_bytes",
     "nacho_probe", "nacho_merge_wavefronts", "nacho_rowcost_partitions", "nacho_partition_rowcost",
-    "nacho_spmv_rowcost", "nacho_partition_csr64", "nacho_spmv_fused",
+    "nacho_spmv_rowcost", "nacho_partition_csr64", "nacho_spmv_fused", "nacho_spadd_fused",
 ]
 
 
@@ -99,6 +99,7 @@ def lib():
         L.nacho_spadd_k.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
         L.nacho_spmul_k.argtypes = L.nacho_spadd_k.argtypes
+        L.nacho_spadd_fused.argtypes = L.nacho_spadd_k.argtypes
         L.nacho_workspace_parts.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nacho_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
@@ -415,6 +416,19 @@ def nacho_spadd_k(ops, out: SparseOut, P=0, ws=None):
     arr = _pack(ops)
     _check(lib().nacho_spadd_k(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
                                ws.numel(), _stream()), "nacho_spadd_k")
+    return out
+
+
+def nacho_spadd_fused(ops, out: SparseOut, P=0, ws=None):
+    """nacho_spadd_k on sparse vectors without a partition pass: the workgroups of the merge kernel search
+    their own boundaries.  Enqueues only."""
+    dt = dtype_code(ops[0].val.dtype)
+    dev = ops[0].val.device
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPADD, ops, dt, 0, P), dev)
+    arr = _pack(ops)
+    _check(lib().nacho_spadd_fused(C.cast(arr, C.c_void_p), len(ops), dt, P, C.byref(out.c), _ptr(ws),
+                                   ws.numel(), _stream()), "nacho_spadd_fused")
     return out
 
 

@@ -834,6 +834,45 @@ int32_t nacho_spadd_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t
     return sparse_combine(false, ops, k, dtype, P, out, ws, ws_bytes, hip_stream);
 }
 
+int32_t nacho_spadd_fused(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P, const nacho_sparse_out *out,
+                          void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!out || P < 0) return NACHO_ERR_INVALID_ARG;
+    if (dtype != NACHO_F32 && dtype != NACHO_F64) return NACHO_ERR_INVALID_ARG;
+    DevOperands dev;
+    int64_t total = 0;
+    Format fmt;
+    int32_t rc = check_operands(ops, k, true, &dev, &total, &fmt);
+    if (rc != NACHO_OK) return rc;
+    if (fmt != FMT_VECTOR) return NACHO_ERR_UNSUPPORTED;
+    SpaddValues vals;
+    std::memset(&vals, 0, sizeof(vals));
+    for (int t = 0; t < k; ++t) {
+        if (ops[t].lvl[0].count > 0 && !ops[t].val) return NACHO_ERR_INVALID_ARG;
+        vals.v[t] = ops[t].val;
+    }
+    if (!out->counts || !out->status || !out->pos1 || out->cap_nnz < 0) return NACHO_ERR_INVALID_ARG;
+    if (out->cap_nnz > 0 && (!out->crd1 || !out->val)) return NACHO_ERR_INVALID_ARG;
+    const int64_t Pe = fused_partitions(NACHO_OP_SPADD, fmt, dtype, k, total, P);
+    SpaddWs w = carve_spadd(ws, Pe, k, dev.d);
+    if (!ws || ws_bytes < w.bytes) return NACHO_ERR_WORKSPACE;
+    SpaddOut o;
+    std::memset(&o, 0, sizeof(o));
+    o.pos1 = out->pos1; o.crd1 = out->crd1; o.val = out->val;
+    o.cap_nnz = out->cap_nnz; o.counts = out->counts; o.status = out->status;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    profile_begin(s);
+    // no partition kernel: the prefix-sum state and the status word are cleared by fill kernels
+    if (launch_zero_vector(NACHO_F64, w.tile_state, spadd_state_words(Pe), s) != hipSuccess) return NACHO_ERR_HIP;
+    if (launch_zero_vector(NACHO_F32, o.status, 1, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("clear_state");
+    SpaddSearch search;
+    search.coord = w.parts.coord; search.posn = w.parts.posn; search.cost = w.parts.cost; search.total = total;
+    if (launch_spadd_vector_search(dtype, dev, vals, Pe, search, w.tile_state, o, s) != hipSuccess) return NACHO_ERR_HIP;
+    profile_mark("spadd_merge_fused");
+    return NACHO_OK;
+}
+
 int32_t nacho_spmul_k(const nacho_tensor *ops, int32_t k, int32_t dtype, int64_t P,
                       const nacho_sparse_out *out, void *ws, size_t ws_bytes, void *hip_stream)
 {

@@ -73,6 +73,18 @@ int spadd_resident();
 int spadd_wavefronts();
 // 64-bit words of prefix-sum state a call with P partitions uses.
 int64_t spadd_state_words(int64_t P);
+// The partition table a merge kernel that searches its own boundaries fills, and the total cost Q*.
+struct SpaddSearch {
+    int32_t *coord, *posn;
+    int64_t *cost;
+    int64_t total;
+};
+// Sparse vectors, union: as launch_spadd, but without a partition kernel before it -- every workgroup
+// searches its two boundaries (equal-share queries over P partitions) and stores them in the table.
+// The prefix-sum state and the status word must be zero when the kernel starts.
+hipError_t launch_spadd_vector_search(int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
+                                      const SpaddSearch &search, unsigned long long *tile_state, const SpaddOut &out,
+                                      hipStream_t s);
 // Count, prefix sum and fill in one kernel, one workgroup per partition.  `multiply`: the k-way
 // intersection with products instead of the union with sums (vectors and CSR only).
 hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,

@@ -50,6 +50,7 @@
 // same; a wavefront that gives up reports NACHO_ERR_HIP and writes nothing.)
 #include "common.hpp"
 #include "kernels.hpp"
+#include "search.hpp"
 
 namespace nacho {
 
@@ -357,12 +358,16 @@ __device__ inline bool sum_totals(const unsigned long long *totals, const unsign
 // kMapped: the operands are remapped ones (Section 3.3): CSR over the rows all
 // operands store, positions counted over those rows only; the entries of row
 // i' of operand t are read from start[t][i'] on.
-template <int FMT, typename T, int K, bool kMul, bool kMapped>
+// kSearch (sparse vectors): there is no partition kernel before this one; wavefronts 0 and 1 of the
+// workgroup search its two boundaries themselves (Algorithm 1, equal-share queries) and store them in
+// the partition table on the way -- the search fused into the executing kernel.
+template <int FMT, typename T, int K, bool kMul, bool kMapped, bool kSearch = false>
 __global__ void __launch_bounds__(kThreads)
 spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
              const int32_t *__restrict__ coord, const int32_t *__restrict__ posn,
-             unsigned long long *__restrict__ tile_state, SpaddOut out, WaveLog wlog)
+             unsigned long long *__restrict__ tile_state, SpaddOut out, WaveLog wlog, SpaddSearch search)
 {
+    static_assert(!kSearch || (FMT == SPADD_VECTOR && !kMapped), "the fused search is built for sparse vectors");
     const WaveStamp stamp = wave_begin();
     if (kMapped && ops.dyn_plan) {
         // the number of partitions is a result of earlier kernels of the call: the launch is sized for
@@ -394,12 +399,31 @@ spadd_kernel(DevOperands ops, SpaddValues vals, int64_t P, int64_t n_chunks,
     // ---- 1. segments of this partition ----------------------------------
     int q_lo[K], off[K + 1];
     off[0] = 0;
+    if constexpr (kSearch) {
+        __shared__ int own_bounds[2][K];
+        if (wave < 2) {                        // (whole wavefronts)
+            int found[K];
+            search_boundary<K, 0>(ops, 1, P, 0, nullptr, search.total, search.coord, search.posn, search.cost,
+                                  p + wave, found);
+            if (lane == 0) {
 #pragma unroll
-    for (int t = 0; t < K; ++t) {
-        if (t >= k) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
-        q_lo[t] = posn[(p * k + t) * D + (D - 1)];
-        const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
-        off[t + 1] = off[t] + (q_hi - q_lo[t]);
+                for (int t = 0; t < K; ++t) own_bounds[wave][t] = found[t];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
+            q_lo[t] = t < k ? own_bounds[0][t] : 0;
+            off[t + 1] = off[t] + (t < k ? own_bounds[1][t] - q_lo[t] : 0);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
+            if (t >= k) { off[t + 1] = off[t]; q_lo[t] = 0; continue; }
+            q_lo[t] = posn[(p * k + t) * D + (D - 1)];
+            const int q_hi = posn[((p + 1) * k + t) * D + (D - 1)];
+            off[t + 1] = off[t] + (q_hi - q_lo[t]);
+        }
     }
     int n = off[K];                            // <= kCapacity by the host's choice of the partition count
     // Only an operand that violates its preconditions (unsorted or repeated
@@ -1081,8 +1105,29 @@ hipError_t launch_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, 
                     const int32_t *posn, unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
 {
     hipLaunchKernelGGL((spadd_kernel<FMT, T, K, kMul, kMapped>), dim3((unsigned)P), dim3(kThreads), 0, s, ops, vals,
-                       P, chunks_of(P, chunk_size(FMT)), coord, posn, tile_state, out, nacho_host::wave_log());
+                       P, chunks_of(P, chunk_size(FMT)), coord, posn, tile_state, out, nacho_host::wave_log(),
+                       SpaddSearch{});
     return hipGetLastError();
+}
+
+template <typename T, int K>
+hipError_t launch_search_k(const DevOperands &ops, const SpaddValues &vals, int64_t P, const SpaddSearch &search,
+                           unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
+{
+    hipLaunchKernelGGL((spadd_kernel<SPADD_VECTOR, T, K, false, false, true>), dim3((unsigned)P), dim3(kThreads), 0, s,
+                       ops, vals, P, chunks_of(P, chunk_size(SPADD_VECTOR)), search.coord, search.posn, tile_state,
+                       out, nacho_host::wave_log(), search);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_search_one(const DevOperands &ops, const SpaddValues &vals, int64_t P, const SpaddSearch &search,
+                             unsigned long long *tile_state, const SpaddOut &out, hipStream_t s)
+{
+    if (ops.k <= 2) return launch_search_k<T, 2>(ops, vals, P, search, tile_state, out, s);
+    if (ops.k <= 3) return launch_search_k<T, 3>(ops, vals, P, search, tile_state, out, s);
+    if (ops.k <= 4) return launch_search_k<T, 4>(ops, vals, P, search, tile_state, out, s);
+    return launch_search_k<T, 8>(ops, vals, P, search, tile_state, out, s);
 }
 
 // instantiated for up to 2, 3, 4 and 8 operands: the per-entry loops over the runs are unrolled
@@ -1115,6 +1160,14 @@ int spadd_capacity(int fmt, int dtype)
 // 64-bit words of look-up state: one per chunk, then one 32-bit word per workgroup -- twice (third-order
 // tensors count slices in the second set); sized for the smaller chunk, which covers both
 int64_t spadd_state_words(int64_t P) { return 2 * (chunks_of(P, kChunkOther) + (P + 1) / 2); }
+
+hipError_t launch_spadd_vector_search(int dtype, const DevOperands &ops, const SpaddValues &vals, int64_t P,
+                                      const SpaddSearch &search, unsigned long long *tile_state, const SpaddOut &out,
+                                      hipStream_t s)
+{
+    if (dtype == NACHO_F64) return launch_search_one<double>(ops, vals, P, search, tile_state, out, s);
+    return launch_search_one<float>(ops, vals, P, search, tile_state, out, s);
+}
 
 hipError_t launch_spadd(int fmt, int dtype, bool multiply, const DevOperands &ops, const SpaddValues &vals,
                         int64_t P, const int32_t *coord, const int32_t *posn, unsigned long long *tile_state,
