@@ -163,19 +163,26 @@ __device__ __forceinline__ LevelResult tracked_search(const DevOperands &ops, in
 }
 
 // How many of the wavefront's 64 values xs -- ascending with the lane, lanes past the valid ones hold
-// the largest value there is -- are smaller than this lane's key.  An 8-ary search: the values of
-// lanes 7, 15, .. 55 pick the group of eight lanes, seven shuffles inside the group that do not depend
-// on each other count the rest (a binary search is a chain of seven dependent shuffles, and these
-// rank searches were half of a round's time).
+// the largest value there is -- are smaller than this lane's key.  Three levels of a 4-ary search: the
+// values of lanes 15, 31, 47 (through scalar registers) pick sixteen lanes, three shuffles their
+// quarter, three more count inside it; the last lane of a quarter is a pivot that was compared
+// before, but for lane 63.  (A binary search is a chain of seven dependent shuffles and twice the
+// instructions; these rank searches were half of a round's time, and the kernel is bound by the
+// instructions its wavefronts issue.)
 template <typename CoordT>
 __device__ inline int rank_among(CoordT xs, CoordT key)
 {
-    int group = 0;
+    int sixteen = 0;
 #pragma unroll
-    for (int g = 0; g < 7; ++g) group += lane_value(xs, 8 * g + 7) < key ? 1 : 0;
-    int n = group * 8 + (lane_value(xs, NACHO_WAVE - 1) < key ? 1 : 0);
+    for (int g = 0; g < 3; ++g) sixteen += lane_value(xs, 16 * g + 15) < key ? 1 : 0;
+    const int b1 = sixteen * 16;
+    int quarter = 0;
 #pragma unroll
-    for (int i = 0; i < 7; ++i) n += __shfl(xs, group * 8 + i, NACHO_WAVE) < key ? 1 : 0;
+    for (int g = 0; g < 3; ++g) quarter += __shfl(xs, b1 + 4 * g + 3, NACHO_WAVE) < key ? 1 : 0;
+    const int b2 = b1 + quarter * 4;
+    int n = b2 + (lane_value(xs, NACHO_WAVE - 1) < key ? 1 : 0);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) n += __shfl(xs, b2 + i, NACHO_WAVE) < key ? 1 : 0;
     return n;
 }
 
