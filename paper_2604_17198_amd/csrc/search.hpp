@@ -295,18 +295,12 @@ __device__ __forceinline__ LevelResult sampled_search(const DevOperands &ops, in
             for (int u = 0; u < K; ++u) {
                 if (u == t) continue;
                 const int c = lo_t[u];              // u's samples below this coordinate
-                int costA, costB;
-                if (kLast) {
-                    const int posA = c == 0 ? l[u] : sample_pos(l[u], w[u], c - 1) + 1;
-                    const int posB = c == mt[u] ? h[u] : sample_pos(l[u], w[u], c);
-                    costA = posA - base[u];
-                    costB = posB - base[u];
-                } else {
-                    const int a = __shfl(ca[u], (c - 1) & (NACHO_WAVE - 1), NACHO_WAVE);
-                    const int bq = __shfl(cb[u], c & (NACHO_WAVE - 1), NACHO_WAVE);
-                    costA = c == 0 ? cl[u] : a;
-                    costB = c == mt[u] ? ch[u] : bq;
-                }
+                // cost before u's sample c - 1 ... before its sample c: what the lanes c - 1 and c hold
+                // (with positions as costs, the last level, these are the samples' positions)
+                const int a = __shfl(ca[u], (c - 1) & (NACHO_WAVE - 1), NACHO_WAVE);
+                const int bq = __shfl(cb[u], c & (NACHO_WAVE - 1), NACHO_WAVE);
+                const int costA = c == 0 ? cl[u] : a;
+                const int costB = c == mt[u] ? ch[u] : bq;
                 glo += costA;
                 ghi += costB;
             }
