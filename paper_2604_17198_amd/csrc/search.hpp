@@ -443,7 +443,7 @@ __device__ inline int64_t level_total(const DevOperands &ops, int m, const int *
 // kMode: 0 = vectors, CSR, DCSR; 1 = coordinate lists; 2 = three compressed levels (CSF).
 // found[t] (operands of one level only): operand t's position of the boundary, in every lane.
 template <int K, int kMode>
-__device__ __forceinline__ void search_boundary(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
+__device__ inline void search_boundary(const DevOperands &ops, int64_t cost_scale, int64_t P, int64_t grain,
                                                 const int64_t *__restrict__ queries, int64_t total_unscaled,
                                                 int32_t *__restrict__ coord, int32_t *__restrict__ posn,
                                                 int64_t *__restrict__ cost, int64_t b, int (&found)[K])
